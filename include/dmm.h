@@ -1,0 +1,153 @@
+/* dmm.h -- C ABI of the universal one-sided matmul hot path on one MI355X.
+ *
+ * The library computes C = A B for three distributed matrices with arbitrary,
+ * possibly misaligned partitionings and replication factors ("Slicing Is All
+ * You Need", arXiv 2510.08874).  Every virtual rank's tiles live as separate
+ * HBM buffers on the one GPU; a one-sided "get" of a remote tile is a direct
+ * strided read of that buffer.  The path is
+ *
+ *   dmm_plan      host, integer only: Stationary-C op generation by slicing
+ *                 (Algorithm 1 + the replication rule of Section 4.1), then a
+ *                 grouping of the ops by output sub-tile so that every C region
+ *                 is accumulated by one workgroup in ascending k, no atomics;
+ *   dmm_execute   device: one grouped-GEMM launch over all ranks' ops (the
+ *                 "local matrix multiplication" step of Section 4.2), then the
+ *                 replica sum when C is replicated;
+ *   dmm_reduce_replicas   device: reduce_replicas of Table 1 on its own.
+ *
+ * Conventions
+ *   - All matrices and tiles are row-major.  Index intervals are half-open.
+ *   - Host pointers: descriptors, cut arrays, pointer tables, ld tables.
+ *     Device pointers: the tile buffers named *inside* the pointer tables.
+ *   - Tile tables are indexed  rep * (grid_rows * grid_cols) + ti * grid_cols + tj.
+ *   - Every function returns DMM_OK (0) or a negative dmm_status; nothing throws
+ *     across the boundary; on failure output arguments are left untouched.
+ *   - A plan may be used by one thread at a time.
+ */
+#ifndef DMM_H
+#define DMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DMM_OK = 0,
+  DMM_EINVAL = -1, /* null argument, bad cuts (not spanning [0, dim], decreasing), empty grid, bad dtype/flag */
+  DMM_ESHAPE = -2, /* shapes do not form C[m,n] = A[m,k] B[k,n] */
+  DMM_EREPL = -3,  /* replication factor does not divide nranks (Section 2.1: p/c must be an integer),
+                      or the process grid needs more ranks than one replica has */
+  DMM_ENOMEM = -4, /* host or device allocation failed */
+  DMM_EHIP = -5,   /* a HIP call failed; dmm_last_hip_error() holds its code */
+  DMM_ELD = -6     /* a leading dimension is smaller than the tile's width */
+} dmm_status;
+
+/* Element type of the A and B tiles.  C tiles and all partial sums are fp32. */
+typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
+
+/* dmm_execute flags */
+#define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
+
+/* Distributed matrix descriptor (Section 3): shape, partition object, replication
+ * factor.  The partition is a tile grid given by cut points (a uniform tile
+ * shape is cuts[i] = min(i * t, dim); uneven cuts are allowed, and so are empty
+ * tiles) plus a process grid onto which tiles are dealt block-cyclically, row-
+ * major (Section 2.1, ScaLAPACK convention):
+ *     owner(ti, tj, rep) = rep * (nranks / replication)
+ *                        + (ti % proc_rows) * proc_cols + (tj % proc_cols).
+ * The `replication` copies are laid out over consecutive blocks of
+ * nranks / replication ranks; rank r belongs to replica r / (nranks/replication).
+ * Caller-owned; dmm_plan copies what it needs. */
+typedef struct {
+  int64_t rows, cols;           /* global shape */
+  int32_t grid_rows, grid_cols; /* tile grid: grid_shape() of Table 1 */
+  const int64_t *row_cuts;      /* host, grid_rows + 1 entries, [0] = 0, [last] = rows, non-decreasing */
+  const int64_t *col_cuts;      /* host, grid_cols + 1 entries */
+  int32_t proc_rows, proc_cols; /* process grid inside one replica */
+  int32_t replication;          /* c >= 1, must divide nranks */
+} dmm_matrix_desc;
+
+/* One local multiply = one op of Algorithm 1: the three tiles and the global box
+ * [m0,m1) x [k0,k1) x [n0,n1) whose A slice (rows m, cols k), B slice (rows k,
+ * cols n) and C slice (rows m, cols n) are multiplied.  Offsets inside a tile
+ * are the global bound minus the tile's lower bound (footnote of Section 4.1). */
+typedef struct {
+  int32_t rank;             /* virtual rank that owns the stationary C tile */
+  int32_t a_rep, a_ti, a_tj;
+  int32_t b_rep, b_ti, b_tj;
+  int32_t c_rep, c_ti, c_tj;
+  int64_t m0, m1, k0, k1, n0, n1;
+} dmm_task;
+
+/* One unit of GPU work: a macro-tile of one group's output sub-tile, i.e. the
+ * C region rows [m0, m0 + m_ext) x cols [n0, n0 + n_ext) (global indices) of
+ * replica c_rep, which one workgroup accumulates over the group's K-segments in
+ * ascending k and writes once.  group = -1 marks a zero-fill item: a C region
+ * whose replica has an empty share of the inner dimension. */
+typedef struct {
+  int64_t group;            /* index into group_offsets, or -1 */
+  int64_t m0, n0;           /* global top-left corner */
+  int32_t m_ext, n_ext;     /* extent, each at most the macro-tile edge */
+  int32_t c_rep, c_ti, c_tj;/* C tile written */
+  int32_t reserved;
+} dmm_work_item;
+
+typedef struct dmm_plan_s dmm_plan_t;
+
+/* Slicing planner (Algorithm 1; replication rule of Section 4.1; grouping by
+ * output sub-tile).  Host only: makes no HIP call.  `nranks` is p, the number
+ * of virtual ranks.  `flags` must be 0.  On success *out owns the plan. */
+int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C,
+             int32_t nranks, uint32_t flags, dmm_plan_t **out);
+
+/* Accessors.  Returned pointers are borrowed from the plan and live until
+ * dmm_plan_destroy.  A null plan gives 0 / NULL. */
+int64_t dmm_plan_num_tasks(const dmm_plan_t *p);
+const dmm_task *dmm_plan_tasks(const dmm_plan_t *p);        /* Algorithm-1 order: rank ascending, then loop order */
+const int64_t *dmm_plan_order(const dmm_plan_t *p);         /* stable sort of task indices by (c_rep, c_ti, c_tj, m0, n0, k0) */
+int64_t dmm_plan_num_groups(const dmm_plan_t *p);
+const int64_t *dmm_plan_group_offsets(const dmm_plan_t *p); /* num_groups + 1 offsets into order */
+int64_t dmm_plan_num_items(const dmm_plan_t *p);
+const dmm_work_item *dmm_plan_items(const dmm_plan_t *p);   /* launch order (workgroup id -> item) */
+int32_t dmm_plan_macro_tile(const dmm_plan_t *p);           /* edge of the square macro-tile, elements */
+
+/* Run the plan: C = A B (overwrite; C need not be initialised).
+ *   dtype                 element type of every A and B tile
+ *   a_tiles, b_tiles      host arrays of device pointers, one per (replica, tile) in table order
+ *   c_tiles               host array of device pointers to fp32 tiles
+ *   a_ld, b_ld, c_ld      host arrays, leading dimension in elements, >= the tile's width
+ *   flags                 0 or DMM_NO_REDUCE
+ *   hip_stream            hipStream_t, may be null (default stream)
+ * Pointers of empty tiles may be null.  Tile buffers are caller-owned and must
+ * stay valid until the stream work completes.  Asynchronous: returns after
+ * enqueueing.  Every element of every C replica is written exactly once with
+ * that replica's partial sum; then, unless DMM_NO_REDUCE, replica 0 receives
+ * the sum over replicas (other replicas keep their partials).  The first call
+ * on a plan allocates the plan's device work table; later calls allocate
+ * nothing and do not synchronise. */
+int dmm_execute(dmm_plan_t *p, int dtype,
+                const void *const *a_tiles, const int64_t *a_ld,
+                const void *const *b_tiles, const int64_t *b_ld,
+                void *const *c_tiles, const int64_t *c_ld,
+                uint32_t flags, void *hip_stream);
+
+/* reduce_replicas(origin) of Table 1: for every C tile, the origin replica's
+ * buffer receives C_0 + C_1 + ... (fp32, ascending replica index); the other
+ * replicas are left unchanged.  A no-op when C has one replica. */
+int dmm_reduce_replicas(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld,
+                        int32_t origin_replica, void *hip_stream);
+
+/* Frees host and device memory of the plan (synchronises the device first if
+ * the plan ever executed).  Null is allowed. */
+void dmm_plan_destroy(dmm_plan_t *p);
+
+const char *dmm_strerror(int status);
+int dmm_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread, 0 if none */
+int dmm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMM_H */

@@ -1,0 +1,284 @@
+// Host side of the library: slicing planner, task grouping, work-item table.
+// Integer arithmetic only; no HIP call is made from this file.
+//
+//  - op generation: Algorithm 1 (Stationary C) over every virtual rank, with the
+//    replication rule of Section 4.1 (replica r of a c-fold replicated C works
+//    on the k range [floor(rK/c), floor((r+1)K/c)) and every k bound is clipped
+//    to it).  overlapping_tiles (Table 1) is answered by binary search on the
+//    cut arrays instead of a scan, and "the tiles I own" are enumerated directly
+//    from the block-cyclic rule (Section 2.1) instead of testing every tile.
+//  - grouping: the paper executes ops in list order (Section 4.2); here ops are
+//    regrouped by output sub-tile so one workgroup accumulates all K-segments of
+//    a C region in ascending k and writes it once, without atomics.
+//  - work items: every group is cut into macro-tiles; the launch order deals
+//    contiguous runs of neighbouring macro-tiles to each of the 8 XCDs
+//    (workgroup id modulo 8 selects the XCD, each XCD has its own L2).
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "plan_internal.h"
+
+namespace dmm {
+namespace {
+
+struct Interval {
+  int64_t lo, hi;
+  bool empty() const { return lo >= hi; }
+};
+
+inline Interval meet(Interval a, Interval b) { return {std::max(a.lo, b.lo), std::min(a.hi, b.hi)}; }
+
+// Indices [first, last] of the tiles along one axis that can intersect `iv`
+// (empty tiles inside the range still have to be skipped by the caller).
+inline void tile_range(const std::vector<int64_t> &cuts, Interval iv, int32_t *first, int32_t *last) {
+  if (iv.empty()) { *first = 0; *last = -1; return; }
+  // first tile whose upper cut lies above iv.lo
+  auto up = std::upper_bound(cuts.begin() + 1, cuts.end(), iv.lo);
+  // last tile whose lower cut lies below iv.hi
+  auto lo = std::lower_bound(cuts.begin(), cuts.end() - 1, iv.hi);
+  *first = (int32_t)(up - (cuts.begin() + 1));
+  *last = (int32_t)(lo - cuts.begin()) - 1;
+}
+
+int check_cuts(const int64_t *cuts, int32_t n, int64_t dim) {
+  if (!cuts || n < 1 || dim < 0) return DMM_EINVAL;
+  if (cuts[0] != 0 || cuts[n] != dim) return DMM_EINVAL;
+  for (int32_t i = 0; i < n; ++i)
+    if (cuts[i + 1] < cuts[i]) return DMM_EINVAL;
+  return DMM_OK;
+}
+
+int load_grid(const dmm_matrix_desc *d, int32_t nranks, Grid *g) {
+  if (d->grid_rows < 1 || d->grid_cols < 1) return DMM_EINVAL;
+  int rc = check_cuts(d->row_cuts, d->grid_rows, d->rows);
+  if (rc) return rc;
+  rc = check_cuts(d->col_cuts, d->grid_cols, d->cols);
+  if (rc) return rc;
+  if (d->proc_rows < 1 || d->proc_cols < 1) return DMM_EINVAL;
+  if (d->replication < 1 || nranks % d->replication != 0) return DMM_EREPL;
+  if ((int64_t)d->proc_rows * d->proc_cols > nranks / d->replication) return DMM_EREPL;
+  g->rows = d->rows;
+  g->cols = d->cols;
+  g->gr = d->grid_rows;
+  g->gc = d->grid_cols;
+  g->rc.assign(d->row_cuts, d->row_cuts + d->grid_rows + 1);
+  g->cc.assign(d->col_cuts, d->col_cuts + d->grid_cols + 1);
+  g->pr = d->proc_rows;
+  g->pc = d->proc_cols;
+  g->c = d->replication;
+  return DMM_OK;
+}
+
+// Ops of one virtual rank, appended in Algorithm 1's loop order.
+void generate_rank(const dmm_plan_t &P, int32_t rank, std::vector<dmm_task> *out) {
+  const Grid &A = P.A, &B = P.B, &C = P.C;
+  const int32_t p = P.nranks;
+  const int32_t c_per = p / C.c, a_per = p / A.c, b_per = p / B.c;
+  const int32_t c_rep = rank / c_per, a_rep = rank / a_per, b_rep = rank / b_per;
+  const int32_t local = rank % c_per;
+  if (local >= C.pr * C.pc) return;  // this rank holds no tile of C
+  const int32_t my_pr = local / C.pc, my_pc = local % C.pc;
+  const int64_t K = A.cols;
+  const Interval share{(int64_t)c_rep * K / C.c, ((int64_t)c_rep + 1) * K / C.c};
+
+  for (int32_t i = my_pr; i < C.gr; i += C.pr) {
+    const Interval c_rows{C.rc[i], C.rc[i + 1]};
+    if (c_rows.empty()) continue;
+    int32_t a_r0, a_r1, a_c0, a_c1;
+    tile_range(A.rc, c_rows, &a_r0, &a_r1);
+    tile_range(A.cc, share, &a_c0, &a_c1);
+    for (int32_t j = my_pc; j < C.gc; j += C.pc) {
+      const Interval c_cols{C.cc[j], C.cc[j + 1]};
+      if (c_cols.empty()) continue;
+      int32_t b_c0, b_c1;
+      tile_range(B.cc, c_cols, &b_c0, &b_c1);
+      for (int32_t ai = a_r0; ai <= a_r1; ++ai) {
+        const Interval m = meet(c_rows, {A.rc[ai], A.rc[ai + 1]});
+        if (m.empty()) continue;
+        for (int32_t aj = a_c0; aj <= a_c1; ++aj) {
+          const Interval a_k = meet({A.cc[aj], A.cc[aj + 1]}, share);
+          if (a_k.empty()) continue;
+          int32_t b_r0, b_r1;
+          tile_range(B.rc, a_k, &b_r0, &b_r1);
+          for (int32_t bi = b_r0; bi <= b_r1; ++bi) {
+            const Interval k = meet(a_k, {B.rc[bi], B.rc[bi + 1]});
+            if (k.empty()) continue;
+            for (int32_t bj = b_c0; bj <= b_c1; ++bj) {
+              const Interval n = meet(c_cols, {B.cc[bj], B.cc[bj + 1]});
+              if (n.empty()) continue;
+              dmm_task t;
+              t.rank = rank;
+              t.a_rep = a_rep; t.a_ti = ai; t.a_tj = aj;
+              t.b_rep = b_rep; t.b_ti = bi; t.b_tj = bj;
+              t.c_rep = c_rep; t.c_ti = i;  t.c_tj = j;
+              t.m0 = m.lo; t.m1 = m.hi;
+              t.k0 = k.lo; t.k1 = k.hi;
+              t.n0 = n.lo; t.n1 = n.hi;
+              out->push_back(t);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+struct GroupKey {
+  int32_t rep, ti, tj;
+  int64_t m0, n0;
+  bool operator==(const GroupKey &o) const {
+    return rep == o.rep && ti == o.ti && tj == o.tj && m0 == o.m0 && n0 == o.n0;
+  }
+};
+
+inline GroupKey key_of(const dmm_task &t) { return {t.c_rep, t.c_ti, t.c_tj, t.m0, t.n0}; }
+
+void group_tasks(dmm_plan_t *P) {
+  const auto &T = P->tasks;
+  const int64_t n = (int64_t)T.size();
+  P->order.resize(n);
+  for (int64_t i = 0; i < n; ++i) P->order[i] = i;
+  // total order: output sub-tile, then k, then original position (= stable)
+  std::sort(P->order.begin(), P->order.end(), [&T](int64_t x, int64_t y) {
+    const dmm_task &a = T[x], &b = T[y];
+    if (a.c_rep != b.c_rep) return a.c_rep < b.c_rep;
+    if (a.c_ti != b.c_ti) return a.c_ti < b.c_ti;
+    if (a.c_tj != b.c_tj) return a.c_tj < b.c_tj;
+    if (a.m0 != b.m0) return a.m0 < b.m0;
+    if (a.n0 != b.n0) return a.n0 < b.n0;
+    if (a.k0 != b.k0) return a.k0 < b.k0;
+    return x < y;
+  });
+  P->group_offsets.clear();
+  P->groups.clear();
+  for (int64_t pos = 0; pos < n; ++pos) {
+    const dmm_task &t = T[P->order[pos]];
+    if (pos == 0 || !(key_of(t) == key_of(T[P->order[pos - 1]]))) {
+      P->group_offsets.push_back(pos);
+      P->groups.push_back({t.m0, t.m1, t.n0, t.n1, t.c_rep, t.c_ti, t.c_tj, pos, 0});
+    }
+    P->groups.back().count++;
+  }
+  P->group_offsets.push_back(n);
+}
+
+// Macro-tiles of one output region, appended in an order whose every run of 32
+// consecutive entries is a compact 4 x 8 block of macro-tiles (the workgroups of
+// one XCD that run together then share A row panels and B column panels in L2).
+void tile_region(int64_t group, int64_t m0, int64_t m1, int64_t n0, int64_t n1, int32_t rep, int32_t ti,
+                 int32_t tj, std::vector<dmm_work_item> *seq) {
+  const int64_t T = kMacroTile;
+  const int64_t tm = (m1 - m0 + T - 1) / T, tn = (n1 - n0 + T - 1) / T;
+  const int64_t strip = 8, band = 4;
+  for (int64_t s = 0; s < tn; s += strip)
+    for (int64_t r0 = 0; r0 < tm; r0 += band)
+      for (int64_t r = r0; r < std::min(tm, r0 + band); ++r)
+        for (int64_t c = s; c < std::min(tn, s + strip); ++c) {
+          dmm_work_item it;
+          it.group = group;
+          it.m0 = m0 + r * T;
+          it.n0 = n0 + c * T;
+          it.m_ext = (int32_t)std::min<int64_t>(T, m1 - it.m0);
+          it.n_ext = (int32_t)std::min<int64_t>(T, n1 - it.n0);
+          it.c_rep = rep; it.c_ti = ti; it.c_tj = tj;
+          it.reserved = 0;
+          seq->push_back(it);
+        }
+}
+
+void build_items(dmm_plan_t *P) {
+  std::vector<dmm_work_item> seq;
+  for (size_t g = 0; g < P->groups.size(); ++g) {
+    const Group &G = P->groups[g];
+    tile_region((int64_t)g, G.m0, G.m1, G.n0, G.n1, G.c_rep, G.c_ti, G.c_tj, &seq);
+  }
+  // C regions of replicas whose share of k is empty still have to be defined
+  // (their partial sum is zero): zero-fill items, one set per such C tile.
+  const Grid &C = P->C;
+  const int64_t K = P->A.cols;
+  for (int32_t rep = 0; rep < C.c; ++rep) {
+    if ((int64_t)rep * K / C.c < ((int64_t)rep + 1) * K / C.c) continue;
+    for (int32_t ti = 0; ti < C.gr; ++ti)
+      for (int32_t tj = 0; tj < C.gc; ++tj)
+        if (C.rc[ti] < C.rc[ti + 1] && C.cc[tj] < C.cc[tj + 1])
+          tile_region(-1, C.rc[ti], C.rc[ti + 1], C.cc[tj], C.cc[tj + 1], rep, ti, tj, &seq);
+  }
+  // Deal 8 contiguous runs of the sequence to the 8 XCDs: launch slot i goes to
+  // XCD i % 8, so run x occupies the slots congruent to x.
+  const int64_t n = (int64_t)seq.size(), X = 8;
+  P->items.clear();
+  P->items.reserve(n);
+  int64_t longest = 0;
+  for (int64_t x = 0; x < X; ++x) longest = std::max(longest, (x + 1) * n / X - x * n / X);
+  for (int64_t j = 0; j < longest; ++j)
+    for (int64_t x = 0; x < X; ++x) {
+      const int64_t b = x * n / X, e = (x + 1) * n / X;
+      if (b + j < e) P->items.push_back(seq[b + j]);
+    }
+}
+
+}  // namespace
+}  // namespace dmm
+
+extern "C" {
+
+int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C, int32_t nranks,
+             uint32_t flags, dmm_plan_t **out) {
+  if (!A || !B || !C || !out || flags != 0 || nranks < 1) return DMM_EINVAL;
+  dmm_plan_t *P = new (std::nothrow) dmm_plan_t;
+  if (!P) return DMM_ENOMEM;
+  int rc = DMM_OK;
+  try {
+    P->nranks = nranks;
+    if ((rc = dmm::load_grid(A, nranks, &P->A)) || (rc = dmm::load_grid(B, nranks, &P->B)) ||
+        (rc = dmm::load_grid(C, nranks, &P->C))) {
+      delete P;
+      return rc;
+    }
+    if (P->A.cols != P->B.rows || P->A.rows != P->C.rows || P->B.cols != P->C.cols) {
+      delete P;
+      return DMM_ESHAPE;
+    }
+    for (int32_t rank = 0; rank < nranks; ++rank) dmm::generate_rank(*P, rank, &P->tasks);
+    dmm::group_tasks(P);
+    dmm::build_items(P);
+  } catch (const std::bad_alloc &) {
+    delete P;
+    return DMM_ENOMEM;
+  }
+  *out = P;
+  return DMM_OK;
+}
+
+int64_t dmm_plan_num_tasks(const dmm_plan_t *p) { return p ? (int64_t)p->tasks.size() : 0; }
+const dmm_task *dmm_plan_tasks(const dmm_plan_t *p) { return p ? p->tasks.data() : nullptr; }
+const int64_t *dmm_plan_order(const dmm_plan_t *p) { return p ? p->order.data() : nullptr; }
+int64_t dmm_plan_num_groups(const dmm_plan_t *p) { return p ? (int64_t)p->groups.size() : 0; }
+const int64_t *dmm_plan_group_offsets(const dmm_plan_t *p) { return p ? p->group_offsets.data() : nullptr; }
+int64_t dmm_plan_num_items(const dmm_plan_t *p) { return p ? (int64_t)p->items.size() : 0; }
+const dmm_work_item *dmm_plan_items(const dmm_plan_t *p) { return p ? p->items.data() : nullptr; }
+int32_t dmm_plan_macro_tile(const dmm_plan_t *) { return dmm::kMacroTile; }
+
+void dmm_plan_destroy(dmm_plan_t *p) {
+  if (!p) return;
+  if (p->dev) dmm::destroy_device_state(p->dev);
+  delete p;
+}
+
+const char *dmm_strerror(int status) {
+  switch (status) {
+    case DMM_OK: return "ok";
+    case DMM_EINVAL: return "invalid argument (null pointer, bad cut points, empty grid, bad dtype or flag)";
+    case DMM_ESHAPE: return "shapes do not form C[m,n] = A[m,k] B[k,n]";
+    case DMM_EREPL: return "replication factor does not divide the rank count, or process grid too large for one replica";
+    case DMM_ENOMEM: return "out of memory";
+    case DMM_EHIP: return "a HIP call failed (see dmm_last_hip_error)";
+    case DMM_ELD: return "leading dimension smaller than the tile width";
+    default: return "unknown status";
+  }
+}
+
+int dmm_version(void) { return 1; }
+
+}  // extern "C"
