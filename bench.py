@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: plan -> grouped GEMM -> replica sum.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
+
+One step = one pass of the whole path over one batch of synthetic input already
+resident in HBM: ``dmm_plan`` on the descriptors (host slicing + grouping), then
+``dmm_execute`` (work-table upload, the grouped-GEMM launch and, when C is
+replicated, the replica-sum launch).  W untimed steps, then exactly K timed
+steps between two device synchronisations; one JSON line on stdout.
+
+The line also carries
+  roofline      the grouped-GEMM kernel against the dense bf16 (or fp32) MFMA
+                peak: algorithmic FLOPs (2 M N K per launch) / its average
+                duration, taken from HIP events the library records around the
+                launch on the launch stream (DMM_TIMING);
+  roofline_replica_sum   the replica-sum kernel against peak HBM bandwidth:
+                (c + 1) * 4 bytes per C element / its average duration;
+  cpu_baseline  the CPU oracle (fp64 triple loop, as it stands) timed on the
+                host cores on a bounded sample of rows of the same product.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (default: the 8192^3 2.5D configuration)")
+    ap.add_argument("--ld-multiple", type=int, default=1, help="pad leading dimensions to this many elements")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is the one-GPU part of the method (all virtual ranks' tiles live on one "
+              "MI355X); --gpus must be 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import workloads
+    from paper_2510_08874_amd import DMM_TIMING, binding
+    from paper_2510_08874_amd.tiles import DeviceProblem
+
+    binding.lib()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    cfg = workloads.config(args.workload)
+    A, B = workloads.make_operands(cfg)
+    prob = DeviceProblem(cfg, A, B, ld_multiple=args.ld_multiple)
+    stream = torch.cuda.current_stream().cuda_stream
+    c_rep = cfg["C"]["replication"]
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    def step(prev):
+        plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])      # slicing + grouping (host)
+        plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING, stream)  # upload + GEMM + replica sum
+        times = None
+        if prev is not None:
+            times = prev.elapsed_ms()
+            prev.destroy()
+        return plan, times
+
+    prev = None
+    for _ in range(args.warmup):
+        prev, _ = step(prev)
+    torch.cuda.synchronize()
+    gemm_ms, red_ms = [], []
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        prev, times = step(prev)       # `times` belong to the previous step's plan
+        if i > 0:
+            gemm_ms.append(times[0])
+            red_ms.append(times[1])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    last = prev.elapsed_ms()
+    gemm_ms.append(last[0])
+    red_ms.append(last[1])
+    prev.destroy()
+
+    # host-only cost of planning, for the record
+    tp0 = time.perf_counter()
+    for _ in range(20):
+        binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"]).destroy()
+    plan_us = (time.perf_counter() - tp0) / 20 * 1e6
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    fl = workloads.flops(cfg)
+    value = fl / (ms_per_step * 1e-3) / 1e12
+    g_avg = float(np.mean(gemm_ms))
+    g_best = float(np.min(gemm_ms))
+    achieved = fl / (g_avg * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[cfg["dtype"]]
+
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload, {})
+
+    out = {
+        "metric": "plan-execute TFLOP/s and % of MFMA peak per partitioning config (1 GPU)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: M={cfg['M']} K={cfg['K']} N={cfg['N']} {cfg['dtype']}, {cfg['what']}",
+                   "virtual_ranks": cfg["nranks"], "tasks": prob.plan.num_tasks(), "groups": prob.plan.num_groups(),
+                   "work_items": prob.plan.num_items(), "ld_multiple": args.ld_multiple,
+                   "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "plan_host_us": round(plan_us, 1)},
+        "pct_of_mfma_peak": round(100.0 * value / peak, 2),
+        "roofline": {"kernel": "grouped_gemm_kernel", "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "avg_ms": round(g_avg, 4), "best_ms": round(g_best, 4),
+                     "best_frac": round(fl / (g_best * 1e-3) / 1e12 / peak, 4),
+                     "traffic": traffic.get("gemm_bytes")},
+    }
+    if c_rep > 1:
+        r_avg = float(np.mean(red_ms))
+        r_best = float(np.min(red_ms))
+        red_bytes = (c_rep + 1) * 4.0 * cfg["M"] * cfg["N"]
+        out["roofline_replica_sum"] = {"kernel": "reduce_replicas_kernel", "bound": "hbm",
+                                       "achieved": round(red_bytes / (r_avg * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                                       "unit": "GB/s", "frac": round(red_bytes / (r_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                       "avg_ms": round(r_avg, 4), "best_ms": round(r_best, 4),
+                                       "traffic": traffic.get("reduce_bytes")}
+
+    # parity spot check on the output of the timed run, and the CPU baseline
+    from oracle import matmul as omatmul
+    rows = np.array(sorted({0, cfg["M"] - 1} | {int(r) for r in np.random.default_rng(3).integers(0, cfg["M"], 6)}))
+    got = prob.C.gather_rows(rows, 0).astype(np.float64)
+    ref = omatmul.matmul(A[rows], B, bf16=(cfg["dtype"] == "bf16"))
+    out["parity"] = {"rows_checked": int(len(rows)),
+                     "rel_frobenius": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+
+    if not args.no_cpu_baseline:
+        n_rows = args.cpu_rows or max(1, min(cfg["M"], int(3.0e12 / (2.0 * cfg["K"] * cfg["N"]))))
+        sel = np.arange(n_rows)
+        tc0 = time.perf_counter()
+        omatmul.matmul(A[sel], B, bf16=(cfg["dtype"] == "bf16"))
+        tc = time.perf_counter() - tc0
+        out["cpu_baseline"] = {"value": round(2.0 * n_rows * cfg["K"] * cfg["N"] / tc / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": omatmul.num_threads(), "kind": "oracle",
+                               "sample": f"fp64 i-k-j triple loop on the first {n_rows} of {cfg['M']} rows of C "
+                                         f"(all {cfg['N']} columns, K={cfg['K']}), {tc:.1f} s",
+                               "seconds": round(tc, 2)}
+    prob.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -49,6 +49,8 @@ typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
 
 /* dmm_execute flags */
 #define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
+#define DMM_TIMING 2u    /* record events around the GEMM launch and around the replica-sum launch
+                            on the given stream; read them with dmm_plan_elapsed_ms */
 
 /* Distributed matrix descriptor (Section 3): shape, partition object, replication
  * factor.  The partition is a tile grid given by cut points (a uniform tile
@@ -118,7 +120,7 @@ int32_t dmm_plan_macro_tile(const dmm_plan_t *p);           /* edge of the squar
  *   a_tiles, b_tiles      host arrays of device pointers, one per (replica, tile) in table order
  *   c_tiles               host array of device pointers to fp32 tiles
  *   a_ld, b_ld, c_ld      host arrays, leading dimension in elements, >= the tile's width
- *   flags                 0 or DMM_NO_REDUCE
+ *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING
  *   hip_stream            hipStream_t, may be null (default stream)
  * Pointers of empty tiles may be null.  Tile buffers are caller-owned and must
  * stay valid until the stream work completes.  Asynchronous: returns after
@@ -139,8 +141,15 @@ int dmm_execute(dmm_plan_t *p, int dtype,
 int dmm_reduce_replicas(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld,
                         int32_t origin_replica, void *hip_stream);
 
-/* Frees host and device memory of the plan (synchronises the device first if
- * the plan ever executed).  Null is allowed. */
+/* Device time of the two kernels of the last dmm_execute(..., DMM_TIMING, ...) on this
+ * plan, in milliseconds, excluding the work-table upload.  Blocks until those kernels
+ * have finished.  A kernel that was not timed (or did not run) reports -1.  Either
+ * output pointer may be null.  (Measurement aid for the roofline figures: Section 5.2
+ * reports the best of repeated runs.) */
+int dmm_plan_elapsed_ms(dmm_plan_t *p, float *gemm_ms, float *reduce_ms);
+
+/* Frees host and device memory of the plan (waits for the plan's own enqueued
+ * work first; device buffers return to a process-wide pool).  Null is allowed. */
 void dmm_plan_destroy(dmm_plan_t *p);
 
 const char *dmm_strerror(int status);

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libdmm.so")
 DMM_OK, DMM_EINVAL, DMM_ESHAPE, DMM_EREPL, DMM_ENOMEM, DMM_EHIP, DMM_ELD = 0, -1, -2, -3, -4, -5, -6
 DMM_BF16, DMM_F32 = 1, 2
 DMM_NO_REDUCE = 1
+DMM_TIMING = 2
 STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EREPL", -4: "ENOMEM", -5: "EHIP", -6: "ELD"}
 
 
@@ -91,6 +92,8 @@ def lib() -> C.CDLL:
         L.dmm_execute.argtypes = [P, C.c_int, P, P, P, P, P, P, C.c_uint32, P]
         L.dmm_reduce_replicas.restype = C.c_int
         L.dmm_reduce_replicas.argtypes = [P, P, P, C.c_int32, P]
+        L.dmm_plan_elapsed_ms.restype = C.c_int
+        L.dmm_plan_elapsed_ms.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.dmm_plan_destroy.restype = None
         L.dmm_plan_destroy.argtypes = [P]
         L.dmm_strerror.restype = C.c_char_p
@@ -103,7 +106,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
-           "dmm_execute", "dmm_reduce_replicas", "dmm_plan_destroy", "dmm_strerror",
+           "dmm_execute", "dmm_reduce_replicas", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version")
 
 
@@ -205,6 +208,14 @@ class Plan:
         rc = lib().dmm_reduce_replicas(self._h, ct, cl, origin, C.c_void_p(stream or 0))
         if rc != DMM_OK:
             raise DmmError(rc, "dmm_reduce_replicas")
+
+    def elapsed_ms(self):
+        """(gemm_ms, reduce_ms) of the last execute with DMM_TIMING; -1 = not timed."""
+        g, r = C.c_float(-1.0), C.c_float(-1.0)
+        rc = lib().dmm_plan_elapsed_ms(self._h, C.byref(g), C.byref(r))
+        if rc != DMM_OK:
+            raise DmmError(rc, "dmm_plan_elapsed_ms")
+        return float(g.value), float(r.value)
 
     def destroy(self) -> None:
         if getattr(self, "_h", None):

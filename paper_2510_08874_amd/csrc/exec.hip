@@ -25,6 +25,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -381,60 +382,112 @@ thread_local int g_last_hip_error = 0;
     }                                            \
   } while (0)
 
-// A device buffer fed through two pinned staging slots: upload() copies host bytes
-// asynchronously on the caller's stream and skips the copy when the bytes are the
-// ones already resident.
-struct Uploader {
+// One device buffer plus two pinned staging slots and their events.  Slabs are
+// recycled through a process-wide pool (in the spirit of the memory pool of
+// Section 4.2: allocate once, sub-allocate from the CPU side), so creating and
+// destroying plans in a loop does not hit hipMalloc / hipHostMalloc each time.
+struct Slab {
   char *dev = nullptr;
-  size_t cap = 0;
   char *pinned[2] = {nullptr, nullptr};
   hipEvent_t ev[2] = {nullptr, nullptr};
+  size_t cap = 0;
+};
+
+class SlabPool {
+ public:
+  int acquire(size_t bytes, Slab *out) {
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      int best = -1;
+      for (size_t i = 0; i < free_.size(); ++i)
+        if (free_[i].cap >= bytes && (best < 0 || free_[i].cap < free_[(size_t)best].cap)) best = (int)i;
+      if (best >= 0) {
+        *out = free_[(size_t)best];
+        free_.erase(free_.begin() + best);
+        return DMM_OK;
+      }
+    }
+    size_t want = 64 * 1024;
+    while (want < bytes) want *= 2;
+    Slab s;
+    hipError_t e = hipMalloc((void **)&s.dev, want);
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+      e = hipHostMalloc((void **)&s.pinned[i], want, hipHostMallocDefault);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&s.ev[i], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+      destroy(&s);
+      g_last_hip_error = (int)e;
+      return e == hipErrorOutOfMemory ? DMM_ENOMEM : DMM_EHIP;
+    }
+    s.cap = want;
+    *out = s;
+    return DMM_OK;
+  }
+  // The caller guarantees that no stream work still uses the slab.
+  void release(Slab *s) {
+    if (!s->dev) return;
+    std::lock_guard<std::mutex> g(mu_);
+    if (free_.size() < 16) free_.push_back(*s);
+    else destroy(s);
+    *s = Slab();
+  }
+
+ private:
+  static void destroy(Slab *s) {
+    if (s->dev) (void)hipFree(s->dev);
+    for (int i = 0; i < 2; ++i) {
+      if (s->pinned[i]) (void)hipHostFree(s->pinned[i]);
+      if (s->ev[i]) (void)hipEventDestroy(s->ev[i]);
+    }
+    *s = Slab();
+  }
+  std::mutex mu_;
+  std::vector<Slab> free_;
+};
+
+SlabPool &pool() {
+  static SlabPool *p = new SlabPool;   // never destroyed: outlives the HIP runtime teardown order
+  return *p;
+}
+
+// upload() copies host bytes to the slab's device buffer asynchronously on the
+// caller's stream, and skips the copy when those bytes are already resident.
+struct Uploader {
+  Slab slab;
   bool ev_used[2] = {false, false};
   int cur = 0;
   std::vector<char> resident;
   bool valid = false;
 
-  int reserve(size_t bytes) {
-    if (bytes <= cap) return DMM_OK;
-    release();
-    size_t want = bytes < 4096 ? 4096 : bytes;
-    DMM_HIP(hipMalloc((void **)&dev, want));
-    for (int s = 0; s < 2; ++s) {
-      DMM_HIP(hipHostMalloc((void **)&pinned[s], want, hipHostMallocDefault));
-      DMM_HIP(hipEventCreateWithFlags(&ev[s], hipEventDisableTiming));
-      ev_used[s] = false;
-    }
-    cap = want;
-    valid = false;
-    return DMM_OK;
-  }
+  char *dev() const { return slab.dev; }
   int upload(const void *src, size_t bytes, hipStream_t stream) {
     if (valid && resident.size() == bytes && (bytes == 0 || std::memcmp(resident.data(), src, bytes) == 0))
       return DMM_OK;
-    int rc = reserve(bytes);
-    if (rc) return rc;
     if (bytes == 0) return DMM_OK;
+    if (bytes > slab.cap) {
+      // growing: the old slab may still be read by enqueued work of this plan
+      if (slab.dev) {
+        DMM_HIP(hipStreamSynchronize(stream));
+        pool().release(&slab);
+      }
+      int rc = pool().acquire(bytes, &slab);
+      if (rc) return rc;
+      ev_used[0] = ev_used[1] = false;
+      valid = false;
+    }
     cur ^= 1;
-    if (ev_used[cur]) DMM_HIP(hipEventSynchronize(ev[cur]));  // slot last used two uploads ago
-    std::memcpy(pinned[cur], src, bytes);
-    DMM_HIP(hipMemcpyAsync(dev, pinned[cur], bytes, hipMemcpyHostToDevice, stream));
-    DMM_HIP(hipEventRecord(ev[cur], stream));
+    if (ev_used[cur]) DMM_HIP(hipEventSynchronize(slab.ev[cur]));  // slot last used two uploads ago
+    std::memcpy(slab.pinned[cur], src, bytes);
+    DMM_HIP(hipMemcpyAsync(slab.dev, slab.pinned[cur], bytes, hipMemcpyHostToDevice, stream));
+    DMM_HIP(hipEventRecord(slab.ev[cur], stream));
     ev_used[cur] = true;
     resident.assign((const char *)src, (const char *)src + bytes);
     valid = true;
     return DMM_OK;
   }
   void release() {
-    if (dev) (void)hipFree(dev);
-    for (int s = 0; s < 2; ++s) {
-      if (pinned[s]) (void)hipHostFree(pinned[s]);
-      if (ev[s]) (void)hipEventDestroy(ev[s]);
-      pinned[s] = nullptr;
-      ev[s] = nullptr;
-      ev_used[s] = false;
-    }
-    dev = nullptr;
-    cap = 0;
+    pool().release(&slab);
     valid = false;
   }
 };
@@ -442,32 +495,62 @@ struct Uploader {
 struct DeviceState {
   Uploader gemm_table;   // [ItemDev x items][SegDev x segments]
   Uploader red_table;    // [RedItem][RedTile][part pointers][part lds]
-  bool attr_set = false;
   std::vector<char> host;  // scratch for table assembly
+  hipEvent_t last_use = nullptr;      // recorded after the last launch of every call
+  bool last_use_recorded = false;
+  hipEvent_t t_gemm[2] = {nullptr, nullptr}, t_red[2] = {nullptr, nullptr};  // DMM_TIMING
+  bool gemm_timed = false, red_timed = false;
 };
 
 void destroy_device_state(DeviceState *d) {
   if (!d) return;
-  (void)hipDeviceSynchronize();
+  // wait for this plan's own work only, then hand the buffers back to the pool
+  if (d->last_use_recorded) (void)hipEventSynchronize(d->last_use);
   d->gemm_table.release();
   d->red_table.release();
+  if (d->last_use) (void)hipEventDestroy(d->last_use);
+  for (int i = 0; i < 2; ++i) {
+    if (d->t_gemm[i]) (void)hipEventDestroy(d->t_gemm[i]);
+    if (d->t_red[i]) (void)hipEventDestroy(d->t_red[i]);
+  }
   delete d;
 }
 
 namespace {
 
+std::once_flag g_attr_once;
+int g_attr_status = DMM_OK;
+
 int ensure_state(dmm_plan_t *P) {
+  std::call_once(g_attr_once, [] {
+    hipError_t e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<2>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              LDS_BYTES);
+    if (e != hipSuccess) {
+      g_last_hip_error = (int)e;
+      g_attr_status = DMM_EHIP;
+    }
+  });
+  if (g_attr_status) return g_attr_status;
   if (!P->dev) {
     P->dev = new (std::nothrow) DeviceState;
     if (!P->dev) return DMM_ENOMEM;
+    DMM_HIP(hipEventCreateWithFlags(&P->dev->last_use, hipEventDisableTiming));
   }
-  if (!P->dev->attr_set) {
-    DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                LDS_BYTES));
-    DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                LDS_BYTES));
-    P->dev->attr_set = true;
-  }
+  return DMM_OK;
+}
+
+int mark_use(dmm_plan_t *P, hipStream_t stream) {
+  DMM_HIP(hipEventRecord(P->dev->last_use, stream));
+  P->dev->last_use_recorded = true;
+  return DMM_OK;
+}
+
+int timing_events(hipEvent_t ev[2]) {
+  for (int i = 0; i < 2; ++i)
+    if (!ev[i]) DMM_HIP(hipEventCreate(&ev[i]));
   return DMM_OK;
 }
 
@@ -482,7 +565,8 @@ int check_lds(const Grid &G, const int64_t *ld) {
   return DMM_OK;
 }
 
-int launch_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, hipStream_t stream) {
+int launch_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, hipStream_t stream,
+                  bool timed) {
   const Grid &C = P->C;
   if (C.c <= 1) return DMM_OK;
   const int nparts = C.c;
@@ -540,11 +624,19 @@ int launch_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int3
   std::memcpy(h.data() + o_lds, part_ld.data(), part_ld.size() * sizeof(int64_t));
   int rc = P->dev->red_table.upload(h.data(), total, stream);
   if (rc) return rc;
-  char *d = P->dev->red_table.dev;
+  char *d = P->dev->red_table.dev();
+  if (timed) {
+    if ((rc = timing_events(P->dev->t_red))) return rc;
+    DMM_HIP(hipEventRecord(P->dev->t_red[0], stream));
+  }
   hipLaunchKernelGGL(reduce_replicas_kernel, dim3((unsigned)items.size()), dim3(RED_NT), 0, stream,
                      (const RedItem *)(d + o_items), (const RedTile *)(d + o_tiles),
                      (const float *const *)(d + o_parts), (const int64_t *)(d + o_lds), nparts, vec_ok ? 1 : 0);
   DMM_HIP(hipGetLastError());
+  if (timed) {
+    DMM_HIP(hipEventRecord(P->dev->t_red[1], stream));
+    P->dev->red_timed = true;
+  }
   return DMM_OK;
 }
 
@@ -561,7 +653,8 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   using namespace dmm;
   if (!P || !a_tiles || !a_ld || !b_tiles || !b_ld || !c_tiles || !c_ld) return DMM_EINVAL;
   if (dtype != DMM_BF16 && dtype != DMM_F32) return DMM_EINVAL;
-  if (flags & ~DMM_NO_REDUCE) return DMM_EINVAL;
+  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING)) return DMM_EINVAL;
+  const bool timed = (flags & DMM_TIMING) != 0;
   int rc;
   if ((rc = check_lds(P->A, a_ld)) || (rc = check_lds(P->B, b_ld)) || (rc = check_lds(P->C, c_ld))) return rc;
   const int64_t es = dtype == DMM_BF16 ? 2 : 4;
@@ -615,18 +708,43 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         hi[i] = d;
       }
       if ((rc = P->dev->gemm_table.upload(h.data(), total, stream))) return rc;
-      const ItemDev *di = (const ItemDev *)P->dev->gemm_table.dev;
-      const SegDev *ds = (const SegDev *)(P->dev->gemm_table.dev + o_segs);
+      const ItemDev *di = (const ItemDev *)P->dev->gemm_table.dev();
+      const SegDev *ds = (const SegDev *)(P->dev->gemm_table.dev() + o_segs);
+      if (timed) {
+        if ((rc = timing_events(P->dev->t_gemm))) return rc;
+        DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
+      }
       if (dtype == DMM_BF16)
         hipLaunchKernelGGL(grouped_gemm_kernel<2>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
       else
         hipLaunchKernelGGL(grouped_gemm_kernel<4>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
       DMM_HIP(hipGetLastError());
+      if (timed) {
+        DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
+        P->dev->gemm_timed = true;
+      }
     }
-    if (!(flags & DMM_NO_REDUCE) && P->C.c > 1) return launch_reduce(P, c_tiles, c_ld, 0, stream);
+    if (!(flags & DMM_NO_REDUCE) && P->C.c > 1 && (rc = launch_reduce(P, c_tiles, c_ld, 0, stream, timed))) return rc;
+    return mark_use(P, stream);
   } catch (const std::bad_alloc &) {
     return DMM_ENOMEM;
   }
+}
+
+int dmm_plan_elapsed_ms(dmm_plan_t *P, float *gemm_ms, float *reduce_ms) {
+  using namespace dmm;
+  if (!P) return DMM_EINVAL;
+  float g = -1.f, r = -1.f;
+  if (P->dev && P->dev->gemm_timed) {
+    DMM_HIP(hipEventSynchronize(P->dev->t_gemm[1]));
+    DMM_HIP(hipEventElapsedTime(&g, P->dev->t_gemm[0], P->dev->t_gemm[1]));
+  }
+  if (P->dev && P->dev->red_timed) {
+    DMM_HIP(hipEventSynchronize(P->dev->t_red[1]));
+    DMM_HIP(hipEventElapsedTime(&r, P->dev->t_red[0], P->dev->t_red[1]));
+  }
+  if (gemm_ms) *gemm_ms = g;
+  if (reduce_ms) *reduce_ms = r;
   return DMM_OK;
 }
 
@@ -639,7 +757,8 @@ int dmm_reduce_replicas(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld
   if ((rc = check_lds(P->C, c_ld))) return rc;
   try {
     if ((rc = ensure_state(P))) return rc;
-    return launch_reduce(P, c_tiles, c_ld, origin_replica, (hipStream_t)hip_stream);
+    if ((rc = launch_reduce(P, c_tiles, c_ld, origin_replica, (hipStream_t)hip_stream, false))) return rc;
+    return P->C.c > 1 ? mark_use(P, (hipStream_t)hip_stream) : DMM_OK;
   } catch (const std::bad_alloc &) {
     return DMM_ENOMEM;
   }
