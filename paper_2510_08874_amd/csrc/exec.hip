@@ -1,26 +1,6 @@
-// Device side of the library (gfx950 only): the grouped GEMM that executes the
-// whole op list in one launch, the replica-sum kernel, and the host code that
-// turns a plan plus tile pointers into the device work table.
-//
-// Grouped GEMM (the "local matrix multiplication" step of Section 4.2, for all
-// ranks at once).  One workgroup owns one 256 x 256 macro-tile of one output
-// sub-tile and walks the group's K-segments in ascending k; each segment reads
-// an A slice and a B slice straight out of the owning virtual rank's tile
-// buffer (the one-sided "get" of Section 3 as a strided load).  Accumulation is
-// fp32 in MFMA accumulators; the C region is written once, so no atomics and a
-// fixed summation order.
-//
-//   8 waves (2 x 4), wave tile 128 x 64, K step 64 (bf16) or 32 (fp32).
-//   global -> VGPR -> LDS, two LDS stages (2 x 64 KB), one barrier per K step.
-//   A stage: 256 rows x 128 B, 16-byte chunks XOR-swizzled by row.
-//   B stage: K rows x 256 columns, 64/128-byte column segments XOR-swizzled by k.
-//   bf16: v_mfma_f32_32x32x16_bf16; A fragments by ds_read_b128, B fragments by
-//         ds_read_b64_tr_b16 (B is row-major k x n, the MFMA wants k-contiguous).
-//   fp32: v_mfma_f32_32x32x2_f32; A fragments by ds_read_b128 with the k order
-//         permuted identically on the B side.
-//   Edges: rows beyond the item's extent are clamped (their results are never
-//   stored); partial 16-byte chunks along n and the K tail of a segment are
-//   loaded element-wise with zero fill.
+// Device-facing half of the library (gfx950 only): the host code that turns a plan
+// plus tile pointers into device work tables and launches the grouped GEMM
+// (gemm_kernel.hpp), and the replica-sum kernel (reduce_replicas of Table 1).
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -29,27 +9,12 @@
 #include <new>
 #include <vector>
 
+#include "gemm_kernel.hpp"
 #include "plan_internal.h"
 
 namespace dmm {
 
-// ------------------------------------------------------------------ device tables
-
-struct SegDev {          // one K-segment of a group, pointers at the group's (m0, k0) / (k0, n0)
-  const char *a;
-  const char *b;
-  int64_t lda, ldb;      // elements
-  int32_t klen;
-  int32_t pad;
-};
-
-struct ItemDev {         // one macro-tile
-  float *c;              // top-left of the macro-tile in the C tile
-  int64_t ldc;
-  int32_t seg_begin, seg_count;
-  int32_t m_off, n_off;  // offset inside the group's sub-tile
-  int32_t m_ext, n_ext;
-};
+// ------------------------------------------------------------------ device tables (replica sum)
 
 struct RedTile {         // one C tile for the replica sum
   float *out;
@@ -64,268 +29,9 @@ struct RedItem {
   int32_t pad;
 };
 
-// ------------------------------------------------------------------ GEMM kernel
-
-constexpr int BM = 256, BN = 256;
-constexpr int NT = 512;                       // 8 waves
-constexpr int WAVES_M = 2, WAVES_N = 4;       // wave tile 128 x 64
-constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-constexpr int FM = WTM / 32, FN = WTN / 32;   // 4 x 2 MFMA tiles of 32 x 32
-constexpr int A_STAGE = BM * 128;             // bytes: 256 rows x 128 B
-constexpr int B_STAGE = 32 * 1024;            // bytes: 64 x 512 B (bf16) or 32 x 1024 B (fp32)
-constexpr int STAGE = A_STAGE + B_STAGE;
-constexpr int LDS_BYTES = 2 * STAGE;          // 128 KB
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) short short4_t;
-typedef __attribute__((ext_vector_type(16))) float floatx16;
-typedef __attribute__((address_space(3))) short4_t *lds_short4_ptr;
-// Pointers read from the work table would otherwise be treated as generic (flat) addresses.
-typedef const __attribute__((address_space(1))) char *gptr;
-typedef __attribute__((address_space(1))) float *gfloat_ptr;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef u32x4 u32x4_a2 __attribute__((aligned(2)));   // 16 bytes at element alignment only
-typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-template <int ES>
-struct Shape;                                  // per element size
-template <>
-struct Shape<2> {                              // bf16
-  static constexpr int BK = 64;                // elements per K step
-  static constexpr int B_ROW = 512;            // bytes per k row of the B stage
-  static constexpr int B_CHUNKS = 32;          // 16-byte chunks per k row
-};
-template <>
-struct Shape<4> {                              // fp32
-  static constexpr int BK = 32;
-  static constexpr int B_ROW = 1024;
-  static constexpr int B_CHUNKS = 64;
-};
-
-__device__ __forceinline__ int a_swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
-
-// byte offset of 16-byte chunk `c` (0..7) of row `row` in the A stage
-__device__ __forceinline__ int a_lds_off(int row, int c) { return row * 128 + ((c ^ a_swizzle(row)) << 4); }
-
-// byte offset of 16-byte chunk `c` of k row `k` in the B stage.  bf16: 64-byte
-// segments (4 chunks) are XOR-ed with k & 3 so the four k rows one transposed
-// read touches fall into different banks; fp32: 128-byte segments (8 chunks)
-// XOR-ed with (k >> 2) & 7 so rows k and k + 4, read together, do not collide.
-template <int ES>
-__device__ __forceinline__ int b_lds_off(int k, int c) {
-  if (ES == 2) return k * 512 + ((((c >> 2) ^ (k & 3)) << 2 | (c & 3)) << 4);
-  return k * 1024 + ((((c >> 3) ^ ((k >> 2) & 7)) << 3 | (c & 7)) << 4);
-}
-
-// 16 bytes = 16/ES elements starting at p; `valid` of them exist, the rest read as 0.
-template <int ES>
-__device__ __forceinline__ uint4 load_chunk(gptr p, int valid) {
-  constexpr int PER = 16 / ES;
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (valid >= PER) {
-    // only element alignment is guaranteed (odd leading dimensions); gfx950 serves
-    // unaligned 16-byte global loads in hardware
-    if (ES == 2) v = *(const __attribute__((address_space(1))) u32x4_a2 *)p;
-    else v = *(const __attribute__((address_space(1))) u32x4_a4 *)p;
-  } else if (valid > 0) {
-    if (ES == 2) {
-      const __attribute__((address_space(1))) unsigned short *q =
-          (const __attribute__((address_space(1))) unsigned short *)p;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const unsigned int e = i < valid ? (unsigned int)q[i] : 0u;
-        v[i >> 1] |= e << ((i & 1) * 16);
-      }
-    } else {
-      const __attribute__((address_space(1))) unsigned int *q =
-          (const __attribute__((address_space(1))) unsigned int *)p;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] = i < valid ? q[i] : 0u;
-    }
-  }
-  return make_uint4(v[0], v[1], v[2], v[3]);
-}
-
-template <int ES>
-__global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restrict__ items,
-                                                          const SegDev *__restrict__ segs) {
-  using S = Shape<ES>;
-  constexpr int BK = S::BK;
-  constexpr int PER = 16 / ES;                          // elements per 16-byte chunk
-  constexpr int A_PER_THREAD = (BM * 8) / NT;           // 4 chunks of the A stage per thread
-  constexpr int B_PER_THREAD = (BK * S::B_CHUNKS) / NT; // 4 chunks of the B stage per thread
-  constexpr int B_ROWS_PER_PASS = NT / S::B_CHUNKS;     // 16 (bf16) or 8 (fp32)
-
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-
-  const ItemDev it = items[blockIdx.x];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-
-  floatx16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  // this thread's chunks of the A stage: rows a_row + 64 i, chunk a_c
-  const int a_row = tid >> 3, a_c = tid & 7;
-  // ... and of the B stage: k rows b_k + B_ROWS_PER_PASS i, chunk b_c
-  const int b_k = tid / S::B_CHUNKS, b_c = tid % S::B_CHUNKS;
-  const int b_valid = it.n_ext - b_c * PER;              // columns of this chunk inside the item
-
-  int a_rows_clamped[A_PER_THREAD];
-#pragma unroll
-  for (int i = 0; i < A_PER_THREAD; ++i) {
-    const int r = a_row + 64 * i;
-    a_rows_clamped[i] = r < it.m_ext ? r : it.m_ext - 1;
-  }
-
-  uint4 ra[A_PER_THREAD], rb[B_PER_THREAD];
-
-  // K iteration state: segment index and position inside it
-  int seg = 0, kpos = 0;
-  SegDev sd;
-  if (it.seg_count > 0) sd = segs[it.seg_begin];
-
-  auto fetch = [&]() {
-    // load the K step at (seg, kpos) into registers
-    const int krem = sd.klen - kpos;                     // > 0
-    gptr ap = (gptr)sd.a + ((int64_t)it.m_off * sd.lda + kpos) * ES;
-    const int a_valid = krem - a_c * PER;
-#pragma unroll
-    for (int i = 0; i < A_PER_THREAD; ++i)
-      ra[i] = load_chunk<ES>(ap + ((int64_t)a_rows_clamped[i] * sd.lda + a_c * PER) * ES, a_valid);
-    gptr bp = (gptr)sd.b + ((int64_t)kpos * sd.ldb + it.n_off) * ES;
-#pragma unroll
-    for (int i = 0; i < B_PER_THREAD; ++i) {
-      const int k = b_k + B_ROWS_PER_PASS * i;
-      rb[i] = load_chunk<ES>(bp + ((int64_t)k * sd.ldb + b_c * PER) * ES, k < krem ? b_valid : 0);
-    }
-  };
-  auto advance = [&]() -> bool {                         // false when the item's K range is exhausted
-    kpos += BK;
-    if (kpos >= sd.klen) {
-      ++seg;
-      kpos = 0;
-      if (seg >= it.seg_count) return false;
-      sd = segs[it.seg_begin + seg];
-    }
-    return true;
-  };
-  auto stash = [&](int stage) {
-    char *sa = lds + stage * STAGE;
-    char *sb = sa + A_STAGE;
-#pragma unroll
-    for (int i = 0; i < A_PER_THREAD; ++i) *(uint4 *)(sa + a_lds_off(a_row + 64 * i, a_c)) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_PER_THREAD; ++i)
-      *(uint4 *)(sb + b_lds_off<ES>(b_k + B_ROWS_PER_PASS * i, b_c)) = rb[i];
-  };
-
-  auto compute = [&](int stage) {
-    const char *sa = lds + stage * STAGE;
-    const char *sb = sa + A_STAGE;
-    if (ES == 2) {
-#pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 af[FM], bfr[FN];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-          const int row = wm * WTM + i * 32 + (lane & 31);
-          af[i] = *(const bf16x8 *)(sa + a_lds_off(row, kk * 2 + (lane >> 5)));
-        }
-        const int g = lane >> 4, li = lane & 15;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int ncol = wn * WTN + j * 32 + (g & 1) * 16 + (li & 3) * 4;   // 4 columns, 8 bytes
-          const int k0 = kk * 16 + (g >> 1) * 8 + (li >> 2);
-          short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_short4_ptr)(sb + b_lds_off<2>(k0, ncol >> 3) + (ncol & 7) * 2));
-          short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_short4_ptr)(sb + b_lds_off<2>(k0 + 4, ncol >> 3) + (ncol & 7) * 2));
-          union { short4_t h[2]; bf16x8 v; } u;
-          u.h[0] = lo;
-          u.h[1] = hi;
-          bfr[j] = u.v;
-        }
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-    } else {
-      // fp32: blocks of 8 k; lane half h reads the float4 at k = 8 kb + 4 h .. + 3, and MFMA
-      // number e consumes element e, i.e. k = 8 kb + 4 h + e on the A side; the B side reads
-      // the same k for its lane half.
-#pragma unroll
-      for (int kb = 0; kb < BK / 8; ++kb) {
-        float4 af[FM];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-          const int row = wm * WTM + i * 32 + (lane & 31);
-          af[i] = *(const float4 *)(sa + a_lds_off(row, kb * 2 + (lane >> 5)));
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int k = kb * 8 + (lane >> 5) * 4 + e;
-          float bv[FN];
-#pragma unroll
-          for (int j = 0; j < FN; ++j) {
-            const int ncol = wn * WTN + j * 32 + (lane & 31);
-            bv[j] = *(const float *)(sb + b_lds_off<4>(k, ncol >> 2) + (ncol & 3) * 4);
-          }
-#pragma unroll
-          for (int i = 0; i < FM; ++i) {
-            const float av = e == 0 ? af[i].x : e == 1 ? af[i].y : e == 2 ? af[i].z : af[i].w;
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[j], acc[i][j], 0, 0, 0);
-          }
-        }
-      }
-    }
-  };
-
-  if (it.seg_count > 0) {
-    fetch();
-    stash(0);
-    __syncthreads();
-    int stage = 0;
-    bool more = advance();
-    while (true) {
-      if (more) fetch();                     // global loads of the next step fly during the MFMAs
-      compute(stage);
-      if (!more) break;
-      stash(stage ^ 1);
-      __syncthreads();
-      stage ^= 1;
-      more = advance();
-    }
-  }
-
-  gfloat_ptr cbase = (gfloat_ptr)it.c;
-  // epilogue: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 tile
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int col = wn * WTN + j * 32 + (lane & 31);
-      if (col < it.n_ext) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (row < it.m_ext) cbase[(int64_t)row * it.ldc + col] = acc[i][j][r];
-        }
-      }
-    }
-}
+using GemmWaves = Waves<2, 2>;   // 4 waves, wave tile 128 x 128: accumulators in AGPRs, 512 registers per wave
 
 // ------------------------------------------------------------------ replica sum
 
@@ -523,10 +229,10 @@ int g_attr_status = DMM_OK;
 
 int ensure_state(dmm_plan_t *P) {
   std::call_once(g_attr_once, [] {
-    hipError_t e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<2>,
+    hipError_t e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<2, GemmWaves>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<4, GemmWaves>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               LDS_BYTES);
     if (e != hipSuccess) {
       g_last_hip_error = (int)e;
@@ -658,6 +364,12 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   int rc;
   if ((rc = check_lds(P->A, a_ld)) || (rc = check_lds(P->B, b_ld)) || (rc = check_lds(P->C, c_ld))) return rc;
   const int64_t es = dtype == DMM_BF16 ? 2 : 4;
+  const int64_t bk = dtype == DMM_BF16 ? Shape<2>::BK : Shape<4>::BK;
+  // the kernel addresses a macro-tile's rows with 32-bit byte offsets from the step's base
+  for (int64_t i = 0; i < P->A.c * P->A.tiles_per_rep(); ++i)
+    if (a_ld[i] * es * BM >= (int64_t)1 << 32) return DMM_ELD;
+  for (int64_t i = 0; i < P->B.c * P->B.tiles_per_rep(); ++i)
+    if (b_ld[i] * es * 64 >= (int64_t)1 << 32) return DMM_ELD;
   hipStream_t stream = (hipStream_t)hip_stream;
   try {
     if ((rc = ensure_state(P))) return rc;
@@ -681,6 +393,12 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         s.ldb = b_ld[bi];
         s.a = (const char *)a_tiles[ai] + ((t.m0 - P->A.rc[t.a_ti]) * s.lda + (t.k0 - P->A.cc[t.a_tj])) * es;
         s.b = (const char *)b_tiles[bi] + ((t.k0 - P->B.rc[t.b_ti]) * s.ldb + (t.n0 - P->B.cc[t.b_tj])) * es;
+        // bytes that may be read from the segment's origin to the end of the tile buffer
+        // ((rows - 1) * ld + cols elements are guaranteed to exist)
+        const int64_t a_h = P->A.rc[t.a_ti + 1] - P->A.rc[t.a_ti], a_w = P->A.cc[t.a_tj + 1] - P->A.cc[t.a_tj];
+        const int64_t b_h = P->B.rc[t.b_ti + 1] - P->B.rc[t.b_ti], b_w = P->B.cc[t.b_tj + 1] - P->B.cc[t.b_tj];
+        s.a_bytes = ((a_h - 1) * s.lda + a_w - ((t.m0 - P->A.rc[t.a_ti]) * s.lda + (t.k0 - P->A.cc[t.a_tj]))) * es;
+        s.b_bytes = ((b_h - 1) * s.ldb + b_w - ((t.k0 - P->B.rc[t.b_ti]) * s.ldb + (t.n0 - P->B.cc[t.b_tj]))) * es;
         s.klen = (int32_t)(t.k1 - t.k0);
         s.pad = 0;
         hs[pos] = s;
@@ -695,12 +413,14 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         if (w.group >= 0) {
           const Group &G = P->groups[(size_t)w.group];
           d.seg_begin = (int32_t)G.first;
-          d.seg_count = (int32_t)G.count;
+          d.nsteps = 0;
+          for (int64_t q = 0; q < G.count; ++q)
+            d.nsteps += (int32_t)((hs[G.first + q].klen + bk - 1) / bk);
           d.m_off = (int32_t)(w.m0 - G.m0);
           d.n_off = (int32_t)(w.n0 - G.n0);
         } else {
           d.seg_begin = 0;
-          d.seg_count = 0;
+          d.nsteps = 0;
           d.m_off = d.n_off = 0;
         }
         d.m_ext = w.m_ext;
@@ -715,9 +435,9 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
       }
       if (dtype == DMM_BF16)
-        hipLaunchKernelGGL(grouped_gemm_kernel<2>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
+        hipLaunchKernelGGL((grouped_gemm_kernel<2, GemmWaves>), dim3((unsigned)n_items), dim3(GemmWaves::NT), LDS_BYTES, stream, di, ds);
       else
-        hipLaunchKernelGGL(grouped_gemm_kernel<4>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
+        hipLaunchKernelGGL((grouped_gemm_kernel<4, GemmWaves>), dim3((unsigned)n_items), dim3(GemmWaves::NT), LDS_BYTES, stream, di, ds);
       DMM_HIP(hipGetLastError());
       if (timed) {
         DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
