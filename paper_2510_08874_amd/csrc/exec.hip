@@ -31,8 +31,6 @@ struct RedItem {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-using GemmWaves = Waves<2, 2>;   // 4 waves, wave tile 128 x 128: accumulators in AGPRs, 512 registers per wave
-
 // ------------------------------------------------------------------ replica sum
 
 // out = ((p0 + p1) + p2) + ...  for a block of rows of one C tile (reduce_replicas, Table 1).
@@ -229,10 +227,10 @@ int g_attr_status = DMM_OK;
 
 int ensure_state(dmm_plan_t *P) {
   std::call_once(g_attr_once, [] {
-    hipError_t e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<2, GemmWaves>,
+    hipError_t e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<2>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<4, GemmWaves>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               LDS_BYTES);
     if (e != hipSuccess) {
       g_last_hip_error = (int)e;
@@ -435,9 +433,9 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
       }
       if (dtype == DMM_BF16)
-        hipLaunchKernelGGL((grouped_gemm_kernel<2, GemmWaves>), dim3((unsigned)n_items), dim3(GemmWaves::NT), LDS_BYTES, stream, di, ds);
+        hipLaunchKernelGGL(grouped_gemm_kernel<2>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
       else
-        hipLaunchKernelGGL((grouped_gemm_kernel<4, GemmWaves>), dim3((unsigned)n_items), dim3(GemmWaves::NT), LDS_BYTES, stream, di, ds);
+        hipLaunchKernelGGL(grouped_gemm_kernel<4>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
       DMM_HIP(hipGetLastError());
       if (timed) {
         DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));

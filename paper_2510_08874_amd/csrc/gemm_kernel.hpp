@@ -9,20 +9,28 @@
 // registers; each C element is written once, so there are no atomics and the
 // summation order is fixed.
 //
-// Layout of the work
-//   8 waves (2 x 4), wave tile 128 x 64 = 4 x 2 MFMA tiles of 32 x 32.
-//   K step: 64 (bf16) or 32 (fp32) elements = 128 bytes of every A row.
-//   Two LDS stages of 64 KB: A stage 256 rows x 128 B, B stage K rows x 256 columns.
+// Shape of the work
+//   4 waves (2 x 2), one per SIMD; wave tile 128 x 128 = 4 x 4 MFMA tiles of
+//   32 x 32 (256 accumulator registers per lane, held in AGPRs).
+//   K step: 64 bytes of every A row = 32 bf16 or 16 fp32, consumed as two MFMA
+//   sub-steps (v_mfma_f32_32x32x16_bf16 / v_mfma_f32_32x32x2_f32).
+//   LDS: a ring of 4 stages of 32 KB (A: 256 rows x 64 B, B: K rows x 256 columns).
 //   16-byte chunks are XOR-swizzled (A by row, B by k) so that ds_read_b128 of A
 //   fragments and ds_read_b64_tr_b16 of B fragments are free of bank conflicts.
 //
 // Global -> LDS
 //   global_load_lds_dwordx4: every lane moves 16 bytes from an arbitrary global
 //   address to LDS, lane l landing at M0 + 16 l, with no register staging.  A wave
-//   fills 1 KB per instruction (8 A rows, or 2 / 1 B rows); the swizzle is realised
+//   fills 1 KB per instruction (16 A rows, or 2 / 1 B rows); the swizzle is realised
 //   by permuting which global chunk a lane fetches.  Sources need only element
-//   alignment (odd leading dimensions are fine).  The loads of step s + 1 are in
-//   flight while step s is multiplied.
+//   alignment (odd leading dimensions are fine).
+//   A CU's memory pipeline takes ~16-20 cycles per such instruction and stalls the
+//   issuing wave meanwhile, and with one wave per SIMD a stalled wave starves its
+//   matrix pipe.  So the loads are not issued in bursts: the loads of step s + 3 are
+//   spread over the MFMA stream of step s, one per four MFMAs per wave, and the four
+//   waves use different slots (the loop body is instantiated once per wave with a
+//   rotated schedule), so that at most one wave of the CU issues a load in any slot.
+//   Data therefore has more than two K steps (> 2000 cycles) to land.
 //
 // Edges, without a second load path
 //   rows past the item's extent    -> the lane reads the last valid row instead
@@ -39,6 +47,8 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #ifdef DMM_NO_SCHED_BARRIER
 #define DMM_SCHED_BARRIER
@@ -68,22 +78,21 @@ struct ItemDev {         // one macro-tile
 };
 
 constexpr int BM = 256, BN = 256;
-constexpr int A_STAGE = BM * 128;             // bytes: 256 rows x 128 B
-constexpr int B_STAGE = 32 * 1024;            // bytes: 64 x 512 B (bf16) or 32 x 1024 B (fp32)
-constexpr int STAGE = A_STAGE + B_STAGE;
-constexpr int LDS_BYTES = 2 * STAGE;          // 128 KB
-
-// Wave arrangement of a workgroup: WAVES_M x WAVES_N waves, each owning a
-// (256 / WAVES_M) x (256 / WAVES_N) part of the macro-tile as FM x FN MFMA tiles of 32 x 32.
-template <int WAVES_M_, int WAVES_N_>
-struct Waves {
-  static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-  static constexpr int NW = WAVES_M * WAVES_N;
-  static constexpr int NT = 64 * NW;
-  static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-  static constexpr int FM = WTM / 32, FN = WTN / 32;
-  static constexpr int LOADS = 32 / NW;      // wave-wide 1 KB loads per wave, per operand, per K step
-};
+constexpr int A_ROW = 64;                     // bytes of an A row per K step
+constexpr int A_STAGE = BM * A_ROW;           // 16 KB
+constexpr int B_STAGE = 16 * 1024;            // 32 x 512 B (bf16) or 16 x 1024 B (fp32)
+constexpr int STAGE = A_STAGE + B_STAGE;      // 32 KB
+constexpr int NSTAGE = 4;
+constexpr int LDS_BYTES = NSTAGE * STAGE;     // 128 KB
+constexpr int NW = 4;                         // waves per workgroup, 2 x 2
+constexpr int NT = 64 * NW;
+constexpr int WAVES_N = 2;
+constexpr int WTM = 128, WTN = 128;           // wave tile
+constexpr int FM = 4, FN = 4;                 // MFMA tiles of 32 x 32 per wave
+constexpr int LOADS = 16 / NW;                // wave-wide 1 KB loads per wave, per operand, per K step
+constexpr int KSUB = 2;                       // MFMA sub-steps per K step
+constexpr int SLOTS = KSUB * FM * FN;         // MFMA slots per K step (32)
+static_assert(LOADS == 4 && SLOTS == 2 * LOADS * NW, "the load slots of run_item are written out for 8 loads per step");
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
@@ -99,35 +108,34 @@ template <int ES>
 struct Shape;
 template <>
 struct Shape<2> {                              // bf16
-  static constexpr int BK = 64;                // elements per K step
+  static constexpr int BK = 32;                // elements per K step
   static constexpr int B_ROW = 512;            // bytes per k row of the B stage
   static constexpr int B_CHUNKS = 32;          // 16-byte chunks per k row
-  static constexpr int KSUB = 4;               // MFMA sub-steps per K step (16 k each)
 };
 template <>
 struct Shape<4> {                              // fp32
-  static constexpr int BK = 32;
+  static constexpr int BK = 16;
   static constexpr int B_ROW = 1024;
   static constexpr int B_CHUNKS = 64;
-  static constexpr int KSUB = 4;               // 8 k each
 };
 
-template <int ES, int FM, int FN>
+template <int ES>
 struct FragSet;
-template <int FM, int FN>
-struct FragSet<2, FM, FN> {        // bf16: A rows x 8 k and B columns x 8 k per lane
-  bf16x8 a[FM], b[FN];
+template <>
+struct FragSet<2> {                // bf16: A rows x 8 k and B columns x 8 k per lane
+  bf16x8 a[FM];
+  short4_t b[FN][2];
 };
-template <int FM, int FN>
-struct FragSet<4, FM, FN> {        // fp32: A rows x 4 k per lane; B value per MFMA e and column block
+template <>
+struct FragSet<4> {                // fp32: A rows x 4 k per lane; B value per MFMA e and column block
   float4 a[FM];
   float b[4][FN];
 };
 
-__device__ __forceinline__ int a_swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
-
-// byte offset of 16-byte chunk `c` (0..7) of row `row` in the A stage
-__device__ __forceinline__ int a_lds_off(int row, int c) { return row * 128 + ((c ^ a_swizzle(row)) << 4); }
+// A stage: row r at r * 64, its four 16-byte chunks XOR-ed with a function of the row that
+// spreads both 8 and 16 consecutive rows reading the same logical chunk over all banks.
+__device__ __forceinline__ int a_swizzle(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+__device__ __forceinline__ int a_lds_off(int row, int c) { return row * A_ROW + ((c ^ a_swizzle(row)) << 4); }
 
 // chunk position <-> logical chunk inside a k row of the B stage (an involution).
 // bf16: 64-byte segments (4 chunks) XOR-ed with k & 3, so the four k rows that one
@@ -147,14 +155,49 @@ __device__ __forceinline__ int b_lds_off(int k, int c) {
 // address lds_base + 16 l (lds_base wave-uniform, passed in M0); lanes switched off by the
 // exec mask leave their slot untouched.  The source is a wave-uniform 64-bit base plus a
 // 32-bit per-lane byte offset.  Issued as inline assembly so that the compiler does not
-// serialise it against LDS reads of the *other* stage (it cannot tell the stages apart and
+// serialise it against LDS reads of *other* stages (it cannot tell the stages apart and
 // would wait for vmcnt(0) before every ds_read); completion is awaited explicitly with
-// s_waitcnt vmcnt(0) before the barrier that publishes the stage.
+// s_waitcnt vmcnt before the barrier that publishes a stage.
 __device__ __forceinline__ void load_to_lds_16(gptr base, unsigned lane_off, unsigned lds_base) {
+#ifdef DMM_EXP_NODMA
+  return;
+#endif
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base)
                : "memory");
+}
+// The form used in the K loop: the LDS address is a wave-uniform base plus a compile-time
+// constant, and the lanes that take part are given as an exec mask (all ones for an ordinary
+// step, fewer when some lanes would overrun a tile buffer, zero when there is nothing to load),
+// so a load slot is five instructions and no branch.  Every instruction costs a wave at
+// least 4 issue cycles and only about seven fit in the shadow of one MFMA.  The s_mov to exec
+// doubles as the wait state required between the M0 write and the LDS-DMA instruction.
+template <int IMM>
+__device__ __forceinline__ void load_to_lds_16_masked(gptr base, unsigned lane_off, unsigned lds_base,
+                                                      unsigned lo, unsigned hi) {
+#ifdef DMM_EXP_NODMA
+  return;
+#endif
+#if defined(DMM_EXP_SLOT_A)      // scalar part only
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_mov_b32 exec_lo, %4\n\ts_mov_b32 exec_hi, %5\n\t"
+               "s_mov_b64 exec, -1"
+#elif defined(DMM_EXP_SLOT_E)    // nothing, but the operands stay alive
+  asm volatile("; slot"
+#elif defined(DMM_EXP_SLOT_C)    // only the M0 write
+  asm volatile("s_add_u32 m0, %2, %3"
+#elif defined(DMM_EXP_SLOT_D)    // only the load (M0 left as it is: lands somewhere in LDS)
+  asm volatile("global_load_lds_dwordx4 %0, %1"
+#elif defined(DMM_EXP_SLOT_B)    // no exec writes
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %0, %1"
+#else
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_mov_b32 exec_lo, %4\n\ts_mov_b32 exec_hi, %5\n\t"
+               "global_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1"
+#endif
+               :
+               : "v"(lane_off), "s"(base), "s"(lds_base), "n"(IMM), "s"(lo), "s"(hi)
+               : "memory", "scc");
 }
 
 // The first `n` (< 16 / ES) elements at p, the rest zero; n <= 0 reads nothing.
@@ -194,114 +237,165 @@ __device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
   return v;
 }
 
-template <int ES, class W>
-__global__ __launch_bounds__(W::NT) void grouped_gemm_kernel(const ItemDev *__restrict__ items,
-                                                             const SegDev *__restrict__ segs) {
+// The work of one wave on one item.  ROT = this wave's index: it selects the MFMA slots
+// in which the wave issues its global->LDS loads (slot % 4 == ROT).
+template <int ES, int ROT>
+__device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__restrict__ segs, char *lds,
+                                         floatx16 (&acc)[FM][FN]) {
   using S = Shape<ES>;
-  constexpr int WAVES_N = W::WAVES_N, NW = W::NW, WTM = W::WTM, WTN = W::WTN, FM = W::FM, FN = W::FN,
-                LOADS = W::LOADS;
   constexpr int BK = S::BK;
   constexpr int PER = 16 / ES;                          // elements per 16-byte chunk
   constexpr int B_ROWS_PER_KB = 1024 / S::B_ROW;        // k rows one wave-wide load covers
-  constexpr int KSUB = S::KSUB;
+  constexpr int wave = ROT;
+  constexpr int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-
-  const ItemDev it = items[blockIdx.x];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int lane = threadIdx.x & 63;
   const unsigned lds_base = (unsigned)(uintptr_t)(lds_void_ptr)lds;   // LDS byte address of stage 0
 
-  floatx16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
   // ---- global -> LDS ------------------------------------------------------------------
-  // Wave w, load i fills KB number NW i + w of the A stage (rows 8 (NW i + w) .. + 7) and KB
+  // Wave w, load i fills KB number NW i + w of the A stage (rows 16 (NW i + w) .. + 15) and KB
   // number NW i + w of the B stage (k rows B_ROWS_PER_KB (NW i + w) ..).  Lane l owns the slot at
-  // +16 l of that KB; a_src / b_src are the byte offsets of the chunk it fetches, relative
-  // to the step's base address.
-  unsigned a_src[LOADS], b_src[LOADS];
-  const int a_slot_row = lane >> 3;                      // row of this lane's slot inside an A KB
+  // +16 l of that KB.
+  const int a_slot_row = lane >> 2;                      // row of this lane's slot inside an A KB
+  const int a_slot_pos = lane & 3;                       // chunk position inside that row
   const int b_slot_k = lane / S::B_CHUNKS;               // k row of this lane's slot inside a B KB
   const int b_slot_pos = lane % S::B_CHUNKS;             // chunk position inside that k row
 
-  int seg = 0, kpos = 0;
-  SegDev sd;
-  // state of the step whose loads were issued last (the one being landed into LDS)
-  gptr st_a = nullptr, st_b = nullptr;                   // base addresses of the step
-  int64_t st_a_left = 0, st_b_left = 0;                  // readable bytes from those bases
-  int st_krem = 0;                                       // k elements of the segment left at the step
-  bool st_fix = false;                                   // the step needs patching before it is published
-
-  auto open_segment = [&]() {
-    sd = segs[it.seg_begin + seg];
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      const int row = (i * NW + wave) * 8 + a_slot_row;
-      const int src_row = row < it.m_ext ? row : it.m_ext - 1;
-      const int c = (lane & 7) ^ a_swizzle(row);
-      a_src[i] = (unsigned)(((int64_t)src_row * sd.lda + c * PER) * ES);
-    }
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      const int k = (i * NW + wave) * B_ROWS_PER_KB + b_slot_k;
-      const int c = b_swizzle_chunk<ES>(k, b_slot_pos);
-      b_src[i] = (unsigned)(((int64_t)k * sd.ldb + c * PER) * ES);
-    }
+  // byte offset, from a step's base address, of the chunk this lane fetches with load i
+  auto a_offset = [&](const SegDev &sd, int i) -> unsigned {
+    const int row = (i * NW + wave) * 16 + a_slot_row;
+    const int src_row = row < it.m_ext ? row : it.m_ext - 1;
+    const int c = a_slot_pos ^ a_swizzle(row);
+    return (unsigned)(((int64_t)src_row * sd.lda + c * PER) * ES);
+  };
+  auto b_offset = [&](const SegDev &sd, int i) -> unsigned {
+    const int k = (i * NW + wave) * B_ROWS_PER_KB + b_slot_k;
+    const int c = b_swizzle_chunk<ES>(k, b_slot_pos);
+    return (unsigned)(((int64_t)k * sd.ldb + c * PER) * ES);
   };
 
-  // issue the loads of the K step at (seg, kpos) into LDS stage `stage`
-  auto fetch = [&](int stage) {
-    const unsigned sa = lds_base + stage * STAGE + wave * 1024;
-    st_a = (gptr)sd.a + ((int64_t)it.m_off * sd.lda + kpos) * ES;
-    st_b = (gptr)sd.b + ((int64_t)kpos * sd.ldb + it.n_off) * ES;
-    st_a_left = sd.a_bytes - ((int64_t)it.m_off * sd.lda + kpos) * ES;
-    st_b_left = sd.b_bytes - ((int64_t)kpos * sd.ldb + it.n_off) * ES;
-    st_krem = sd.klen - kpos;
-    // largest offset any lane uses in this step, against the last offset that is safe to read 16 bytes at
+  // `lead` runs ahead and issues loads; `lag` follows and publishes (repairs) stages.  Both are kept
+  // as a handful of scalars that advance by additions: the per-step bookkeeping sits between two
+  // K steps, where nothing hides it, so it has to be a few instructions.
+  int lead_seg = 0, lead_kpos = 0, lead_klen = 0;        // lead cursor
+  int lag_seg = 0, lag_kpos = 0, lag_klen = 0;           // lag cursor
+  unsigned a_src[LOADS], b_src[LOADS];                   // per-lane chunk offsets for the lead segment
+  gptr ld_a = nullptr, ld_b = nullptr;                   // base addresses of the lead step
+  int64_t ld_a_left = 0, ld_b_left = 0;                  // readable bytes from those bases
+  int64_t ld_b_step = 0;                                 // bytes one K step advances in B
+  int64_t ld_a_need = 0, ld_b_need = 0;                  // bytes a step reads at most from its bases
+  unsigned ld_lo = 0, ld_hi = 0;                         // exec mask of the lead step's loads: all lanes or none
+  unsigned fix_bits = 0;                                 // bit (t & 3): step t must be repaired when published
+
+  // geometry of the K step at (sd, kpos): base addresses and the bytes readable from them
+  auto step_geometry = [&](const SegDev &sd, int kpos, gptr &pa, gptr &pb, int64_t &a_left, int64_t &b_left) {
+#ifdef DMM_EXP_SAMEK
+    kpos &= 255;
+#endif
+    pa = (gptr)sd.a + ((int64_t)it.m_off * sd.lda + kpos) * ES;
+    pb = (gptr)sd.b + ((int64_t)kpos * sd.ldb + it.n_off) * ES;
+    a_left = sd.a_bytes - ((int64_t)it.m_off * sd.lda + kpos) * ES;
+    b_left = sd.b_bytes - ((int64_t)kpos * sd.ldb + it.n_off) * ES;
+  };
+  auto open_lead = [&]() {                               // lead enters segment lead_seg at kpos 0
+    const SegDev sd = segs[it.seg_begin + lead_seg];
+    lead_klen = sd.klen;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      a_src[i] = a_offset(sd, i);
+      b_src[i] = b_offset(sd, i);
+    }
+    step_geometry(sd, 0, ld_a, ld_b, ld_a_left, ld_b_left);
+    ld_b_step = (int64_t)BK * sd.ldb * ES;
     const int rows = it.m_ext < BM ? it.m_ext : BM;
-    const int64_t a_max = ((int64_t)(rows - 1) * sd.lda + 7 * PER) * ES;
-    const int64_t b_max = ((int64_t)(BK - 1) * sd.ldb + (S::B_CHUNKS - 1) * PER) * ES;
-    const bool safe = a_max + 16 <= st_a_left && b_max + 16 <= st_b_left;
-    st_fix = !safe || st_krem < BK;
-    if (safe) {
-#pragma unroll
-      for (int i = 0; i < LOADS; ++i) load_to_lds_16(st_a, a_src[i], sa + i * (NW * 1024));
-#pragma unroll
-      for (int i = 0; i < LOADS; ++i) load_to_lds_16(st_b, b_src[i], sa + A_STAGE + i * (NW * 1024));
+    ld_a_need = ((int64_t)(rows - 1) * sd.lda + 3 * PER) * ES + 16;
+    ld_b_need = ((int64_t)(BK - 1) * sd.ldb + (S::B_CHUNKS - 1) * PER) * ES + 16;
+  };
+  auto advance_lead = [&]() {                            // to the next K step (the caller knows one exists)
+    lead_kpos += BK;
+    if (__builtin_expect(lead_kpos >= lead_klen, 0)) {
+      ++lead_seg;
+      lead_kpos = 0;
+      open_lead();
     } else {
-#pragma unroll
-      for (int i = 0; i < LOADS; ++i)
-        if ((int64_t)a_src[i] + 16 <= st_a_left) load_to_lds_16(st_a, a_src[i], sa + i * (NW * 1024));
-#pragma unroll
-      for (int i = 0; i < LOADS; ++i)
-        if ((int64_t)b_src[i] + 16 <= st_b_left) load_to_lds_16(st_b, b_src[i], sa + A_STAGE + i * (NW * 1024));
+#ifndef DMM_EXP_SAMEK
+      ld_a += BK * ES;
+      ld_b += ld_b_step;
+#endif
+      ld_a_left -= BK * ES;
+      ld_b_left -= ld_b_step;
     }
   };
+  auto advance_lag = [&]() {
+    lag_kpos += BK;
+    if (__builtin_expect(lag_kpos >= lag_klen, 0)) {
+      ++lag_seg;
+      lag_kpos = 0;
+      lag_klen = segs[it.seg_begin + lag_seg].klen;
+    }
+  };
+  // Make lead step number t ready for the load slots.  An ordinary step is loaded by the slots with
+  // all lanes; when there is no step the slots run with no lane (and move nothing); a step in
+  // which some lane would overrun a tile buffer is loaded here and now, lane-masked, and the
+  // slots again run empty.  The step goes to stage t & 3, which is free.
+  auto prepare_lead = [&](bool exists, int t) {
+    unsigned all = 0u;
+    if (exists) {
+      const bool safe = ld_a_left >= ld_a_need && ld_b_left >= ld_b_need;
+      const bool fix = !safe || lead_klen - lead_kpos < BK;
+      fix_bits = (fix_bits & ~(1u << (t & 3))) | ((fix ? 1u : 0u) << (t & 3));
+      if (__builtin_expect(safe, 1)) {
+        all = ~0u;
+      } else {
+        const unsigned sa = lds_base + (t & 3) * STAGE + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+          if ((int64_t)a_src[i] + 16 <= ld_a_left) load_to_lds_16(ld_a, a_src[i], sa + i * (NW * 1024));
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+          if ((int64_t)b_src[i] + 16 <= ld_b_left) load_to_lds_16(ld_b, b_src[i], sa + A_STAGE + i * (NW * 1024));
+      }
+    }
+#ifdef DMM_EXP_MASK0
+    all = 0u;
+#endif
+    ld_lo = ld_hi = __builtin_amdgcn_readfirstlane(all);
+  };
+  // load number j of the lead step (0 .. LOADS - 1: A, LOADS .. 2 LOADS - 1: B) into the LDS stage
+  // whose base address (plus this wave's KB offset) is `stage_base`
+  auto dma = [&](auto jc, unsigned stage_base) {
+    constexpr int j = decltype(jc)::value;
+    if constexpr (j < LOADS)
+      load_to_lds_16_masked<j * (NW * 1024)>(ld_a, a_src[j], stage_base, ld_lo, ld_hi);
+    else
+      load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, b_src[j - LOADS], stage_base, ld_lo, ld_hi);
+  };
 
-  // After this wave's loads have landed: every lane repairs its own slots of stage `stage`:
-  // chunks it was masked out of are read element by element, and everything at k >= st_krem
-  // is zeroed on both operands (so that stale or non-finite bytes cannot reach a sum).
-  auto fixup = [&](int stage) {
+  // After this wave's loads of the lag step have landed: every lane repairs its own slots of
+  // `stage`: chunks it was masked out of are read element by element, and everything at
+  // k >= remaining segment length is zeroed on both operands (so that stale or non-finite
+  // bytes cannot reach a sum).  Rare: K tails and tile-buffer ends only.
+  auto publish_fix = [&](int t) {                        // t = number of the lag step
+    if (__builtin_expect(((fix_bits >> (t & 3)) & 1u) == 0u, 1)) return;
+    const int stage = t & 3;
+    const SegDev lsd = segs[it.seg_begin + lag_seg];
+    gptr pa, pb;
+    int64_t a_left, b_left;
+    step_geometry(lsd, lag_kpos, pa, pb, a_left, b_left);
+    const int krem = lsd.klen - lag_kpos;
     char *sa = lds + stage * STAGE + wave * 1024 + lane * 16;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int row = (i * NW + wave) * 8 + a_slot_row;
-      const int c = (lane & 7) ^ a_swizzle(row);
-      int keep = st_krem - c * PER;                       // elements of the chunk inside the segment
+      const int row = (i * NW + wave) * 16 + a_slot_row;
+      const int c = a_slot_pos ^ a_swizzle(row);
+      const unsigned off = a_offset(lsd, i);
+      int keep = krem - c * PER;                          // elements of the chunk inside the segment
       keep = keep > PER ? PER : keep;
       u32x4 *slot = (u32x4 *)(sa + i * (NW * 1024));
-      const int64_t room = st_a_left - (int64_t)a_src[i];  // readable bytes at the chunk
+      const int64_t room = a_left - (int64_t)off;         // readable bytes at the chunk
       if (room < 16) {
         const int avail = (int)(room > 0 ? room / ES : 0);
-        *slot = load_partial<ES>(st_a + a_src[i], keep < avail ? keep : avail);
+        *slot = load_partial<ES>(pa + off, keep < avail ? keep : avail);
       } else if (keep <= 0) {
         *slot = u32x4{0u, 0u, 0u, 0u};
       } else if (keep < PER) {
@@ -311,146 +405,192 @@ __global__ __launch_bounds__(W::NT) void grouped_gemm_kernel(const ItemDev *__re
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int k = (i * NW + wave) * B_ROWS_PER_KB + b_slot_k;
+      const unsigned off = b_offset(lsd, i);
       u32x4 *slot = (u32x4 *)(sa + A_STAGE + i * (NW * 1024));
-      const int64_t room = st_b_left - (int64_t)b_src[i];
-      if (k >= st_krem) {
+      const int64_t room = b_left - (int64_t)off;
+      if (k >= krem) {
         *slot = u32x4{0u, 0u, 0u, 0u};
       } else if (room < 16) {
-        *slot = load_partial<ES>(st_b + b_src[i], (int)(room > 0 ? room / ES : 0));
+        *slot = load_partial<ES>(pb + off, (int)(room > 0 ? room / ES : 0));
       }
     }
   };
 
-  auto advance = [&]() {                                 // to the next K step (the caller knows one exists)
-    kpos += BK;
-    if (kpos >= sd.klen) {
-      ++seg;
-      kpos = 0;
-      open_segment();
-    }
-  };
-
-  // ---- LDS -> registers -> MFMA, software-pipelined over the KSUB sub-steps of a K step ----
-  // A K step is consumed in KSUB sub-steps (16 k for bf16, 8 k for fp32).  The fragments of
-  // sub-step q + 1 are read from LDS while the MFMAs of sub-step q run; the last sub-step's
-  // MFMAs are issued after the barrier so that they overlap the first reads of the next stage.
-  using Frags = FragSet<ES, FM, FN>;
+  // ---- LDS -> registers ----------------------------------------------------------------
+  using Frags = FragSet<ES>;
   Frags fr[2];
+  constexpr int READS = ES == 2 ? FM + 2 * FN : FM + 4 * FN;   // LDS reads per sub-step
 
-  auto load_frags = [&](int stage, int q, Frags &f) {
+  // read number r of sub-step q of `stage` into f.  bf16 order: B0 (2 reads), A0, B1, B2, B3, A1..A3,
+  // so that the operands of the next sub-step's first MFMAs arrive first.
+  auto read_op = [&](int stage, int q, int r, Frags &f) {
     const char *sa = lds + stage * STAGE;
     const char *sb = sa + A_STAGE;
     if constexpr (ES == 2) {
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int row = wm * WTM + i * 32 + (lane & 31);
-        f.a[i] = *(const bf16x8 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
-      }
-      // ds_read_b64_tr_b16: in every group of 16 lanes, lane i supplies the address of 4
-      // consecutive columns of k row i / 4 and receives column i of those 4 k rows.
-      const int g = lane >> 4, li = lane & 15;
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
+      constexpr int kind[12] = {4, 4, 0, 5, 5, 6, 6, 7, 7, 1, 2, 3};   // 0..3: A frag i; 4..7: B frag j
+      constexpr int half[12] = {0, 1, 0, 0, 1, 0, 1, 0, 1, 0, 0, 0};
+      const int what = kind[r];
+      if (what < 4) {
+        const int row = wm * WTM + what * 32 + (lane & 31);
+        f.a[what] = *(const bf16x8 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
+      } else {
+        // ds_read_b64_tr_b16: in every group of 16 lanes, lane i supplies the address of 4
+        // consecutive columns of k row i / 4 and receives column i of those 4 k rows.
+        const int j = what - 4, h = half[r];
+        const int g = lane >> 4, li = lane & 15;
         const int ncol = wn * WTN + j * 32 + (g & 1) * 16 + (li & 3) * 4;   // 4 columns, 8 bytes
-        const int k0 = q * 16 + (g >> 1) * 8 + (li >> 2);
-        short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        const int k0 = q * 16 + (g >> 1) * 8 + (li >> 2) + 4 * h;
+        f.b[j][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
             (lds_short4_ptr)(sb + b_lds_off<2>(k0, ncol >> 3) + (ncol & 7) * 2));
-        short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_short4_ptr)(sb + b_lds_off<2>(k0 + 4, ncol >> 3) + (ncol & 7) * 2));
-        union { short4_t h[2]; bf16x8 v; } u;
-        u.h[0] = lo;
-        u.h[1] = hi;
-        f.b[j] = u.v;
       }
     } else {
       // fp32: lane half h reads the float4 at k = 8 q + 4 h .. + 3 of its A row; MFMA number e
       // consumes element e, i.e. k = 8 q + 4 h + e, and the B side reads that same k row.
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int row = wm * WTM + i * 32 + (lane & 31);
-        f.a[i] = *(const float4 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      if (r < FM) {
+        const int row = wm * WTM + r * 32 + (lane & 31);
+        f.a[r] = *(const float4 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
+      } else {
+        const int e = (r - FM) / FN, j = (r - FM) % FN;
         const int k = q * 8 + (lane >> 5) * 4 + e;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int ncol = wn * WTN + j * 32 + (lane & 31);
-          f.b[e][j] = *(const float *)(sb + b_lds_off<4>(k, ncol >> 2) + (ncol & 3) * 4);
-        }
+        const int ncol = wn * WTN + j * 32 + (lane & 31);
+        f.b[e][j] = *(const float *)(sb + b_lds_off<4>(k, ncol >> 2) + (ncol & 3) * 4);
       }
     }
   };
-  auto mma = [&](const Frags &f) {
+  auto mfma_op = [&](const Frags &f, int n) {            // MFMA slot n of a sub-step: tile (n / FN, n % FN)
+    const int i = n / FN, j = n % FN;
     if constexpr (ES == 2) {
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+      union { short4_t h[2]; bf16x8 v; } u;
+      u.h[0] = f.b[j][0];
+      u.h[1] = f.b[j][1];
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], u.v, acc[i][j], 0, 0, 0);
     } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-          const float av = e == 0 ? f.a[i].x : e == 1 ? f.a[i].y : e == 2 ? f.a[i].z : f.a[i].w;
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, f.b[e][j], acc[i][j], 0, 0, 0);
-        }
-    }
-  };
-  // pin the order: one LDS read after every MFMA of the previous sub-step
-  auto interleave = [&]() {
-#ifdef DMM_NO_INTERLEAVE
-    return;
-#endif
-    if constexpr (ES == 2) {
-      constexpr int READS = FM + 2 * FN;
-#pragma unroll
-      for (int n = 0; n < FM * FN; ++n) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // 1 MFMA
-        if (n < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+      for (int e = 0; e < 4; ++e) {
+        const float av = e == 0 ? f.a[i].x : e == 1 ? f.a[i].y : e == 2 ? f.a[i].z : f.a[i].w;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, f.b[e][j], acc[i][j], 0, 0, 0);
       }
     }
+  };
+  // One sub-step: its FM FN MFMA slots; after slot n either one of this wave's loads (when
+  // slot % 4 == ROT) or the next LDS read of the following sub-step.  `first` = index of the
+  // sub-step's first slot within the K step (0 or 16).
+  auto sub_step = [&](auto first_tag, const Frags &cur, Frags &nxt, int rd_stage, int rd_q, int ld_stage) {
+    constexpr int first = decltype(first_tag)::value;
+    const unsigned ld_base = lds_base + ld_stage * STAGE + wave * 1024;
+    // (unrolled by hand over the 16 slots so that slot numbers are compile-time constants)
+    auto slot = [&](auto nc) {
+      constexpr int n = decltype(nc)::value;
+      constexpr int r = n - (n + NW - 1 - ROT) / NW;    // LDS reads issued in earlier slots of this sub-step
+      mfma_op(cur, n);
+      constexpr int g = first + n;
+      if constexpr (g % NW == ROT) {
+        dma(std::integral_constant<int, g / NW>{}, ld_base);
+      } else if (ES == 2) {
+#ifndef DMM_EXP_NOREAD
+        read_op(rd_stage, rd_q, r, nxt);
+#endif
+      }
+      if (ES == 4 && n == 0) {                           // fp32: all reads up front (64 MFMAs follow)
+#pragma unroll
+        for (int x = 0; x < READS; ++x) read_op(rd_stage, rd_q, x, nxt);
+      }
+      DMM_SCHED_BARRIER;
+    };
+    slot(std::integral_constant<int, 0>{});  slot(std::integral_constant<int, 1>{});
+    slot(std::integral_constant<int, 2>{});  slot(std::integral_constant<int, 3>{});
+    slot(std::integral_constant<int, 4>{});  slot(std::integral_constant<int, 5>{});
+    slot(std::integral_constant<int, 6>{});  slot(std::integral_constant<int, 7>{});
+    slot(std::integral_constant<int, 8>{});  slot(std::integral_constant<int, 9>{});
+    slot(std::integral_constant<int, 10>{}); slot(std::integral_constant<int, 11>{});
+    slot(std::integral_constant<int, 12>{}); slot(std::integral_constant<int, 13>{});
+    slot(std::integral_constant<int, 14>{}); slot(std::integral_constant<int, 15>{});
   };
 
-  if (it.nsteps > 0) {
-    open_segment();
-    fetch(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#ifndef DMM_NO_FIXUP
-    if (st_fix) fixup(0);
-#endif
-    __syncthreads();
-    int stage = 0;
-    load_frags(0, 0, fr[0]);
-#pragma clang loop unroll(disable)
-    for (int s = 0; s < it.nsteps; ++s) {
-      st_fix = false;
-      if (s + 1 < it.nsteps) {                 // global loads of the next step fly during the MFMAs
-        advance();
-        fetch(stage ^ 1);
-      }
-      DMM_SCHED_BARRIER;
+  // ---- the K loop ------------------------------------------------------------------------
+  // Iteration s multiplies stage s % 4 while the loads of step s + 3 are issued into stage
+  // (s + 3) % 4, which every wave finished reading before the barrier of iteration s - 1.
+  const int n = it.nsteps;
+  open_lead();
+  lag_klen = lead_klen;
+  // prologue: steps 0, 1, 2 in flight; publish step 0
+  int issued = 0;
 #pragma unroll
-      for (int q = 0; q + 1 < KSUB; ++q) {
-        load_frags(stage, q + 1, fr[(q + 1) & 1]);
-        mma(fr[q & 1]);
-        interleave();
-        DMM_SCHED_BARRIER;
-      }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#ifndef DMM_NO_FIXUP
-      if (st_fix) fixup(stage ^ 1);
-#endif
-      __syncthreads();                         // every wave has read this stage; the next one has landed
-      stage ^= 1;
-      load_frags(stage, 0, fr[0]);             // (after the last step this reads a stale stage: unused)
-      mma(fr[(KSUB - 1) & 1]);
-      interleave();
-      DMM_SCHED_BARRIER;
+  for (int t = 0; t < NSTAGE - 1; ++t) {
+    if (t < n) {
+      prepare_lead(true, t);
+      const unsigned base = lds_base + t * STAGE + wave * 1024;
+      dma(std::integral_constant<int, 0>{}, base); dma(std::integral_constant<int, 1>{}, base);
+      dma(std::integral_constant<int, 2>{}, base); dma(std::integral_constant<int, 3>{}, base);
+      dma(std::integral_constant<int, 4>{}, base); dma(std::integral_constant<int, 5>{}, base);
+      dma(std::integral_constant<int, 6>{}, base); dma(std::integral_constant<int, 7>{}, base);
+      ++issued;
+      if (t + 1 < n) advance_lead();
     }
+  }
+  if (issued >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LOADS) : "memory");
+  else if (issued == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  publish_fix(0);
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < READS; ++r) read_op(0, 0, r, fr[0]);
+  // here the lead cursor is at step min(3, n - 1), which has been issued iff n <= 3
+  bool loads_on = n > NSTAGE - 1;                        // a step s + 3 exists for s = 0
+  prepare_lead(loads_on, NSTAGE - 1);
+
+#pragma clang loop unroll(disable)
+  for (int s = 0; s < n; ++s) {
+    const int stage = s & (NSTAGE - 1);
+    const int ld_stage = (s + NSTAGE - 1) & (NSTAGE - 1);
+    sub_step(std::integral_constant<int, 0>{}, fr[0], fr[1], stage, 1, ld_stage);
+    // publish step s + 1: this wave's loads of it must have landed; steps s + 2 and (half of) s + 3
+    // may stay in flight (loads return in order)
+#ifndef DMM_EXP_NOVMWAIT
+    if (loads_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
+    else if (s + 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#else
+    if (s + 1 >= n) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+    if (s + 1 < n) {
+      advance_lag();
+      publish_fix(s + 1);
+    }
+#ifndef DMM_EXP_NOBARRIER
+    __syncthreads();                         // every wave has read stage s; step s + 1 is complete
+#endif
+    sub_step(std::integral_constant<int, FM * FN>{}, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
+    loads_on = s + NSTAGE < n;               // step (s + 1) + 3 exists
+    if (loads_on) advance_lead();
+    prepare_lead(loads_on, s + NSTAGE);      // it goes to the stage this iteration consumed
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the workgroup has gone
+}
+
+template <int ES>
+__global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restrict__ items,
+                                                          const SegDev *__restrict__ segs) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const ItemDev it = items[blockIdx.x];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  if (it.nsteps > 0) {
+    // one instantiation per wave: the four waves of the CU issue their loads in different slots
+    if (wave == 0) run_item<ES, 0>(it, segs, lds, acc);
+    else if (wave == 1) run_item<ES, 1>(it, segs, lds, acc);
+    else if (wave == 2) run_item<ES, 2>(it, segs, lds, acc);
+    else run_item<ES, 3>(it, segs, lds, acc);
   }
 
   // epilogue: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 tile
