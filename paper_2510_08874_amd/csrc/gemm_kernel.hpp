@@ -261,31 +261,39 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   const int b_slot_k = lane / S::B_CHUNKS;               // k row of this lane's slot inside a B KB
   const int b_slot_pos = lane % S::B_CHUNKS;             // chunk position inside that k row
 
-  // byte offset, from a step's base address, of the chunk this lane fetches with load i
-  auto a_offset = [&](const SegDev &sd, int i) -> unsigned {
+  // Byte offset, from a step's base address, of the chunk this lane fetches with load i:
+  // (source row) * (row pitch in bytes) + (chunk inside the row) * 16.  The row and the chunk
+  // depend on the item only; the pitch is a scalar of the segment.  So a segment switch touches
+  // scalars only, and a load slot rebuilds its offset with one 24-bit multiply-add (pitches are
+  // below 2^24 bytes: the host rejects larger leading dimensions).
+  unsigned a_srow[LOADS], a_c16[LOADS], b_srow[LOADS], b_c16[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
     const int row = (i * NW + wave) * 16 + a_slot_row;
-    const int src_row = row < it.m_ext ? row : it.m_ext - 1;
-    const int c = a_slot_pos ^ a_swizzle(row);
-    return (unsigned)(((int64_t)src_row * sd.lda + c * PER) * ES);
-  };
-  auto b_offset = [&](const SegDev &sd, int i) -> unsigned {
+    a_srow[i] = (unsigned)(row < it.m_ext ? row : it.m_ext - 1);
+    a_c16[i] = (unsigned)((a_slot_pos ^ a_swizzle(row)) << 4);
     const int k = (i * NW + wave) * B_ROWS_PER_KB + b_slot_k;
-    const int c = b_swizzle_chunk<ES>(k, b_slot_pos);
-    return (unsigned)(((int64_t)k * sd.ldb + c * PER) * ES);
-  };
+    b_srow[i] = (unsigned)k;
+    b_c16[i] = (unsigned)(b_swizzle_chunk<ES>(k, b_slot_pos) << 4);
+  }
+  auto a_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(a_srow[i], pitch) + a_c16[i]; };
+  auto b_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(b_srow[i], pitch) + b_c16[i]; };
 
   // `lead` runs ahead and issues loads; `lag` follows and publishes (repairs) stages.  Both are kept
   // as a handful of scalars that advance by additions: the per-step bookkeeping sits between two
   // K steps, where nothing hides it, so it has to be a few instructions.
-  int lead_seg = 0, lead_kpos = 0, lead_klen = 0;        // lead cursor
+  int lead_seg = 0, lead_kpos = 0;                       // lead cursor
+  int lead_left = 0;                                     // steps left in its segment, the current one included
+  bool lead_tail = false;                                // the segment's last step is a K tail
+  bool lead_seg_safe = true;                             // no step of the segment can overrun a tile buffer
   int lag_seg = 0, lag_kpos = 0, lag_klen = 0;           // lag cursor
-  unsigned a_src[LOADS], b_src[LOADS];                   // per-lane chunk offsets for the lead segment
+  unsigned ld_a_pitch = 0, ld_b_pitch = 0;               // row pitch in bytes of the lead segment's A and B tiles
   gptr ld_a = nullptr, ld_b = nullptr;                   // base addresses of the lead step
-  int64_t ld_a_left = 0, ld_b_left = 0;                  // readable bytes from those bases
   int64_t ld_b_step = 0;                                 // bytes one K step advances in B
-  int64_t ld_a_need = 0, ld_b_need = 0;                  // bytes a step reads at most from its bases
   unsigned ld_lo = 0, ld_hi = 0;                         // exec mask of the lead step's loads: all lanes or none
-  unsigned fix_bits = 0;                                 // bit (t & 3): step t must be repaired when published
+  // Repair flags as a shift register: every prepared step pushes one bit; the step that is
+  // published in an iteration is the one pushed three pushes earlier (bit 2).
+  unsigned fix_bits = 0;
 
   // geometry of the K step at (sd, kpos): base addresses and the bytes readable from them
   auto step_geometry = [&](const SegDev &sd, int kpos, gptr &pa, gptr &pb, int64_t &a_left, int64_t &b_left) {
@@ -297,33 +305,37 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     a_left = sd.a_bytes - ((int64_t)it.m_off * sd.lda + kpos) * ES;
     b_left = sd.b_bytes - ((int64_t)kpos * sd.ldb + it.n_off) * ES;
   };
+  // bytes a step reads at most from its base addresses
+  auto step_need = [&](const SegDev &sd, int64_t &a_need, int64_t &b_need) {
+    const int rows = it.m_ext < BM ? it.m_ext : BM;
+    a_need = ((int64_t)(rows - 1) * sd.lda + 3 * PER) * ES + 16;
+    b_need = ((int64_t)(BK - 1) * sd.ldb + (S::B_CHUNKS - 1) * PER) * ES + 16;
+  };
   auto open_lead = [&]() {                               // lead enters segment lead_seg at kpos 0
     const SegDev sd = segs[it.seg_begin + lead_seg];
-    lead_klen = sd.klen;
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      a_src[i] = a_offset(sd, i);
-      b_src[i] = b_offset(sd, i);
-    }
-    step_geometry(sd, 0, ld_a, ld_b, ld_a_left, ld_b_left);
+    lead_kpos = 0;
+    lead_left = (sd.klen + BK - 1) / BK;
+    lead_tail = sd.klen % BK != 0;
+    ld_a_pitch = (unsigned)(sd.lda * ES);
+    ld_b_pitch = (unsigned)(sd.ldb * ES);
     ld_b_step = (int64_t)BK * sd.ldb * ES;
-    const int rows = it.m_ext < BM ? it.m_ext : BM;
-    ld_a_need = ((int64_t)(rows - 1) * sd.lda + 3 * PER) * ES + 16;
-    ld_b_need = ((int64_t)(BK - 1) * sd.ldb + (S::B_CHUNKS - 1) * PER) * ES + 16;
+    int64_t a_left, b_left, a_need, b_need;
+    step_geometry(sd, 0, ld_a, ld_b, a_left, b_left);
+    step_need(sd, a_need, b_need);
+    // the last step of the segment reads furthest: if it is safe, all are
+    lead_seg_safe = a_left - (int64_t)(lead_left - 1) * (BK * ES) >= a_need &&
+                    b_left - (int64_t)(lead_left - 1) * ld_b_step >= b_need;
   };
   auto advance_lead = [&]() {                            // to the next K step (the caller knows one exists)
-    lead_kpos += BK;
-    if (__builtin_expect(lead_kpos >= lead_klen, 0)) {
+    if (__builtin_expect(--lead_left == 0, 0)) {
       ++lead_seg;
-      lead_kpos = 0;
       open_lead();
     } else {
+      lead_kpos += BK;
 #ifndef DMM_EXP_SAMEK
       ld_a += BK * ES;
       ld_b += ld_b_step;
 #endif
-      ld_a_left -= BK * ES;
-      ld_b_left -= ld_b_step;
     }
   };
   auto advance_lag = [&]() {
@@ -334,31 +346,43 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       lag_klen = segs[it.seg_begin + lag_seg].klen;
     }
   };
-  // Make lead step number t ready for the load slots.  An ordinary step is loaded by the slots with
-  // all lanes; when there is no step the slots run with no lane (and move nothing); a step in
-  // which some lane would overrun a tile buffer is loaded here and now, lane-masked, and the
-  // slots again run empty.  The step goes to stage t & 3, which is free.
-  auto prepare_lead = [&](bool exists, int t) {
+  // Make the lead step ready for the load slots and push its repair flag.  An ordinary step is
+  // loaded by the slots with all lanes; when there is no step the slots run with no lane (and
+  // move nothing); a step in which some lane would overrun a tile buffer is loaded here and
+  // now, lane-masked, and the slots again run empty.  `stage` is the free stage the step goes to.
+  auto prepare_lead = [&](bool exists, int stage) {
     unsigned all = 0u;
+    unsigned fix = 0u;
     if (exists) {
-      const bool safe = ld_a_left >= ld_a_need && ld_b_left >= ld_b_need;
-      const bool fix = !safe || lead_klen - lead_kpos < BK;
-      fix_bits = (fix_bits & ~(1u << (t & 3))) | ((fix ? 1u : 0u) << (t & 3));
-      if (__builtin_expect(safe, 1)) {
-        all = ~0u;
-      } else {
-        const unsigned sa = lds_base + (t & 3) * STAGE + wave * 1024;
+      fix = lead_tail && lead_left == 1 ? 1u : 0u;
+      all = ~0u;
+      if (__builtin_expect(!lead_seg_safe, 0)) {
+        const SegDev sd = segs[it.seg_begin + lead_seg];
+        gptr pa, pb;
+        int64_t a_left, b_left, a_need, b_need;
+        step_geometry(sd, lead_kpos, pa, pb, a_left, b_left);
+        step_need(sd, a_need, b_need);
+        if (!(a_left >= a_need && b_left >= b_need)) {
+          all = 0u;
+          fix = 1u;
+          const unsigned sa = lds_base + stage * STAGE + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-          if ((int64_t)a_src[i] + 16 <= ld_a_left) load_to_lds_16(ld_a, a_src[i], sa + i * (NW * 1024));
+          for (int i = 0; i < LOADS; ++i) {
+            const unsigned off = a_offset(ld_a_pitch, i);
+            if ((int64_t)off + 16 <= a_left) load_to_lds_16(ld_a, off, sa + i * (NW * 1024));
+          }
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-          if ((int64_t)b_src[i] + 16 <= ld_b_left) load_to_lds_16(ld_b, b_src[i], sa + A_STAGE + i * (NW * 1024));
+          for (int i = 0; i < LOADS; ++i) {
+            const unsigned off = b_offset(ld_b_pitch, i);
+            if ((int64_t)off + 16 <= b_left) load_to_lds_16(ld_b, off, sa + A_STAGE + i * (NW * 1024));
+          }
+        }
       }
     }
 #ifdef DMM_EXP_MASK0
     all = 0u;
 #endif
+    fix_bits = (fix_bits << 1) | fix;
     ld_lo = ld_hi = __builtin_amdgcn_readfirstlane(all);
   };
   // load number j of the lead step (0 .. LOADS - 1: A, LOADS .. 2 LOADS - 1: B) into the LDS stage
@@ -366,9 +390,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   auto dma = [&](auto jc, unsigned stage_base) {
     constexpr int j = decltype(jc)::value;
     if constexpr (j < LOADS)
-      load_to_lds_16_masked<j * (NW * 1024)>(ld_a, a_src[j], stage_base, ld_lo, ld_hi);
+      load_to_lds_16_masked<j * (NW * 1024)>(ld_a, a_offset(ld_a_pitch, j), stage_base, ld_lo, ld_hi);
     else
-      load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, b_src[j - LOADS], stage_base, ld_lo, ld_hi);
+      load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, b_offset(ld_b_pitch, j - LOADS), stage_base,
+                                                                 ld_lo, ld_hi);
   };
 
   // After this wave's loads of the lag step have landed: every lane repairs its own slots of
@@ -376,7 +401,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // k >= remaining segment length is zeroed on both operands (so that stale or non-finite
   // bytes cannot reach a sum).  Rare: K tails and tile-buffer ends only.
   auto publish_fix = [&](int t) {                        // t = number of the lag step
-    if (__builtin_expect(((fix_bits >> (t & 3)) & 1u) == 0u, 1)) return;
+    if (__builtin_expect((fix_bits & 4u) == 0u, 1)) return;
     const int stage = t & 3;
     const SegDev lsd = segs[it.seg_begin + lag_seg];
     gptr pa, pb;
@@ -388,7 +413,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     for (int i = 0; i < LOADS; ++i) {
       const int row = (i * NW + wave) * 16 + a_slot_row;
       const int c = a_slot_pos ^ a_swizzle(row);
-      const unsigned off = a_offset(lsd, i);
+      const unsigned off = a_offset((unsigned)(lsd.lda * ES), i);
       int keep = krem - c * PER;                          // elements of the chunk inside the segment
       keep = keep > PER ? PER : keep;
       u32x4 *slot = (u32x4 *)(sa + i * (NW * 1024));
@@ -405,7 +430,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int k = (i * NW + wave) * B_ROWS_PER_KB + b_slot_k;
-      const unsigned off = b_offset(lsd, i);
+      const unsigned off = b_offset((unsigned)(lsd.ldb * ES), i);
       u32x4 *slot = (u32x4 *)(sa + A_STAGE + i * (NW * 1024));
       const int64_t room = b_left - (int64_t)off;
       if (k >= krem) {
@@ -512,7 +537,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // (s + 3) % 4, which every wave finished reading before the barrier of iteration s - 1.
   const int n = it.nsteps;
   open_lead();
-  lag_klen = lead_klen;
+  lag_klen = segs[it.seg_begin].klen;
   // prologue: steps 0, 1, 2 in flight; publish step 0
   int issued = 0;
 #pragma unroll
@@ -526,6 +551,8 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       dma(std::integral_constant<int, 6>{}, base); dma(std::integral_constant<int, 7>{}, base);
       ++issued;
       if (t + 1 < n) advance_lead();
+    } else {
+      fix_bits <<= 1;                                    // keep the register in step: no such step, no repair
     }
   }
   if (issued >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LOADS) : "memory");
@@ -563,7 +590,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     sub_step(std::integral_constant<int, FM * FN>{}, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
     loads_on = s + NSTAGE < n;               // step (s + 1) + 3 exists
     if (loads_on) advance_lead();
-    prepare_lead(loads_on, s + NSTAGE);      // it goes to the stage this iteration consumed
+    prepare_lead(loads_on, stage);           // it goes to the stage this iteration consumed
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the workgroup has gone
 }
