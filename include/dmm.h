@@ -41,8 +41,8 @@ typedef enum {
                       or the process grid needs more ranks than one replica has */
   DMM_ENOMEM = -4, /* host or device allocation failed */
   DMM_EHIP = -5,   /* a HIP call failed; dmm_last_hip_error() holds its code */
-  DMM_ELD = -6     /* a leading dimension is smaller than the tile's width, or so large that 256 rows
-                      of an A tile (64 rows of a B tile) span 4 GiB or more */
+  DMM_ELD = -6     /* a leading dimension is smaller than the tile's width, or a row pitch (leading
+                      dimension times element size) of an A, B or C tile is 2^24 bytes or more */
 } dmm_status;
 
 /* Element type of the A and B tiles.  C tiles and all partial sums are fp32. */

@@ -363,11 +363,15 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   if ((rc = check_lds(P->A, a_ld)) || (rc = check_lds(P->B, b_ld)) || (rc = check_lds(P->C, c_ld))) return rc;
   const int64_t es = dtype == DMM_BF16 ? 2 : 4;
   const int64_t bk = dtype == DMM_BF16 ? Shape<2>::BK : Shape<4>::BK;
-  // the kernel addresses a macro-tile's rows with 32-bit byte offsets from the step's base
+  // the kernel addresses a macro-tile's rows with 32-bit byte offsets, built as a 24-bit
+  // multiply of (row, pitch): every row pitch has to stay below 2^24 bytes
+  constexpr int64_t MAX_PITCH = (int64_t)1 << 24;
   for (int64_t i = 0; i < P->A.c * P->A.tiles_per_rep(); ++i)
-    if (a_ld[i] * es * BM >= (int64_t)1 << 32) return DMM_ELD;
+    if (a_ld[i] * es >= MAX_PITCH) return DMM_ELD;
   for (int64_t i = 0; i < P->B.c * P->B.tiles_per_rep(); ++i)
-    if (b_ld[i] * es * 64 >= (int64_t)1 << 32) return DMM_ELD;
+    if (b_ld[i] * es >= MAX_PITCH) return DMM_ELD;
+  for (int64_t i = 0; i < P->C.c * P->C.tiles_per_rep(); ++i)
+    if (c_ld[i] * 4 >= MAX_PITCH) return DMM_ELD;
   hipStream_t stream = (hipStream_t)hip_stream;
   try {
     if ((rc = ensure_state(P))) return rc;

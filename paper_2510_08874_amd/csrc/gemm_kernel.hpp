@@ -58,6 +58,16 @@
 
 namespace dmm {
 
+#ifdef DMM_EXP_TRACE
+__device__ unsigned long long dmm_trace[4096 * 8];
+#define DMM_TRACE(slot)                                                                      \
+  do {                                                                                       \
+    if (threadIdx.x == 0) dmm_trace[blockIdx.x * 8 + (slot)] = __builtin_amdgcn_s_memtime(); \
+  } while (0)
+#else
+#define DMM_TRACE(slot)
+#endif
+
 struct SegDev {          // one K-segment of a group; pointers at the group's (m0, k0) / (k0, n0)
   const char *a;
   const char *b;
@@ -566,6 +576,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   bool loads_on = n > NSTAGE - 1;                        // a step s + 3 exists for s = 0
   prepare_lead(loads_on, NSTAGE - 1);
 
+  DMM_TRACE(1);
 #pragma clang loop unroll(disable)
   for (int s = 0; s < n; ++s) {
     const int stage = s & (NSTAGE - 1);
@@ -593,6 +604,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     prepare_lead(loads_on, stage);           // it goes to the stage this iteration consumed
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the workgroup has gone
+  DMM_TRACE(2);
 }
 
 template <int ES>
@@ -604,6 +616,17 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
+  DMM_TRACE(0);
+#ifdef DMM_EXP_TRACE
+  if (threadIdx.x == 0)
+    dmm_trace[blockIdx.x * 8 + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |
+                                    __builtin_amdgcn_s_getreg((31 << 11) | 4);
+#endif
+#ifdef DMM_EXP_STAGGER
+  if (blockIdx.x < 256) {
+    for (int g = ((blockIdx.x >> 3) % DMM_EXP_STAGGER) * DMM_EXP_STAG_UNIT; g > 0; --g) __builtin_amdgcn_s_sleep(127);
+  }
+#endif
   floatx16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -620,21 +643,38 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
     else run_item<ES, 3>(it, segs, lds, acc);
   }
 
-  // epilogue: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 tile
-  gfloat_ptr cbase = (gfloat_ptr)it.c;
+  DMM_TRACE(3);
+  // epilogue: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 tile.
+  // Addresses are the item's base plus a 32-bit byte offset (the host rejects C pitches of 2^24
+  // bytes and more): one add per row, the four column blocks of a row through the immediate offset.
+  // A full 256 x 256 item stores without predicates.
+  const __attribute__((address_space(1))) char *cbytes = (const __attribute__((address_space(1))) char *)it.c;
+  const unsigned pitch = (unsigned)it.ldc * 4u;
+  const int row0 = wm * WTM + 4 * (lane >> 5);
+  const int col0 = wn * WTN + (lane & 31);
+  const unsigned voff = (unsigned)row0 * pitch + (unsigned)col0 * 4u;
+  auto store_all = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int col = wn * WTN + j * 32 + (lane & 31);
-      if (col < it.n_ext) {
+      for (int r = 0; r < 16; ++r) {
+        const int dr = i * 32 + 8 * (r >> 2) + (r & 3);
+        const unsigned o = voff + (unsigned)dr * pitch;
+        if (FULL || row0 + dr < it.m_ext) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (row < it.m_ext) cbase[(int64_t)row * it.ldc + col] = acc[i][j][r];
+          for (int j = 0; j < FN; ++j)
+            if (FULL || col0 + j * 32 < it.n_ext) *(gfloat_ptr)(cbytes + o + j * 128) = acc[i][j][r];
         }
       }
-    }
+  };
+  if (it.m_ext == BM && it.n_ext == BN) store_all(std::true_type{});
+  else store_all(std::false_type{});
+  DMM_TRACE(4);
+#ifdef DMM_EXP_TRACE
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  DMM_TRACE(5);
+#endif
 }
 
 }  // namespace dmm

@@ -271,6 +271,13 @@ def test_execute_rejects_bad_arguments():
         prob.plan.execute(binding.DMM_F32, prob.A.tensors, bad_ld, prob.B.tensors, prob.B.ld,
                           prob.C.tensors, prob.C.ld)
     assert e.value.kind == "ELD"
+    # row pitches of 2^24 bytes and more are refused on the host, for every operand, before any launch
+    for which in range(3):
+        lds = [list(prob.A.ld), list(prob.B.ld), list(prob.C.ld)]
+        lds[which][0] = (1 << 24) // 4
+        with pytest.raises(binding.DmmError) as e:
+            prob.plan.execute(binding.DMM_F32, prob.A.tensors, lds[0], prob.B.tensors, lds[1], prob.C.tensors, lds[2])
+        assert e.value.kind == "ELD"
     with pytest.raises(binding.DmmError) as e:
         prob.plan.execute(binding.DMM_F32, [None] * len(prob.A.tensors), prob.A.ld, prob.B.tensors, prob.B.ld,
                           prob.C.tensors, prob.C.ld)
