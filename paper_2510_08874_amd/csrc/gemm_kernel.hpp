@@ -289,16 +289,19 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   auto a_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(a_srow[i], pitch) + a_c16[i]; };
   auto b_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(b_srow[i], pitch) + b_c16[i]; };
 
-  // `lead` runs ahead and issues loads; `lag` follows and publishes (repairs) stages.  Both are kept
-  // as a handful of scalars that advance by additions: the per-step bookkeeping sits between two
-  // K steps, where nothing hides it, so it has to be a few instructions.
+  // `lead` is the K step whose loads are being issued (three steps ahead of the one being
+  // multiplied).  Whatever is done between two K steps is exposed (nothing hides it), so the loop
+  // has a quiet mode: while the lead stays inside a segment, away from its K tail and from the
+  // end of the tile buffers, and no stage waits for a repair, an iteration only bumps two
+  // addresses and a counter.  Everything else (segment switches, tails, buffer ends, the drain
+  // at the end of the item) goes through the general bookkeeping below, a few times per segment.
   int lead_seg = 0, lead_kpos = 0;                       // lead cursor
   int lead_left = 0;                                     // steps left in its segment, the current one included
   bool lead_tail = false;                                // the segment's last step is a K tail
   bool lead_seg_safe = true;                             // no step of the segment can overrun a tile buffer
-  int lag_seg = 0, lag_kpos = 0, lag_klen = 0;           // lag cursor
   unsigned ld_a_pitch = 0, ld_b_pitch = 0;               // row pitch in bytes of the lead segment's A and B tiles
   gptr ld_a = nullptr, ld_b = nullptr;                   // base addresses of the lead step
+  gptr ld_a_next = nullptr, ld_b_next = nullptr;         // ... and of the step after it, if in the same segment
   int64_t ld_b_step = 0;                                 // bytes one K step advances in B
   unsigned ld_lo = 0, ld_hi = 0;                         // exec mask of the lead step's loads: all lanes or none
   // Repair flags as a shift register: every prepared step pushes one bit; the step that is
@@ -307,9 +310,6 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
 
   // geometry of the K step at (sd, kpos): base addresses and the bytes readable from them
   auto step_geometry = [&](const SegDev &sd, int kpos, gptr &pa, gptr &pb, int64_t &a_left, int64_t &b_left) {
-#ifdef DMM_EXP_SAMEK
-    kpos &= 255;
-#endif
     pa = (gptr)sd.a + ((int64_t)it.m_off * sd.lda + kpos) * ES;
     pb = (gptr)sd.b + ((int64_t)kpos * sd.ldb + it.n_off) * ES;
     a_left = sd.a_bytes - ((int64_t)it.m_off * sd.lda + kpos) * ES;
@@ -342,18 +342,8 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       open_lead();
     } else {
       lead_kpos += BK;
-#ifndef DMM_EXP_SAMEK
       ld_a += BK * ES;
       ld_b += ld_b_step;
-#endif
-    }
-  };
-  auto advance_lag = [&]() {
-    lag_kpos += BK;
-    if (__builtin_expect(lag_kpos >= lag_klen, 0)) {
-      ++lag_seg;
-      lag_kpos = 0;
-      lag_klen = segs[it.seg_begin + lag_seg].klen;
     }
   };
   // Make the lead step ready for the load slots and push its repair flag.  An ordinary step is
@@ -389,9 +379,6 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
         }
       }
     }
-#ifdef DMM_EXP_MASK0
-    all = 0u;
-#endif
     fix_bits = (fix_bits << 1) | fix;
     ld_lo = ld_hi = __builtin_amdgcn_readfirstlane(all);
   };
@@ -410,10 +397,19 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // `stage`: chunks it was masked out of are read element by element, and everything at
   // k >= remaining segment length is zeroed on both operands (so that stale or non-finite
   // bytes cannot reach a sum).  Rare: K tails and tile-buffer ends only.
-  auto publish_fix = [&](int t) {                        // t = number of the lag step
+  auto publish_fix = [&](int t) {                        // t = number of the step being published
     if (__builtin_expect((fix_bits & 4u) == 0u, 1)) return;
     const int stage = t & 3;
-    const SegDev lsd = segs[it.seg_begin + lag_seg];
+    // find the step's segment and position (t < nsteps = the sum of the segments' step counts)
+    int seg = 0, first = 0;
+    for (;;) {
+      const int cnt = (segs[it.seg_begin + seg].klen + BK - 1) / BK;
+      if (t < first + cnt) break;
+      first += cnt;
+      ++seg;
+    }
+    const SegDev lsd = segs[it.seg_begin + seg];
+    const int lag_kpos = (t - first) * BK;
     gptr pa, pb;
     int64_t a_left, b_left;
     step_geometry(lsd, lag_kpos, pa, pb, a_left, b_left);
@@ -492,18 +488,24 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       }
     }
   };
+  // The MFMAs are issued as volatile assembly with a memory clobber: that pins every one of them
+  // between the LDS read (or load slot) before it and the one after it, exactly as written here.
+  // (As a plain builtin the instruction selector is free to sink sixteen of them behind all the
+  // reads and loads of the sub-step, which then execute with nothing to hide them.)  The compiler
+  // still sees the register operands and waits for the LDS reads that produce them; what it can
+  // no longer see is the result hazard of the matrix pipe, covered after the loop.
   auto mfma_op = [&](const Frags &f, int n) {            // MFMA slot n of a sub-step: tile (n / FN, n % FN)
     const int i = n / FN, j = n % FN;
     if constexpr (ES == 2) {
       union { short4_t h[2]; bf16x8 v; } u;
       u.h[0] = f.b[j][0];
       u.h[1] = f.b[j][1];
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], u.v, acc[i][j], 0, 0, 0);
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(f.a[i]), "v"(u.v) : "memory");
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float av = e == 0 ? f.a[i].x : e == 1 ? f.a[i].y : e == 2 ? f.a[i].z : f.a[i].w;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, f.b[e][j], acc[i][j], 0, 0, 0);
+        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(av), "v"(f.b[e][j]) : "memory");
       }
     }
   };
@@ -519,6 +521,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       constexpr int r = n - (n + NW - 1 - ROT) / NW;    // LDS reads issued in earlier slots of this sub-step
       mfma_op(cur, n);
       constexpr int g = first + n;
+      if constexpr (g == NW + ((ROT + 1) % NW)) {          // a slot without a load: addresses of the next step
+        ld_a_next = ld_a + BK * ES;
+        ld_b_next = ld_b + ld_b_step;
+      }
       if constexpr (g % NW == ROT) {
         dma(std::integral_constant<int, g / NW>{}, ld_base);
       } else if (ES == 2) {
@@ -547,7 +553,6 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // (s + 3) % 4, which every wave finished reading before the barrier of iteration s - 1.
   const int n = it.nsteps;
   open_lead();
-  lag_klen = segs[it.seg_begin].klen;
   // prologue: steps 0, 1, 2 in flight; publish step 0
   int issued = 0;
 #pragma unroll
@@ -575,6 +580,25 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // here the lead cursor is at step min(3, n - 1), which has been issued iff n <= 3
   bool loads_on = n > NSTAGE - 1;                        // a step s + 3 exists for s = 0
   prepare_lead(loads_on, NSTAGE - 1);
+  int quiet = 0;                                         // iterations whose end is a plain advance of the lead
+  bool mid_plain = false;                                // the coming publication needs no repair and loads go on
+  // After the lead step number `lead_idx` has been prepared by the general path: how many plain
+  // advances follow it.  Their effect on the cursor is booked here, in advance.
+  auto plan_quiet = [&](int lead_idx) {
+    quiet = 0;
+    mid_plain = loads_on && (fix_bits & 4u) == 0u;
+    if (loads_on && lead_seg_safe && (fix_bits & 7u) == 0u) {
+      int q = lead_left - 1 - (lead_tail ? 1 : 0);       // inside the segment, short of its K tail
+      const int r = n - 1 - lead_idx;                    // inside the item
+      q = q < r ? q : r;
+      if (q > 0) {
+        quiet = q;
+        lead_left -= q;
+        lead_kpos += q * BK;
+      }
+    }
+  };
+  plan_quiet(NSTAGE - 1);
 
   DMM_TRACE(1);
 #pragma clang loop unroll(disable)
@@ -584,26 +608,32 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     sub_step(std::integral_constant<int, 0>{}, fr[0], fr[1], stage, 1, ld_stage);
     // publish step s + 1: this wave's loads of it must have landed; steps s + 2 and (half of) s + 3
     // may stay in flight (loads return in order)
-#ifndef DMM_EXP_NOVMWAIT
-    if (loads_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
-    else if (s + 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#else
-    if (s + 1 >= n) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
-    if (s + 1 < n) {
-      advance_lag();
-      publish_fix(s + 1);
+    if (__builtin_expect(mid_plain, 1)) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
+    } else {
+      if (loads_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
+      else if (s + 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (s + 1 < n) publish_fix(s + 1);
     }
 #ifndef DMM_EXP_NOBARRIER
     __syncthreads();                         // every wave has read stage s; step s + 1 is complete
 #endif
     sub_step(std::integral_constant<int, FM * FN>{}, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
-    loads_on = s + NSTAGE < n;               // step (s + 1) + 3 exists
-    if (loads_on) advance_lead();
-    prepare_lead(loads_on, stage);           // it goes to the stage this iteration consumed
+    if (__builtin_expect(quiet > 0, 1)) {
+      --quiet;
+      ld_a = ld_a_next;
+      ld_b = ld_b_next;
+    } else {
+      loads_on = s + NSTAGE < n;             // step (s + 1) + 3 exists
+      if (loads_on) advance_lead();
+      prepare_lead(loads_on, stage);         // it goes to the stage this iteration consumed
+      plan_quiet(s + NSTAGE);
+    }
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the workgroup has gone
+  // nothing may land in LDS after the workgroup has gone; and the last MFMA results must have left
+  // the matrix pipe before other instructions read the accumulators (18 wait states and more)
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 7" ::: "memory");
   DMM_TRACE(2);
 }
 
