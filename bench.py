@@ -17,7 +17,14 @@ The line also carries
   roofline_replica_sum   the replica-sum kernel against peak HBM bandwidth:
                 (c + 1) * 4 bytes per C element / its average duration;
   cpu_baseline  the CPU oracle (fp64 triple loop, as it stands) timed on the
-                host cores on a bounded sample of rows of the same product.
+                host cores on a bounded sample of rows of the same product;
+  context       (bf16 workloads) what the vendor library reaches on this very box
+                for one dense M x K x N product of the same operands' distribution
+                (torch.matmul, bf16 output) and for the same product of zeros.  The
+                chip lowers its clock under matrix load, and by how much depends on
+                the data, so the published peak is not reachable with random
+                operands; these two numbers say how far it is on the day.  Context
+                only: nothing of the product path runs through the vendor library.
 """
 from __future__ import annotations
 
@@ -43,6 +50,7 @@ def main() -> int:
     ap.add_argument("--ld-multiple", type=int, default=1, help="pad leading dimensions to this many elements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
+    ap.add_argument("--no-context", action="store_true", help="skip the vendor-library GEMM timing")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -78,13 +86,19 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    host_s = [0.0, 0.0]       # host seconds spent issuing (plan + execute), and waiting for the step before
+
     def step(prev):
+        h0 = time.perf_counter()
         plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])      # slicing + grouping (host)
         plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING, stream)  # upload + GEMM + replica sum
+        h1 = time.perf_counter()
         times = None
         if prev is not None:
             times = prev.elapsed_ms()
             prev.destroy()
+        host_s[0] += h1 - h0
+        host_s[1] += time.perf_counter() - h1
         return plan, times
 
     prev = None
@@ -92,6 +106,7 @@ def main() -> int:
         prev, _ = step(prev)
     torch.cuda.synchronize()
     gemm_ms, red_ms = [], []
+    host_s[0] = host_s[1] = 0.0
     t0 = time.perf_counter()
     for i in range(args.steps):
         prev, times = step(prev)       # `times` belong to the previous step's plan
@@ -132,7 +147,9 @@ def main() -> int:
         "config": {"workload": f"{cfg['name']}: M={cfg['M']} K={cfg['K']} N={cfg['N']} {cfg['dtype']}, {cfg['what']}",
                    "virtual_ranks": cfg["nranks"], "tasks": prob.plan.num_tasks(), "groups": prob.plan.num_groups(),
                    "work_items": prob.plan.num_items(), "ld_multiple": args.ld_multiple,
-                   "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "plan_host_us": round(plan_us, 1)},
+                   "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "plan_host_us": round(plan_us, 1),
+                   "host_issue_us_per_step": round(host_s[0] / args.steps * 1e6, 1),
+                   "host_wait_us_per_step": round(host_s[1] / args.steps * 1e6, 1)},
         "pct_of_mfma_peak": round(100.0 * value / peak, 2),
         "roofline": {"kernel": "grouped_gemm_kernel", "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
@@ -170,6 +187,26 @@ def main() -> int:
                                          f"(all {cfg['N']} columns, K={cfg['K']}), {tc:.1f} s",
                                "seconds": round(tc, 2)}
     prob.close()
+
+    if not args.no_context and cfg["dtype"] == "bf16":
+        def vendor(kind):
+            mk = torch.randn if kind == "normal" else torch.zeros
+            a = mk(cfg["M"], cfg["K"], device="cuda", dtype=torch.bfloat16)
+            b = mk(cfg["K"], cfg["N"], device="cuda", dtype=torch.bfloat16)
+            for _ in range(3):
+                c = a @ b
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                c = a @ b
+            e1.record()
+            torch.cuda.synchronize()
+            del a, b, c
+            return round(fl / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12, 1)
+        out["context"] = {"vendor_matmul_bf16_out_normal_data_tflops": vendor("normal"),
+                          "vendor_matmul_bf16_out_zero_data_tflops": vendor("zeros"),
+                          "note": "one dense product of the same M, K, N through torch.matmul on this box; not part of the path"}
     print(json.dumps(out), flush=True)
     return 0
 

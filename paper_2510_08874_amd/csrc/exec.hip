@@ -269,9 +269,19 @@ int check_lds(const Grid &G, const int64_t *ld) {
   return DMM_OK;
 }
 
-int launch_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, hipStream_t stream,
-                  bool timed) {
+// The replica sum in two halves, so that dmm_execute can put the table upload in front of the
+// GEMM launch and nothing but the launch itself behind it.
+struct RedLaunch {
+  size_t n_items = 0;
+  size_t o_items = 0, o_tiles = 0, o_parts = 0, o_lds = 0;
+  int nparts = 0;
+  bool vec_ok = true;
+};
+
+int stage_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, hipStream_t stream,
+                 RedLaunch *L) {
   const Grid &C = P->C;
+  L->n_items = 0;
   if (C.c <= 1) return DMM_OK;
   const int nparts = C.c;
   std::vector<RedTile> tiles;
@@ -328,12 +338,28 @@ int launch_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int3
   std::memcpy(h.data() + o_lds, part_ld.data(), part_ld.size() * sizeof(int64_t));
   int rc = P->dev->red_table.upload(h.data(), total, stream);
   if (rc) return rc;
+  L->n_items = items.size();
+  L->o_items = o_items;
+  L->o_tiles = o_tiles;
+  L->o_parts = o_parts;
+  L->o_lds = o_lds;
+  L->nparts = nparts;
+  L->vec_ok = vec_ok;
+  return DMM_OK;
+}
+
+int fire_reduce(dmm_plan_t *P, const RedLaunch &L, hipStream_t stream, bool timed) {
+  if (L.n_items == 0) return DMM_OK;
+  int rc;
   char *d = P->dev->red_table.dev();
+  const size_t o_items = L.o_items, o_tiles = L.o_tiles, o_parts = L.o_parts, o_lds = L.o_lds;
+  const int nparts = L.nparts;
+  const bool vec_ok = L.vec_ok;
   if (timed) {
     if ((rc = timing_events(P->dev->t_red))) return rc;
     DMM_HIP(hipEventRecord(P->dev->t_red[0], stream));
   }
-  hipLaunchKernelGGL(reduce_replicas_kernel, dim3((unsigned)items.size()), dim3(RED_NT), 0, stream,
+  hipLaunchKernelGGL(reduce_replicas_kernel, dim3((unsigned)L.n_items), dim3(RED_NT), 0, stream,
                      (const RedItem *)(d + o_items), (const RedTile *)(d + o_tiles),
                      (const float *const *)(d + o_parts), (const int64_t *)(d + o_lds), nparts, vec_ok ? 1 : 0);
   DMM_HIP(hipGetLastError());
@@ -375,6 +401,9 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   hipStream_t stream = (hipStream_t)hip_stream;
   try {
     if ((rc = ensure_state(P))) return rc;
+    // both work tables go up first, so that the replica sum follows the GEMM without a copy in between
+    RedLaunch red;
+    if (!(flags & DMM_NO_REDUCE) && (rc = stage_reduce(P, c_tiles, c_ld, 0, stream, &red))) return rc;
     const size_t n_items = P->items.size();
     const size_t n_segs = P->tasks.size();
     if (n_items > 0) {
@@ -446,7 +475,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         P->dev->gemm_timed = true;
       }
     }
-    if (!(flags & DMM_NO_REDUCE) && P->C.c > 1 && (rc = launch_reduce(P, c_tiles, c_ld, 0, stream, timed))) return rc;
+    if ((rc = fire_reduce(P, red, stream, timed))) return rc;
     return mark_use(P, stream);
   } catch (const std::bad_alloc &) {
     return DMM_ENOMEM;
@@ -479,7 +508,9 @@ int dmm_reduce_replicas(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld
   if ((rc = check_lds(P->C, c_ld))) return rc;
   try {
     if ((rc = ensure_state(P))) return rc;
-    if ((rc = launch_reduce(P, c_tiles, c_ld, origin_replica, (hipStream_t)hip_stream, false))) return rc;
+    RedLaunch red;
+    if ((rc = stage_reduce(P, c_tiles, c_ld, origin_replica, (hipStream_t)hip_stream, &red))) return rc;
+    if ((rc = fire_reduce(P, red, (hipStream_t)hip_stream, false))) return rc;
     return P->C.c > 1 ? mark_use(P, (hipStream_t)hip_stream) : DMM_OK;
   } catch (const std::bad_alloc &) {
     return DMM_ENOMEM;
