@@ -581,55 +581,62 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   bool loads_on = n > NSTAGE - 1;                        // a step s + 3 exists for s = 0
   prepare_lead(loads_on, NSTAGE - 1);
   int quiet = 0;                                         // iterations whose end is a plain advance of the lead
-  bool mid_plain = false;                                // the coming publication needs no repair and loads go on
+  int mid_plain = 0;                                     // the coming publication needs no repair and loads go on
   // After the lead step number `lead_idx` has been prepared by the general path: how many plain
   // advances follow it.  Their effect on the cursor is booked here, in advance.
   auto plan_quiet = [&](int lead_idx) {
-    quiet = 0;
-    mid_plain = loads_on && (fix_bits & 4u) == 0u;
+    int q = 0;
     if (loads_on && lead_seg_safe && (fix_bits & 7u) == 0u) {
-      int q = lead_left - 1 - (lead_tail ? 1 : 0);       // inside the segment, short of its K tail
+      q = lead_left - 1 - (lead_tail ? 1 : 0);           // inside the segment, short of its K tail
       const int r = n - 1 - lead_idx;                    // inside the item
       q = q < r ? q : r;
-      if (q > 0) {
-        quiet = q;
-        lead_left -= q;
-        lead_kpos += q * BK;
-      }
+      q = q > 0 ? q : 0;
     }
+    // (both are wave-uniform; saying so keeps them in scalar registers inside the loop)
+    quiet = __builtin_amdgcn_readfirstlane(q);
+    mid_plain = __builtin_amdgcn_readfirstlane(loads_on && (fix_bits & 4u) == 0u ? 1 : 0);
+    lead_left -= quiet;
+    lead_kpos += quiet * BK;
   };
   plan_quiet(NSTAGE - 1);
 
   DMM_TRACE(1);
+  // Two nested loops around ONE copy of the iteration: the inner loop runs the quiet iterations
+  // and carries only s, the counter and the two addresses; the outer loop does the general
+  // bookkeeping between runs.  (As a single loop with a rare branch at its end, every scalar the
+  // rare branch may change is copied back and forth once per iteration.)
+  int s = 0;
+  for (;;) {
 #pragma clang loop unroll(disable)
-  for (int s = 0; s < n; ++s) {
-    const int stage = s & (NSTAGE - 1);
-    const int ld_stage = (s + NSTAGE - 1) & (NSTAGE - 1);
-    sub_step(std::integral_constant<int, 0>{}, fr[0], fr[1], stage, 1, ld_stage);
-    // publish step s + 1: this wave's loads of it must have landed; steps s + 2 and (half of) s + 3
-    // may stay in flight (loads return in order)
-    if (__builtin_expect(mid_plain, 1)) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
-    } else {
-      if (loads_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
-      else if (s + 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      if (s + 1 < n) publish_fix(s + 1);
-    }
+    for (;;) {
+      const int stage = s & (NSTAGE - 1);
+      const int ld_stage = (s + NSTAGE - 1) & (NSTAGE - 1);
+      sub_step(std::integral_constant<int, 0>{}, fr[0], fr[1], stage, 1, ld_stage);
+      // publish step s + 1: this wave's loads of it must have landed; steps s + 2 and (half of)
+      // s + 3 may stay in flight (loads return in order)
+      if (__builtin_expect(mid_plain != 0, 1)) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
+      } else {
+        if (loads_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
+        else if (s + 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (s + 1 < n) publish_fix(s + 1);
+      }
 #ifndef DMM_EXP_NOBARRIER
-    __syncthreads();                         // every wave has read stage s; step s + 1 is complete
+      __syncthreads();                       // every wave has read stage s; step s + 1 is complete
 #endif
-    sub_step(std::integral_constant<int, FM * FN>{}, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
-    if (__builtin_expect(quiet > 0, 1)) {
+      sub_step(std::integral_constant<int, FM * FN>{}, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
+      ++s;
+      if (quiet == 0) break;
       --quiet;
       ld_a = ld_a_next;
       ld_b = ld_b_next;
-    } else {
-      loads_on = s + NSTAGE < n;             // step (s + 1) + 3 exists
-      if (loads_on) advance_lead();
-      prepare_lead(loads_on, stage);         // it goes to the stage this iteration consumed
-      plan_quiet(s + NSTAGE);
     }
+    if (s >= n) break;
+    loads_on = s - 1 + NSTAGE < n;           // step s + 3 exists (s is the coming iteration)
+    if (loads_on) advance_lead();
+    prepare_lead(loads_on, (s - 1) & (NSTAGE - 1));   // it goes to the stage the last iteration consumed
+    plan_quiet(s - 1 + NSTAGE);
   }
   // nothing may land in LDS after the workgroup has gone; and the last MFMA results must have left
   // the matrix pipe before other instructions read the accumulators (18 wait states and more)
