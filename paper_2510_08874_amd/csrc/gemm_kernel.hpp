@@ -189,22 +189,8 @@ __device__ __forceinline__ void load_to_lds_16_masked(gptr base, unsigned lane_o
 #ifdef DMM_EXP_NODMA
   return;
 #endif
-#if defined(DMM_EXP_SLOT_A)      // scalar part only
-  asm volatile("s_add_u32 m0, %2, %3\n\ts_mov_b32 exec_lo, %4\n\ts_mov_b32 exec_hi, %5\n\t"
-               "s_mov_b64 exec, -1"
-#elif defined(DMM_EXP_SLOT_E)    // nothing, but the operands stay alive
-  asm volatile("; slot"
-#elif defined(DMM_EXP_SLOT_C)    // only the M0 write
-  asm volatile("s_add_u32 m0, %2, %3"
-#elif defined(DMM_EXP_SLOT_D)    // only the load (M0 left as it is: lands somewhere in LDS)
-  asm volatile("global_load_lds_dwordx4 %0, %1"
-#elif defined(DMM_EXP_SLOT_B)    // no exec writes
-  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\t"
-               "global_load_lds_dwordx4 %0, %1"
-#else
   asm volatile("s_add_u32 m0, %2, %3\n\ts_mov_b32 exec_lo, %4\n\ts_mov_b32 exec_hi, %5\n\t"
                "global_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1"
-#endif
                :
                : "v"(lane_off), "s"(base), "s"(lds_base), "n"(IMM), "s"(lo), "s"(hi)
                : "memory", "scc");
@@ -658,11 +644,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
   if (threadIdx.x == 0)
     dmm_trace[blockIdx.x * 8 + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |
                                     __builtin_amdgcn_s_getreg((31 << 11) | 4);
-#endif
-#ifdef DMM_EXP_STAGGER
-  if (blockIdx.x < 256) {
-    for (int g = ((blockIdx.x >> 3) % DMM_EXP_STAGGER) * DMM_EXP_STAG_UNIT; g > 0; --g) __builtin_amdgcn_s_sleep(127);
-  }
 #endif
   floatx16 acc[FM][FN];
 #pragma unroll
