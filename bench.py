@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
     ap.add_argument("--no-context", action="store_true", help="skip the vendor-library GEMM timing")
+    ap.add_argument("--no-reduce-large", action="store_true",
+                    help="skip the stand-alone replica sum at c = 4 on 16384 x 16384 (5.4 GB moved)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -187,6 +189,35 @@ def main() -> int:
                                          f"(all {cfg['N']} columns, K={cfg['K']}), {tc:.1f} s",
                                "seconds": round(tc, 2)}
     prob.close()
+
+    if not args.no_reduce_large and c_rep > 1:
+        # The replica sum alone at a size where neither launch overhead nor the last-level cache
+        # matter: 16 tiles of 4096 x 4096, four replicas: 4 x 1.07 GB read, 1.07 GB written.
+        Mr = Nr = 16384
+        rcfg = dict(name="reduce-large", M=Mr, K=64, N=Nr, dtype="bf16", nranks=64,
+                    A=workloads.block_desc(Mr, 64, 4, 4, replication=4), B=workloads.block_desc(64, Nr, 4, 4, replication=4),
+                    C=workloads.block_desc(Mr, Nr, 4, 4, replication=4))
+        rp = DeviceProblem(rcfg, c_fill=1.0)
+        for _ in range(2):
+            rp.reduce(0, stream)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+        ev[0].record()
+        for i in range(10):
+            rp.reduce(0, stream)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ts = [ev[i].elapsed_time(ev[i + 1]) for i in range(10)]
+        rbytes = 5 * 4.0 * Mr * Nr
+        out["roofline_replica_sum_large"] = {"kernel": "reduce_replicas_kernel", "bound": "hbm",
+                                             "workload": "c = 4, C 16384 x 16384 fp32 in 4x4 tiles, dmm_reduce_replicas alone",
+                                             "achieved": round(rbytes / (float(np.mean(ts)) * 1e-3) / 1e9, 1),
+                                             "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                             "frac": round(rbytes / (float(np.mean(ts)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                             "avg_ms": round(float(np.mean(ts)), 4), "best_ms": round(min(ts), 4)}
+        rp.close()
+        del rp
+        torch.cuda.empty_cache()
 
     if not args.no_context and cfg["dtype"] == "bf16":
         def vendor(kind):
