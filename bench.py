@@ -29,6 +29,7 @@ The line also carries
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -44,9 +45,11 @@ PEAK_HBM_GBS = 8000.0
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (default: the 8192^3 2.5D configuration)")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default=None,
+                    help="element type of A and B (default: the workload's own)")
     ap.add_argument("--ld-multiple", type=int, default=1, help="pad leading dimensions to this many elements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
@@ -76,6 +79,8 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     cfg = workloads.config(args.workload)
+    if args.dtype and args.dtype != cfg["dtype"]:
+        cfg = dict(cfg, dtype=args.dtype, name=f"{cfg['name']}/{args.dtype}")
     A, B = workloads.make_operands(cfg)
     prob = DeviceProblem(cfg, A, B, ld_multiple=args.ld_multiple)
     stream = torch.cuda.current_stream().cuda_stream
@@ -88,39 +93,48 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    host_s = [0.0, 0.0]       # host seconds spent issuing (plan + execute), and waiting for the step before
+    host_s = [0.0, 0.0]       # host seconds spent issuing (plan + execute), and waiting for finished steps
+    DEPTH = 3                 # steps in flight: a plan is read back and destroyed three steps after its launch
+    inflight = []
+    gemm_ms, red_ms = [], []
 
-    def step(prev):
+    def step(record):
         h0 = time.perf_counter()
         plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])      # slicing + grouping (host)
         plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING, stream)  # upload + GEMM + replica sum
         h1 = time.perf_counter()
-        times = None
-        if prev is not None:
-            times = prev.elapsed_ms()
-            prev.destroy()
+        inflight.append((plan, record))
+        if len(inflight) > DEPTH:
+            retire()
         host_s[0] += h1 - h0
         host_s[1] += time.perf_counter() - h1
-        return plan, times
 
-    prev = None
+    def retire():
+        plan, record = inflight.pop(0)
+        g, r = plan.elapsed_ms()          # waits for that step's events
+        plan.destroy()
+        if record:
+            gemm_ms.append(g)
+            red_ms.append(r)
+
+    # The interpreter's cyclic collector stays off inside the loop: one full collection takes tens of
+    # milliseconds here (it walks torch's objects) and would show up as a GPU idle gap of that length.
+    gc.collect()
+    gc.disable()
     for _ in range(args.warmup):
-        prev, _ = step(prev)
+        step(False)
+    while inflight:
+        retire()
     torch.cuda.synchronize()
-    gemm_ms, red_ms = [], []
     host_s[0] = host_s[1] = 0.0
     t0 = time.perf_counter()
     for i in range(args.steps):
-        prev, times = step(prev)       # `times` belong to the previous step's plan
-        if i > 0:
-            gemm_ms.append(times[0])
-            red_ms.append(times[1])
+        step(True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    last = prev.elapsed_ms()
-    gemm_ms.append(last[0])
-    red_ms.append(last[1])
-    prev.destroy()
+    while inflight:
+        retire()
+    gc.enable()
 
     # host-only cost of planning, for the record
     tp0 = time.perf_counter()
@@ -139,7 +153,7 @@ def main() -> int:
     traffic = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.workload, {})
+        traffic = json.load(open(tpath)).get(cfg["name"], {})
 
     out = {
         "metric": "plan-execute TFLOP/s and % of MFMA peak per partitioning config (1 GPU)",
