@@ -23,8 +23,10 @@ The line also carries
                 (torch.matmul, bf16 output) and for the same product of zeros.  The
                 chip lowers its clock under matrix load, and by how much depends on
                 the data, so the published peak is not reachable with random
-                operands; these two numbers say how far it is on the day.  Context
-                only: nothing of the product path runs through the vendor library.
+                operands; these two numbers say how far it is on the day.  Also the
+                rate of a register-only MFMA loop on every SIMD (the library's
+                dmm_measure_mfma_rate), random and constant operands.  Context only:
+                nothing of the product path runs through the vendor library.
 """
 from __future__ import annotations
 
@@ -249,9 +251,16 @@ def main() -> int:
             torch.cuda.synchronize()
             del a, b, c
             return round(fl / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12, 1)
+        pipe_rand = binding.dmm_measure_mfma_rate(100.0, True)
+        pipe_const = binding.dmm_measure_mfma_rate(100.0, False)
         out["context"] = {"vendor_matmul_bf16_out_normal_data_tflops": vendor("normal"),
                           "vendor_matmul_bf16_out_zero_data_tflops": vendor("zeros"),
-                          "note": "one dense product of the same M, K, N through torch.matmul on this box; not part of the path"}
+                          "mfma_pipe_only_random_operands": {"tflops": round(pipe_rand[0], 1), "shader_mhz": round(pipe_rand[1])},
+                          "mfma_pipe_only_constant_operands": {"tflops": round(pipe_const[0], 1), "shader_mhz": round(pipe_const[1])},
+                          "gemm_frac_of_pipe_only_random": round(achieved / pipe_rand[0], 4),
+                          "note": "vendor: one dense product of the same M, K, N through torch.matmul on this box (not part "
+                                  "of the path); pipe only: 100 ms of back-to-back bf16 MFMAs from registers on every SIMD "
+                                  "(dmm_measure_mfma_rate): what the matrix pipes sustain at the clock the part settles to"}
     print(json.dumps(out), flush=True)
     return 0
 

@@ -149,6 +149,17 @@ int dmm_reduce_replicas(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld
  * reports the best of repeated runs.) */
 int dmm_plan_elapsed_ms(dmm_plan_t *p, float *gemm_ms, float *reduce_ms);
 
+/* Measurement aid, independent of any plan: the rate the matrix pipes of the current device
+ * sustain right now with nothing else going on.  Every SIMD of every CU issues independent
+ * v_mfma_f32_32x32x16_bf16 back to back from registers (no LDS, no memory) for about
+ * `milliseconds` of device time; operands are pseudo-random bf16 values in (-1, 1) when
+ * `random_operands` is non-zero, constants otherwise.  The part lowers its clock under matrix
+ * load by an amount that depends on the operand data, so this, not the published peak, is what
+ * a kernel on this device can approach at that moment.  Outputs (either may be null): achieved
+ * TFLOP/s and the average shader clock in MHz.  Synchronous; launches on the null stream.
+ * Errors: DMM_EINVAL (milliseconds <= 0 or > 1000), DMM_EHIP. */
+int dmm_measure_mfma_rate(float milliseconds, int random_operands, float *tflops, float *shader_mhz);
+
 /* Frees host and device memory of the plan (waits for the plan's own enqueued
  * work first; device buffers return to a process-wide pool).  Null is allowed. */
 void dmm_plan_destroy(dmm_plan_t *p);

@@ -100,6 +100,8 @@ def lib() -> C.CDLL:
         L.dmm_strerror.argtypes = [C.c_int]
         L.dmm_last_hip_error.restype = C.c_int
         L.dmm_version.restype = C.c_int
+        L.dmm_measure_mfma_rate.restype = C.c_int
+        L.dmm_measure_mfma_rate.argtypes = [C.c_float, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         _lib = L
     return _lib
 
@@ -107,7 +109,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
            "dmm_execute", "dmm_reduce_replicas", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
-           "dmm_last_hip_error", "dmm_version")
+           "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
 
 
 def _desc(d: Dict, keep: List) -> dmm_matrix_desc:
@@ -252,3 +254,12 @@ def dmm_strerror(status: int) -> str:
 
 def dmm_version() -> int:
     return int(lib().dmm_version())
+
+
+def dmm_measure_mfma_rate(milliseconds: float, random_operands: bool = True):
+    """(TFLOP/s, shader MHz) of a register-only MFMA loop on the current device."""
+    tf, mhz = C.c_float(0.0), C.c_float(0.0)
+    rc = lib().dmm_measure_mfma_rate(C.c_float(milliseconds), 1 if random_operands else 0, C.byref(tf), C.byref(mhz))
+    if rc != DMM_OK:
+        raise DmmError(rc, "dmm_measure_mfma_rate")
+    return float(tf.value), float(mhz.value)

@@ -101,6 +101,48 @@ __global__ __launch_bounds__(RED_NT) void reduce_replicas_kernel(const RedItem *
   }
 }
 
+// ------------------------------------------------------------------ matrix-pipe rate probe
+
+// Eight independent accumulators per wave, operands held in registers: the MFMA pipe is never
+// idle and nothing else on the chip is busy.  Reports elapsed shader cycles of wave 0 per block.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(unsigned long long *cycles, float *sink, int iters,
+                                                        int random_operands) {
+  floatx16 acc[8];
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      unsigned h = (threadIdx.x * 977u + blockIdx.x * 131071u + s * 8u + e) * 2654435761u;
+      h ^= h >> 15;
+      h *= 0x846ca68bu;
+      h ^= h >> 16;
+      a[s][e] = (__bf16)(random_operands ? ((int)(h & 0xFFFFu) - 32768) * (1.0f / 32768.0f) : 1.0f);
+      b[s][e] = (__bf16)(random_operands ? ((int)(h >> 16) - 32768) * (1.0f / 32768.0f) : 0.5f);
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(a[s]), "+v"(b[s]));
+  const unsigned long long t0 = __builtin_amdgcn_s_memtime();
+  for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[(u + 3 * v) & 7], acc[u], 0, 0, 0);
+  }
+  const unsigned long long t1 = __builtin_amdgcn_s_memtime();
+  float s = 0.f;
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[u][r];
+  if (s == 12345.678f) sink[0] = s;       // keeps the accumulators alive; never true in practice
+  if (threadIdx.x == 0) cycles[blockIdx.x] = t1 - t0;
+}
+
 // ------------------------------------------------------------------ host state
 
 thread_local int g_last_hip_error = 0;
@@ -404,6 +446,61 @@ int fire_reduce(dmm_plan_t *P, const RedLaunch &L, hipStream_t stream, bool time
 extern "C" {
 
 int dmm_last_hip_error(void) { return dmm::g_last_hip_error; }
+
+int dmm_measure_mfma_rate(float milliseconds, int random_operands, float *tflops, float *shader_mhz) {
+  using namespace dmm;
+  if (!(milliseconds > 0.f) || milliseconds > 1000.f) return DMM_EINVAL;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  DMM_HIP(hipGetDevice(&dev));
+  DMM_HIP(hipGetDeviceProperties(&prop, dev));
+  const int blocks = prop.multiProcessorCount;      // one block of four waves per CU
+  unsigned long long *d_cycles = nullptr;
+  float *d_sink = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = DMM_OK;
+  auto fail = [&](hipError_t e) {
+    if (e != hipSuccess && rc == DMM_OK) {
+      g_last_hip_error = (int)e;
+      rc = DMM_EHIP;
+    }
+    return e != hipSuccess;
+  };
+  std::vector<unsigned long long> h((size_t)blocks);
+  float ms = 0.f;
+  double cyc = 0.0;
+  int iters = 4000;                                 // first pass: ~1 ms, to size the second
+  if (fail(hipMalloc((void **)&d_cycles, sizeof(unsigned long long) * (size_t)blocks))) goto done;
+  if (fail(hipMalloc((void **)&d_sink, sizeof(float)))) goto done;
+  if (fail(hipEventCreate(&e0)) || fail(hipEventCreate(&e1))) goto done;
+  for (int pass = 0; pass < 2; ++pass) {
+    if (fail(hipEventRecord(e0, nullptr))) goto done;
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)blocks), dim3(256), 0, nullptr, d_cycles, d_sink, iters,
+                       random_operands);
+    if (fail(hipGetLastError())) goto done;
+    if (fail(hipEventRecord(e1, nullptr)) || fail(hipEventSynchronize(e1))) goto done;
+    if (fail(hipEventElapsedTime(&ms, e0, e1))) goto done;
+    if (pass == 0) {
+      double scale = (double)milliseconds / (ms > 1e-3f ? ms : 1e-3f);
+      double want = iters * scale;
+      if (want > 2.0e8) want = 2.0e8;
+      iters = (int)(want / 4) * 4;
+      if (iters < 4) iters = 4;
+    }
+  }
+  if (fail(hipMemcpy(h.data(), d_cycles, sizeof(unsigned long long) * (size_t)blocks, hipMemcpyDeviceToHost))) goto done;
+  for (unsigned long long c : h) cyc += (double)c;
+  cyc /= blocks;
+  // per block: 4 waves x iters x 8 MFMAs x 32 * 32 * 16 * 2 flop
+  if (tflops) *tflops = (float)((double)blocks * 4.0 * iters * 8.0 * 32768.0 / (ms * 1e-3) / 1e12);
+  if (shader_mhz) *shader_mhz = (float)(cyc / (ms * 1e-3) / 1e6);
+done:
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (d_cycles) (void)hipFree(d_cycles);
+  if (d_sink) (void)hipFree(d_sink);
+  return rc;
+}
 
 int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int64_t *a_ld,
                 const void *const *b_tiles, const int64_t *b_ld, void *const *c_tiles, const int64_t *c_ld,

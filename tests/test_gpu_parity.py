@@ -288,3 +288,19 @@ def test_execute_rejects_bad_arguments():
     with pytest.raises(binding.DmmError):
         prob.plan.reduce_replicas(prob.C.tensors, prob.C.ld, origin=5)
     prob.close()
+
+
+def test_mfma_rate_probe_reports_a_plausible_rate():
+    """The measurement aid runs, rejects bad durations, and lands between 5 % and 100 % of the published peak."""
+    from paper_2510_08874_amd import binding
+    tf, mhz = binding.dmm_measure_mfma_rate(5.0, True)
+    assert 125.0 < tf < 2600.0
+    assert 300.0 < mhz < 2600.0
+    # 32 cycles per MFMA per SIMD: TFLOP/s = CUs * 4 * 1024 flop/cycle * MHz
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert abs(tf - cus * 4 * 1024 * mhz * 1e6 / 1e12) / tf < 0.05
+    for bad in (0.0, -1.0, 5000.0):
+        with pytest.raises(binding.DmmError) as e:
+            binding.dmm_measure_mfma_rate(bad, True)
+        assert e.value.kind == "EINVAL"
