@@ -79,6 +79,7 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    dprop = torch.cuda.get_device_properties(0)
 
     cfg = workloads.config(args.workload)
     if args.dtype and args.dtype != cfg["dtype"]:
@@ -169,9 +170,13 @@ def main() -> int:
                    "host_issue_us_per_step": round(host_s[0] / args.steps * 1e6, 1),
                    "host_wait_us_per_step": round(host_s[1] / args.steps * 1e6, 1)},
         "pct_of_mfma_peak": round(100.0 * value / peak, 2),
+        "device": {"name": dprop.name, "gcn_arch": getattr(dprop, "gcnArchName", ""), "compute_units": dprop.multi_processor_count,
+                   "peak_used": f"{peak} TFLOP/s = published dense {cfg['dtype']} MFMA peak of MI355X "
+                                "(256 CUs x 4 SIMDs x 1024 flop/cycle x 2.4 GHz for bf16)"},
         "roofline": {"kernel": "grouped_gemm_kernel", "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "avg_ms": round(g_avg, 4), "best_ms": round(g_best, 4),
+                     "avg_ms": round(g_avg, 4), "median_ms": round(float(np.median(gemm_ms)), 4),
+                     "best_ms": round(g_best, 4),
                      "best_frac": round(fl / (g_best * 1e-3) / 1e12 / peak, 4),
                      "traffic": traffic.get("gemm_bytes")},
     }
