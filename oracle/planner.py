@@ -1,4 +1,4 @@
-"""Oracle planner: distributed-matrix descriptor + Stationary-C op generation.
+"""Oracle planner: distributed-matrix descriptor + op generation (Stationary C, B, A).
 
 TEST INFRASTRUCTURE ONLY (see the package docstring).  Plain Python, integer
 arithmetic only, no blocking or shortcuts: ``overlapping_tiles`` scans every
@@ -13,6 +13,8 @@ What follows the paper, and where:
 * ``gen_ops_stationary_c``       -- Algorithm 1, with the change Section 4.1
   asks for when the stationary matrix is replicated: replica r searches only
   its 1/c share of the inner dimension and every k-bound is clipped to it.
+* ``gen_ops_stationary_b``       -- Algorithm 2; ``gen_ops_stationary_a`` is its mirror
+  image (Section 4.1 calls it analogous and omits it).
 * ``reorder``                    -- not in the paper: the plain definition
   (a stable sort) of the grouping by output sub-tile that the GPU path uses.
 
@@ -34,6 +36,19 @@ again in the design notes):
 * ``overlapping_tiles`` returns tiles in ascending (tile row, tile column).
 * the global list is the concatenation of the per-process lists by ascending
   rank; the iteration offset of Section 4.2 is not applied.
+* Algorithm 2 names the op's B tile and C tile with identifiers it never
+  defines; they are read as the stationary tile (k, j) and the C tile of the
+  innermost loop.
+* Section 4.1 states the 1/c rule for a replicated stationary C only (its
+  replicas split the inner dimension).  For a replicated stationary B the
+  replicas split M, for a replicated stationary A they split N: in each case the
+  one dimension the stationary matrix does not index, in contiguous element
+  ranges ``[floor(r L / c), floor((r+1) L / c))``.  The test of this reading is
+  that every point of the iteration space is still covered exactly once.
+* with Stationary B or A an op's product goes to the C tile in the process'
+  local replica of C (Section 3: a primitive without replica index addresses the
+  local replica); regions of a C replica that receive nothing hold zero, so that
+  the replica sum is the product.
 """
 from __future__ import annotations
 
@@ -175,7 +190,7 @@ def validate_problem(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int) -> Non
 
 def k_share(replica: int, K: int, c: int) -> Interval:
     """Section 4.1: replica r of a c-fold replicated stationary matrix works on
-    1/c of the inner dimension."""
+    1/c of the inner dimension (of M or N when B or A is the stationary matrix)."""
     return ((replica * K) // c, ((replica + 1) * K) // c)
 
 
@@ -215,12 +230,95 @@ def gen_ops_stationary_c(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, ra
     return ops
 
 
-def plan(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int) -> List[Task]:
-    """Task list of the whole job: every rank's ops, ranks in ascending order."""
+def gen_ops_stationary_b(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, rank: int) -> List[Task]:
+    """Algorithm 2 for one process: its tiles of B stay in place.
+
+    A replicated B splits M between its replicas (see the module docstring)."""
+    ops: List[Task] = []
+    M = A.rows
+    b_rep = B.replica_of(rank, p)
+    a_rep = A.replica_of(rank, p)
+    c_rep = C.replica_of(rank, p)
+    share = k_share(b_rep, M, B.replication)         # this replica's rows of A and C
+    gr, gc = B.grid_shape()
+    for k in range(gr):
+        for j in range(gc):
+            if B.owner((k, j), b_rep, p) != rank:
+                continue
+            b_bounds = B.tile_bounds((k, j))
+            # tiles of A(my share of the rows, the k range of my B tile)
+            a_tiles = A.overlapping_tiles((share, b_bounds[0]), a_rep)
+            for a_idx in a_tiles:
+                a_bounds = A.tile_bounds(a_idx)
+                # tiles of C this product updates: rows of the A tile, columns of my B tile
+                c_tiles = C.overlapping_tiles((bound(a_bounds[0], share), b_bounds[1]), c_rep)
+                for c_idx in c_tiles:
+                    c_bounds = C.tile_bounds(c_idx)
+                    m_bound = bound(bound(c_bounds[0], a_bounds[0]), share)
+                    k_bound = bound(a_bounds[1], b_bounds[0])
+                    n_bound = bound(b_bounds[1], c_bounds[1])
+                    if is_empty(m_bound) or is_empty(k_bound) or is_empty(n_bound):
+                        continue
+                    ops.append(Task(rank, a_rep, a_idx[0], a_idx[1],
+                                    b_rep, k, j,
+                                    c_rep, c_idx[0], c_idx[1],
+                                    m_bound[0], m_bound[1],
+                                    k_bound[0], k_bound[1],
+                                    n_bound[0], n_bound[1]))
+    return ops
+
+
+def gen_ops_stationary_a(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, rank: int) -> List[Task]:
+    """The mirror image of Algorithm 2: the process' tiles of A stay in place.
+
+    A replicated A splits N between its replicas (see the module docstring)."""
+    ops: List[Task] = []
+    N = B.cols
+    a_rep = A.replica_of(rank, p)
+    b_rep = B.replica_of(rank, p)
+    c_rep = C.replica_of(rank, p)
+    share = k_share(a_rep, N, A.replication)         # this replica's columns of B and C
+    gr, gc = A.grid_shape()
+    for i in range(gr):
+        for l in range(gc):
+            if A.owner((i, l), a_rep, p) != rank:
+                continue
+            a_bounds = A.tile_bounds((i, l))
+            # tiles of B(the k range of my A tile, my share of the columns)
+            b_tiles = B.overlapping_tiles((a_bounds[1], share), b_rep)
+            for b_idx in b_tiles:
+                b_bounds = B.tile_bounds(b_idx)
+                # tiles of C this product updates: rows of my A tile, columns of the B tile
+                c_tiles = C.overlapping_tiles((a_bounds[0], bound(b_bounds[1], share)), c_rep)
+                for c_idx in c_tiles:
+                    c_bounds = C.tile_bounds(c_idx)
+                    m_bound = bound(c_bounds[0], a_bounds[0])
+                    k_bound = bound(a_bounds[1], b_bounds[0])
+                    n_bound = bound(bound(b_bounds[1], c_bounds[1]), share)
+                    if is_empty(m_bound) or is_empty(k_bound) or is_empty(n_bound):
+                        continue
+                    ops.append(Task(rank, a_rep, i, l,
+                                    b_rep, b_idx[0], b_idx[1],
+                                    c_rep, c_idx[0], c_idx[1],
+                                    m_bound[0], m_bound[1],
+                                    k_bound[0], k_bound[1],
+                                    n_bound[0], n_bound[1]))
+    return ops
+
+
+_GENERATORS = {"C": gen_ops_stationary_c, "B": gen_ops_stationary_b, "A": gen_ops_stationary_a}
+
+
+def plan(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, stationary: str = "C") -> List[Task]:
+    """Task list of the whole job: every rank's ops, ranks in ascending order.
+
+    ``stationary`` names the data movement strategy of Section 4: the matrix
+    whose tiles stay in place and decide which process performs an op."""
     validate_problem(A, B, C, p)
+    gen = _GENERATORS[stationary]
     tasks: List[Task] = []
     for rank in range(p):
-        tasks.extend(gen_ops_stationary_c(A, B, C, p, rank))
+        tasks.extend(gen(A, B, C, p, rank))
     return tasks
 
 

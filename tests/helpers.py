@@ -63,30 +63,37 @@ def merged_intervals(lo, hi, *cut_lists):
 
 # -- checkers on task records (fields by name; works for any namedtuple-like) --
 
-def coverage_counter(tasks, M, K, N, c_rep=None):
-    """3-D counter over the (i, k, j) iteration space, +1 for every task box."""
+def coverage_counter(tasks, M, K, N, c_rep=None, rep_field="c_rep"):
+    """3-D counter over the (i, k, j) iteration space, +1 for every task box
+    (optionally only the tasks whose ``rep_field`` equals ``c_rep``)."""
     cnt = np.zeros((M, K, N), dtype=np.int32)
     for t in tasks:
-        if c_rep is not None and t.c_rep != c_rep:
+        if c_rep is not None and getattr(t, rep_field) != c_rep:
             continue
         cnt[t.m0:t.m1, t.k0:t.k1, t.n0:t.n1] += 1
     return cnt
 
 
-def check_task_list(tasks, A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int):
-    """Everything the paper and the mathematics fix about a Stationary-C task
-    list; raises AssertionError naming the first violated property."""
+def check_task_list(tasks, A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, stationary: str = "C"):
+    """Everything the paper and the mathematics fix about a task list generated
+    with the given stationary matrix; raises AssertionError naming the first
+    violated property."""
     M, K, N = A.rows, A.cols, B.cols
-    cC = C.replication
+    S = dict(A=A, B=B, C=C)[stationary]
+    cS = S.replication
+    # the dimension the replicas of the stationary matrix split: the one it does not index
+    axis = dict(C=1, B=0, A=2)[stationary]
+    L = (M, K, N)[axis]
+    rep_field = stationary.lower() + "_rep"
     # (1) the boxes tile the iteration space exactly once (Sections 2.1, 4.1)
     cnt = coverage_counter(tasks, M, K, N)
     assert cnt.min(initial=1) == 1 and cnt.max(initial=1) == 1, "iteration space not covered exactly once"
-    # (2) each C replica covers exactly its 1/c share of the inner dimension
-    for r in range(cC):
-        k0, k1 = (r * K) // cC, ((r + 1) * K) // cC
-        cr = coverage_counter(tasks, M, K, N, c_rep=r)
-        assert (cr[:, k0:k1, :] == 1).all(), f"replica {r} misses part of its share"
-        assert cr[:, :k0, :].sum() == 0 and cr[:, k1:, :].sum() == 0, f"replica {r} works outside its share"
+    # (2) each replica of the stationary matrix covers exactly its 1/c share of that dimension
+    for r in range(cS):
+        lo, hi = (r * L) // cS, ((r + 1) * L) // cS
+        cr = np.moveaxis(coverage_counter(tasks, M, K, N, c_rep=r, rep_field=rep_field), axis, 0)
+        assert (cr[lo:hi] == 1).all(), f"replica {r} misses part of its share"
+        assert cr[:lo].sum() == 0 and cr[hi:].sum() == 0, f"replica {r} works outside its share"
     for t in tasks:
         # (3) non-empty boxes, each slice inside its tile
         assert t.m0 < t.m1 and t.k0 < t.k1 and t.n0 < t.n1, "empty task"
@@ -96,17 +103,21 @@ def check_task_list(tasks, A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int):
         assert ar[0] <= t.m0 and t.m1 <= ar[1] and ac[0] <= t.k0 and t.k1 <= ac[1], "A slice leaves its tile"
         assert br[0] <= t.k0 and t.k1 <= br[1] and bc[0] <= t.n0 and t.n1 <= bc[1], "B slice leaves its tile"
         assert cr_[0] <= t.m0 and t.m1 <= cr_[1] and cc[0] <= t.n0 and t.n1 <= cc[1], "C slice leaves its tile"
-        # (4) the stationary tile belongs to the rank; A and B come from its local replica
-        assert C.owner((t.c_ti, t.c_tj), t.c_rep, p) == t.rank, "task on a rank that does not own the C tile"
+        # (4) the stationary tile belongs to the rank; everything comes from (goes to) its local replicas
+        s_idx = dict(A=(t.a_ti, t.a_tj), B=(t.b_ti, t.b_tj), C=(t.c_ti, t.c_tj))[stationary]
+        assert S.owner(s_idx, getattr(t, rep_field), p) == t.rank, "task on a rank that does not own the stationary tile"
         assert t.c_rep == C.replica_of(t.rank, p)
         assert t.a_rep == A.replica_of(t.rank, p) and t.b_rep == B.replica_of(t.rank, p), "not the local replica"
     # (5) closed-form count: product of the merged-cut interval counts, per replica share
+    cuts = [(A.row_cuts, C.row_cuts), (A.col_cuts, B.row_cuts), (B.col_cuts, C.col_cuts)]
+    dims = (M, K, N)
     want = 0
-    mi = merged_intervals(0, M, A.row_cuts, C.row_cuts)
-    ni = merged_intervals(0, N, B.col_cuts, C.col_cuts)
-    for r in range(cC):
-        k0, k1 = (r * K) // cC, ((r + 1) * K) // cC
-        want += mi * merged_intervals(k0, k1, A.col_cuts, B.row_cuts) * ni
+    for r in range(cS):
+        lo, hi = (r * L) // cS, ((r + 1) * L) // cS
+        n = 1
+        for ax in range(3):
+            n *= merged_intervals(lo, hi, *cuts[ax]) if ax == axis else merged_intervals(0, dims[ax], *cuts[ax])
+        want += n
     assert len(tasks) == want, f"{len(tasks)} tasks, closed form says {want}"
 
 

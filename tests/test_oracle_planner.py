@@ -276,6 +276,106 @@ def test_wrong_share_rule_is_caught(monkeypatch):
         helpers.check_task_list(tasks, A, B, C, p)
 
 
+# --- Stationary B and Stationary A (Algorithm 2 and its mirror image) --------------------
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+@pytest.mark.parametrize("seed", range(60))
+def test_stationary_b_and_a_cover_iteration_space_once(seed, mode):
+    prob = helpers.random_problem(seed + 300, allow_empty=(seed % 3 == 0))
+    A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
+    tasks = planner.plan(A, B, C, prob["nranks"], stationary=mode)
+    helpers.check_task_list(tasks, A, B, C, prob["nranks"], stationary=mode)
+
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+def test_stationary_b_and_a_all_replication_combinations_p8(mode):
+    p, M, K, N = 8, 12, 16, 10
+    for cA in helpers.divisors(p):
+        for cB in helpers.divisors(p):
+            for cC in helpers.divisors(p):
+                A = DistMatrix(M, K, (0, 5, 12), (0, 7, 16), 1, 1, cA)
+                B = DistMatrix(K, N, (0, 3, 9, 16), (0, 10), 1, 1, cB)
+                C = DistMatrix(M, N, (0, 4, 12), (0, 6, 10), 1, 1, cC)
+                tasks = planner.plan(A, B, C, p, stationary=mode)
+                helpers.check_task_list(tasks, A, B, C, p, stationary=mode)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_three_modes_multiply_the_same_boxes_without_replication(seed):
+    """Without replication the set of (m, k, n) boxes is the common refinement of the
+    three grids whichever matrix stays in place (Section 4.1: only the process that
+    performs an op changes); the Stationary-C list is pinned by brute force above."""
+    prob = helpers.random_problem(seed + 700)
+    for X in "ABC":
+        prob[X] = dict(prob[X], replication=1)
+    A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
+    boxes = {}
+    for mode in "CBA":
+        tasks = planner.plan(A, B, C, prob["nranks"], stationary=mode)
+        boxes[mode] = sorted((t.a_ti, t.a_tj, t.b_ti, t.b_tj, t.c_ti, t.c_tj, t.m0, t.m1, t.k0, t.k1, t.n0, t.n1)
+                             for t in tasks)
+    assert boxes["C"] == boxes["B"] == boxes["A"]
+
+
+def test_stationary_b_by_hand():
+    """M = 4, K = 6, N = 4; B in two row blocks (k 0:3 and 3:6) on two ranks; A whole,
+    C in two row blocks.  Rank q multiplies A(:, its k block) by its B tile into both
+    C tiles: two ops per rank, worked out by hand."""
+    A = DistMatrix(4, 6, (0, 4), (0, 6), 1, 1, 1)
+    B = DistMatrix(6, 4, (0, 3, 6), (0, 4), 2, 1, 1)
+    C = DistMatrix(4, 4, (0, 2, 4), (0, 4), 2, 1, 1)
+    tasks = planner.plan(A, B, C, 2, stationary="B")
+    want = [Task(0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 2, 0, 3, 0, 4),
+            Task(0, 0, 0, 0, 0, 0, 0, 0, 1, 0, 2, 4, 0, 3, 0, 4),
+            Task(1, 0, 0, 0, 0, 1, 0, 0, 0, 0, 0, 2, 3, 6, 0, 4),
+            Task(1, 0, 0, 0, 0, 1, 0, 0, 1, 0, 2, 4, 3, 6, 0, 4)]
+    assert tasks == want
+
+
+def test_stationary_a_by_hand_replicated():
+    """A whole and replicated twice over two ranks: replica r takes the columns
+    [2r, 2r + 2) of N = 4 (the dimension A does not index).  B and C are whole and
+    not replicated, so both ranks address replica 0 of them."""
+    A = DistMatrix(3, 5, (0, 3), (0, 5), 1, 1, 2)
+    B = DistMatrix(5, 4, (0, 5), (0, 4), 1, 1, 1)
+    C = DistMatrix(3, 4, (0, 3), (0, 4), 1, 1, 1)
+    tasks = planner.plan(A, B, C, 2, stationary="A")
+    want = [Task(0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 3, 0, 5, 0, 2),
+            Task(1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 3, 0, 5, 2, 4)]
+    assert tasks == want
+
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+def test_wrong_split_dimension_is_caught(monkeypatch, mode):
+    """Replicas of a stationary B (A) that split the inner dimension's extent instead
+    of M's (N's) are caught: planted by making every share the full range."""
+    A = DistMatrix(12, 16, (0, 5, 12), (0, 7, 16), 2, 2, 2)
+    B = DistMatrix(16, 10, (0, 3, 9, 16), (0, 4, 10), 3, 1, 2)
+    C = DistMatrix(12, 10, (0, 4, 12), (0, 6, 10), 2, 2, 1)
+    good = planner.plan(A, B, C, 8, stationary=mode)
+    helpers.check_task_list(good, A, B, C, 8, stationary=mode)
+    monkeypatch.setattr(planner, "k_share", lambda r, L, c: (0, L))
+    bad = planner.plan(A, B, C, 8, stationary=mode)
+    with pytest.raises(AssertionError):
+        helpers.check_task_list(bad, A, B, C, 8, stationary=mode)
+
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+@pytest.mark.parametrize("seed", range(20))
+def test_executing_stationary_b_and_a_lists_gives_the_product(seed, mode):
+    prob = helpers.random_problem(seed + 900)
+    A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
+    tasks = planner.plan(A, B, C, prob["nranks"], stationary=mode)
+    rng = np.random.default_rng(seed + 99)
+    Ag = rng.standard_normal((prob["M"], prob["K"]))
+    Bg = rng.standard_normal((prob["K"], prob["N"]))
+    c_tiles = oexec.execute_tasks(tasks, A, B, C, oexec.split_tiles(Ag, A), oexec.split_tiles(Bg, B))
+    got = oexec.reduce_and_gather(c_tiles, C)
+    np.testing.assert_allclose(got, Ag @ Bg, rtol=0, atol=1e-12 * prob["K"])
+    order, offsets = planner.reorder(tasks)
+    helpers.check_reorder(tasks, order, offsets, C)
+
+
 # --- grouping -----------------------------------------------------------------------
 
 @pytest.mark.parametrize("seed", range(40))
