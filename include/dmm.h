@@ -48,6 +48,11 @@ typedef enum {
 /* Element type of the A and B tiles.  C tiles and all partial sums are fp32. */
 typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
 
+/* dmm_plan flags: the data movement strategy of Section 4, i.e. which matrix stays in place
+ * and so decides which rank performs an op.  0 = Stationary C (Algorithm 1). */
+#define DMM_STATIONARY_B 1u /* Algorithm 2 */
+#define DMM_STATIONARY_A 2u /* its mirror image (Section 4.1: "analogous") */
+
 /* dmm_execute flags */
 #define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
 #define DMM_TIMING 2u    /* record events around the GEMM launch and around the replica-sum launch
@@ -77,7 +82,7 @@ typedef struct {
  * cols n) and C slice (rows m, cols n) are multiplied.  Offsets inside a tile
  * are the global bound minus the tile's lower bound (footnote of Section 4.1). */
 typedef struct {
-  int32_t rank;             /* virtual rank that owns the stationary C tile */
+  int32_t rank;             /* virtual rank that owns the stationary tile (of C, B or A) */
   int32_t a_rep, a_ti, a_tj;
   int32_t b_rep, b_ti, b_tj;
   int32_t c_rep, c_ti, c_tj;
@@ -88,7 +93,9 @@ typedef struct {
  * C region rows [m0, m0 + m_ext) x cols [n0, n0 + n_ext) (global indices) of
  * replica c_rep, which one workgroup accumulates over the group's K-segments in
  * ascending k and writes once.  group = -1 marks a zero-fill item: a C region
- * whose replica has an empty share of the inner dimension. */
+ * no op of the plan updates in that replica (a replica with an empty share of the
+ * inner dimension; with Stationary B or A, regions other replicas' ranks compute),
+ * which therefore holds a partial sum of zero. */
 typedef struct {
   int64_t group;            /* index into group_offsets, or -1 */
   int64_t m0, n0;           /* global top-left corner */
@@ -99,9 +106,15 @@ typedef struct {
 
 typedef struct dmm_plan_s dmm_plan_t;
 
-/* Slicing planner (Algorithm 1; replication rule of Section 4.1; grouping by
- * output sub-tile).  Host only: makes no HIP call.  `nranks` is p, the number
- * of virtual ranks.  `flags` must be 0.  On success *out owns the plan. */
+/* Slicing planner (Algorithm 1, or Algorithm 2 / its mirror image when `flags` asks for
+ * Stationary B / A; replication rule of Section 4.1; grouping by output sub-tile).
+ * A c-fold replicated stationary matrix splits between its replicas the one dimension it
+ * does not index, in contiguous ranges [floor(r L / c), floor((r+1) L / c)): K for C
+ * (Section 4.1), M for B, N for A.  An op's product goes to the C tile in the performing
+ * rank's local replica of C; dmm_execute gives every C replica its partial sum and then
+ * adds the replicas up.  Host only: makes no HIP call.  `nranks` is p, the number of
+ * virtual ranks.  `flags`: 0, DMM_STATIONARY_B or DMM_STATIONARY_A (anything else, or
+ * both: DMM_EINVAL).  On success *out owns the plan. */
 int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C,
              int32_t nranks, uint32_t flags, dmm_plan_t **out);
 

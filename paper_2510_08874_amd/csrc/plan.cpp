@@ -4,7 +4,9 @@
 //  - op generation: Algorithm 1 (Stationary C) over every virtual rank, with the
 //    replication rule of Section 4.1 (replica r of a c-fold replicated C works
 //    on the k range [floor(rK/c), floor((r+1)K/c)) and every k bound is clipped
-//    to it).  overlapping_tiles (Table 1) is answered by binary search on the
+//    to it); on request Algorithm 2 (Stationary B) or its mirror image
+//    (Stationary A), whose replicas split M and N respectively in the same
+//    way.  overlapping_tiles (Table 1) is answered by binary search on the
 //    cut arrays instead of a scan, and "the tiles I own" are enumerated directly
 //    from the block-cyclic rule (Section 2.1) instead of testing every tile.
 //  - grouping: the paper executes ops in list order (Section 4.2); here ops are
@@ -124,6 +126,118 @@ void generate_rank(const dmm_plan_t &P, int32_t rank, std::vector<dmm_task> *out
   }
 }
 
+// Ops of one virtual rank with its tiles of B in place (Algorithm 2).  Replica r of a
+// c-fold replicated B works on the rows [floor(rM/c), floor((r+1)M/c)) of A and C.
+void generate_rank_b(const dmm_plan_t &P, int32_t rank, std::vector<dmm_task> *out) {
+  const Grid &A = P.A, &B = P.B, &C = P.C;
+  const int32_t p = P.nranks;
+  const int32_t c_per = p / C.c, a_per = p / A.c, b_per = p / B.c;
+  const int32_t c_rep = rank / c_per, a_rep = rank / a_per, b_rep = rank / b_per;
+  const int32_t local = rank % b_per;
+  if (local >= B.pr * B.pc) return;  // this rank holds no tile of B
+  const int32_t my_pr = local / B.pc, my_pc = local % B.pc;
+  const int64_t M = A.rows;
+  const Interval share{(int64_t)b_rep * M / B.c, ((int64_t)b_rep + 1) * M / B.c};
+  int32_t a_r0, a_r1;
+  tile_range(A.rc, share, &a_r0, &a_r1);
+
+  for (int32_t kk = my_pr; kk < B.gr; kk += B.pr) {
+    const Interval b_rows{B.rc[kk], B.rc[kk + 1]};
+    if (b_rows.empty()) continue;
+    int32_t a_c0, a_c1;
+    tile_range(A.cc, b_rows, &a_c0, &a_c1);
+    for (int32_t j = my_pc; j < B.gc; j += B.pc) {
+      const Interval b_cols{B.cc[j], B.cc[j + 1]};
+      if (b_cols.empty()) continue;
+      int32_t c_c0, c_c1;
+      tile_range(C.cc, b_cols, &c_c0, &c_c1);
+      for (int32_t ai = a_r0; ai <= a_r1; ++ai) {
+        const Interval a_m = meet({A.rc[ai], A.rc[ai + 1]}, share);
+        if (a_m.empty()) continue;
+        int32_t c_r0, c_r1;
+        tile_range(C.rc, a_m, &c_r0, &c_r1);
+        for (int32_t aj = a_c0; aj <= a_c1; ++aj) {
+          const Interval k = meet({A.cc[aj], A.cc[aj + 1]}, b_rows);
+          if (k.empty()) continue;
+          for (int32_t ci = c_r0; ci <= c_r1; ++ci) {
+            const Interval m = meet(a_m, {C.rc[ci], C.rc[ci + 1]});
+            if (m.empty()) continue;
+            for (int32_t cj = c_c0; cj <= c_c1; ++cj) {
+              const Interval n = meet(b_cols, {C.cc[cj], C.cc[cj + 1]});
+              if (n.empty()) continue;
+              dmm_task t;
+              t.rank = rank;
+              t.a_rep = a_rep; t.a_ti = ai; t.a_tj = aj;
+              t.b_rep = b_rep; t.b_ti = kk; t.b_tj = j;
+              t.c_rep = c_rep; t.c_ti = ci; t.c_tj = cj;
+              t.m0 = m.lo; t.m1 = m.hi;
+              t.k0 = k.lo; t.k1 = k.hi;
+              t.n0 = n.lo; t.n1 = n.hi;
+              out->push_back(t);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// Ops of one virtual rank with its tiles of A in place (the mirror image of Algorithm 2).
+// Replica r of a c-fold replicated A works on the columns [floor(rN/c), floor((r+1)N/c)).
+void generate_rank_a(const dmm_plan_t &P, int32_t rank, std::vector<dmm_task> *out) {
+  const Grid &A = P.A, &B = P.B, &C = P.C;
+  const int32_t p = P.nranks;
+  const int32_t c_per = p / C.c, a_per = p / A.c, b_per = p / B.c;
+  const int32_t c_rep = rank / c_per, a_rep = rank / a_per, b_rep = rank / b_per;
+  const int32_t local = rank % a_per;
+  if (local >= A.pr * A.pc) return;  // this rank holds no tile of A
+  const int32_t my_pr = local / A.pc, my_pc = local % A.pc;
+  const int64_t N = B.cols;
+  const Interval share{(int64_t)a_rep * N / A.c, ((int64_t)a_rep + 1) * N / A.c};
+  int32_t b_c0, b_c1;
+  tile_range(B.cc, share, &b_c0, &b_c1);
+
+  for (int32_t i = my_pr; i < A.gr; i += A.pr) {
+    const Interval a_rows{A.rc[i], A.rc[i + 1]};
+    if (a_rows.empty()) continue;
+    int32_t c_r0, c_r1;
+    tile_range(C.rc, a_rows, &c_r0, &c_r1);
+    for (int32_t l = my_pc; l < A.gc; l += A.pc) {
+      const Interval a_cols{A.cc[l], A.cc[l + 1]};
+      if (a_cols.empty()) continue;
+      int32_t b_r0, b_r1;
+      tile_range(B.rc, a_cols, &b_r0, &b_r1);
+      for (int32_t bi = b_r0; bi <= b_r1; ++bi) {
+        const Interval k = meet(a_cols, {B.rc[bi], B.rc[bi + 1]});
+        if (k.empty()) continue;
+        for (int32_t bj = b_c0; bj <= b_c1; ++bj) {
+          const Interval b_n = meet({B.cc[bj], B.cc[bj + 1]}, share);
+          if (b_n.empty()) continue;
+          int32_t c_c0, c_c1;
+          tile_range(C.cc, b_n, &c_c0, &c_c1);
+          for (int32_t ci = c_r0; ci <= c_r1; ++ci) {
+            const Interval m = meet(a_rows, {C.rc[ci], C.rc[ci + 1]});
+            if (m.empty()) continue;
+            for (int32_t cj = c_c0; cj <= c_c1; ++cj) {
+              const Interval n = meet(b_n, {C.cc[cj], C.cc[cj + 1]});
+              if (n.empty()) continue;
+              dmm_task t;
+              t.rank = rank;
+              t.a_rep = a_rep; t.a_ti = i;  t.a_tj = l;
+              t.b_rep = b_rep; t.b_ti = bi; t.b_tj = bj;
+              t.c_rep = c_rep; t.c_ti = ci; t.c_tj = cj;
+              t.m0 = m.lo; t.m1 = m.hi;
+              t.k0 = k.lo; t.k1 = k.hi;
+              t.n0 = n.lo; t.n1 = n.hi;
+              out->push_back(t);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
 struct GroupKey {
   int32_t rep, ti, tj;
   int64_t m0, n0;
@@ -193,17 +307,51 @@ void build_items(dmm_plan_t *P) {
     const Group &G = P->groups[g];
     tile_region((int64_t)g, G.m0, G.m1, G.n0, G.n1, G.c_rep, G.c_ti, G.c_tj, &seq);
   }
-  // C regions of replicas whose share of k is empty still have to be defined
-  // (their partial sum is zero): zero-fill items, one set per such C tile.
+  // Every element of every C replica has to be defined.  Regions no group writes hold a
+  // partial sum of zero: a replica of a stationary C whose share of k is empty; with
+  // Stationary B or A, the parts of a C replica that none of its ranks' ops update.  Zero-fill
+  // items cover, per C tile, the complement of its groups' rectangles (the rectangles are
+  // cells of one grid: the cuts of all of them, taken together).
   const Grid &C = P->C;
-  const int64_t K = P->A.cols;
-  for (int32_t rep = 0; rep < C.c; ++rep) {
-    if ((int64_t)rep * K / C.c < ((int64_t)rep + 1) * K / C.c) continue;
+  size_t g = 0;                                   // groups are sorted by (replica, tile row, tile column)
+  std::vector<int64_t> mc, nc;
+  std::vector<char> covered;
+  for (int32_t rep = 0; rep < C.c; ++rep)
     for (int32_t ti = 0; ti < C.gr; ++ti)
-      for (int32_t tj = 0; tj < C.gc; ++tj)
-        if (C.rc[ti] < C.rc[ti + 1] && C.cc[tj] < C.cc[tj + 1])
-          tile_region(-1, C.rc[ti], C.rc[ti + 1], C.cc[tj], C.cc[tj + 1], rep, ti, tj, &seq);
-  }
+      for (int32_t tj = 0; tj < C.gc; ++tj) {
+        const size_t g0 = g;
+        while (g < P->groups.size() && P->groups[g].c_rep == rep && P->groups[g].c_ti == ti &&
+               P->groups[g].c_tj == tj)
+          ++g;
+        if (C.rc[ti] >= C.rc[ti + 1] || C.cc[tj] >= C.cc[tj + 1]) continue;
+        mc.assign({C.rc[ti], C.rc[ti + 1]});
+        nc.assign({C.cc[tj], C.cc[tj + 1]});
+        for (size_t q = g0; q < g; ++q) {
+          mc.push_back(P->groups[q].m0); mc.push_back(P->groups[q].m1);
+          nc.push_back(P->groups[q].n0); nc.push_back(P->groups[q].n1);
+        }
+        std::sort(mc.begin(), mc.end()); mc.erase(std::unique(mc.begin(), mc.end()), mc.end());
+        std::sort(nc.begin(), nc.end()); nc.erase(std::unique(nc.begin(), nc.end()), nc.end());
+        const size_t nm = mc.size() - 1, nn = nc.size() - 1;
+        covered.assign(nm * nn, 0);
+        for (size_t q = g0; q < g; ++q) {
+          const Group &G = P->groups[q];
+          const size_t i0 = std::lower_bound(mc.begin(), mc.end(), G.m0) - mc.begin();
+          const size_t i1 = std::lower_bound(mc.begin(), mc.end(), G.m1) - mc.begin();
+          const size_t j0 = std::lower_bound(nc.begin(), nc.end(), G.n0) - nc.begin();
+          const size_t j1 = std::lower_bound(nc.begin(), nc.end(), G.n1) - nc.begin();
+          for (size_t i = i0; i < i1; ++i)
+            for (size_t j = j0; j < j1; ++j) covered[i * nn + j] = 1;
+        }
+        for (size_t i = 0; i < nm; ++i)
+          for (size_t j = 0; j < nn;) {
+            if (covered[i * nn + j]) { ++j; continue; }
+            size_t e = j;
+            while (e < nn && !covered[i * nn + e]) ++e;      // a run of uncovered cells in this row band
+            tile_region(-1, mc[i], mc[i + 1], nc[j], nc[e], rep, ti, tj, &seq);
+            j = e;
+          }
+      }
   // Deal 8 contiguous runs of the sequence to the 8 XCDs: launch slot i goes to
   // XCD i % 8, so run x occupies the slots congruent to x.
   const int64_t n = (int64_t)seq.size(), X = 8;
@@ -225,7 +373,9 @@ extern "C" {
 
 int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C, int32_t nranks,
              uint32_t flags, dmm_plan_t **out) {
-  if (!A || !B || !C || !out || flags != 0 || nranks < 1) return DMM_EINVAL;
+  if (!A || !B || !C || !out || nranks < 1) return DMM_EINVAL;
+  if (flags & ~(DMM_STATIONARY_B | DMM_STATIONARY_A)) return DMM_EINVAL;
+  if ((flags & DMM_STATIONARY_B) && (flags & DMM_STATIONARY_A)) return DMM_EINVAL;
   dmm_plan_t *P = new (std::nothrow) dmm_plan_t;
   if (!P) return DMM_ENOMEM;
   int rc = DMM_OK;
@@ -240,7 +390,11 @@ int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matri
       delete P;
       return DMM_ESHAPE;
     }
-    for (int32_t rank = 0; rank < nranks; ++rank) dmm::generate_rank(*P, rank, &P->tasks);
+    for (int32_t rank = 0; rank < nranks; ++rank) {
+      if (flags & DMM_STATIONARY_B) dmm::generate_rank_b(*P, rank, &P->tasks);
+      else if (flags & DMM_STATIONARY_A) dmm::generate_rank_a(*P, rank, &P->tasks);
+      else dmm::generate_rank(*P, rank, &P->tasks);
+    }
     dmm::group_tasks(P);
     dmm::build_items(P);
   } catch (const std::bad_alloc &) {

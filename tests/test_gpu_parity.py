@@ -83,6 +83,59 @@ def test_random_partitionings(seed, dtype):
     _run_full(cfg)
 
 
+# ---- Stationary B and Stationary A plans through the same kernels -----------------------
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_random_partitionings_stationary_b_and_a(seed, dtype, mode):
+    """Same random problems, ops attributed to the owners of B (A) tiles: other groups, other
+    C replicas written, zero-filled remainders; C starts as NaN, so a region left out shows."""
+    prob = helpers.random_problem(seed + 40, max_dim=700, allow_empty=(seed % 2 == 1))
+    cfg = dict(prob, name=f"random{seed + 40}/S{mode}", dtype=dtype, dist=("normal", 1.0), seeds=(seed, seed + 500),
+               stationary=mode)
+    _run_full(cfg)
+
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+@pytest.mark.parametrize("name,dims", [("cfg4", (515, 771, 1030)), ("cfg5", (1229, 997, 1100)), ("cfg3", (300, 333, 1100))])
+def test_families_small_stationary_b_and_a(name, dims, mode):
+    cfg = dict(workloads.scaled_config(name, *dims), stationary=mode)
+    _run_full(cfg)
+
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+def test_stationary_b_and_a_partials_per_replica(mode):
+    """With DMM_NO_REDUCE every C replica holds exactly what the oracle's execution of the
+    oracle's task list puts there (zeros included)."""
+    from paper_2510_08874_amd import binding
+    from oracle import execute as oexec
+    A_d = dict(rows=300, cols=260, row_cuts=(0, 130, 300), col_cuts=(0, 100, 260), proc_rows=2, proc_cols=2, replication=2)
+    B_d = dict(rows=260, cols=280, row_cuts=(0, 90, 260), col_cuts=(0, 150, 280), proc_rows=2, proc_cols=2, replication=2)
+    C_d = dict(rows=300, cols=280, row_cuts=(0, 170, 300), col_cuts=(0, 280), proc_rows=2, proc_cols=1, replication=4)
+    cfg = dict(name=f"partials/S{mode}", M=300, K=260, N=280, nranks=8, A=A_d, B=B_d, C=C_d, dtype="f32",
+               dist=("normal", 1.0), seeds=(71, 72), stationary=mode)
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"))
+    prob.execute(flags=binding.DMM_NO_REDUCE)
+    Ad, Bd, Cd = helpers.dist(A_d), helpers.dist(B_d), helpers.dist(C_d)
+    tasks = oplanner.plan(Ad, Bd, Cd, 8, stationary=mode)
+    A64, B64 = A.astype(np.float64), B.astype(np.float64)
+    c_tiles = oexec.execute_tasks(tasks, Ad, Bd, Cd, oexec.split_tiles(A64, Ad), oexec.split_tiles(B64, Bd))
+    scale = np.linalg.norm(A64 @ B64)
+    for rep in range(4):
+        got = prob.c_global(rep).astype(np.float64)
+        want = np.zeros((300, 280))
+        for (r, ti, tj), tile in c_tiles.items():
+            if r == rep:
+                (r0, r1), (c0, c1) = Cd.tile_bounds((ti, tj))
+                want[r0:r1, c0:c1] = tile
+        assert np.isfinite(got).all()
+        assert np.linalg.norm(got - want) / scale < 1e-5
+        assert ((want == 0) <= (got == 0)).all()        # what nobody computes is an exact zero
+    prob.close()
+
+
 # ---- full size, in the launch configuration the benchmark times -------------------
 
 @pytest.mark.parametrize("name", ["cfg2", "cfg4", "cfg5", "cfg3"])

@@ -17,10 +17,10 @@ binding = pytest.importorskip("paper_2510_08874_amd.binding")
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _both(prob):
+def _both(prob, mode="C"):
     A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
-    want = oplanner.plan(A, B, C, prob["nranks"])
-    plan = binding.Plan(prob["A"], prob["B"], prob["C"], prob["nranks"])
+    want = oplanner.plan(A, B, C, prob["nranks"], stationary=mode)
+    plan = binding.Plan(prob["A"], prob["B"], prob["C"], prob["nranks"], binding.STATIONARY_FLAGS[mode])
     return plan, want, (A, B, C)
 
 
@@ -58,10 +58,43 @@ def test_random_problems_bit_exact(seed):
     helpers.check_task_list([oplanner.Task(*t) for t in got], A, B, C, prob["nranks"])
 
 
+@pytest.mark.parametrize("mode", ["B", "A"])
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_benchmark_configs_bit_exact_stationary_b_and_a(name, mode):
+    cfg = workloads.config(name)
+    plan, want, (A, B, C) = _both(cfg, mode)
+    assert plan.tasks() == [tuple(t) for t in want]
+    order, offsets = oplanner.reorder(want)
+    assert plan.order() == order and plan.group_offsets() == offsets
+    plan.destroy()
+
+
+@pytest.mark.parametrize("mode", ["B", "A"])
+@pytest.mark.parametrize("seed", range(100))
+def test_random_problems_bit_exact_stationary_b_and_a(seed, mode):
+    prob = helpers.random_problem(seed + 2000, allow_empty=(seed % 3 == 0))
+    plan, want, (A, B, C) = _both(prob, mode)
+    got = plan.tasks()
+    assert got == [tuple(t) for t in want]
+    order, offsets = oplanner.reorder(want)
+    assert plan.order() == order and plan.group_offsets() == offsets
+    helpers.check_task_list([oplanner.Task(*t) for t in got], A, B, C, prob["nranks"], stationary=mode)
+    plan.destroy()
+
+
+def test_stationary_flags_exclusive():
+    ok = dict(rows=8, cols=8, row_cuts=(0, 8), col_cuts=(0, 8), proc_rows=1, proc_cols=1, replication=1)
+    for flags in (3, 4, 8):
+        with pytest.raises(binding.DmmError) as e:
+            binding.Plan(ok, ok, ok, 1, flags)
+        assert e.value.kind == "EINVAL"
+
+
+@pytest.mark.parametrize("mode", ["C", "B", "A"])
 @pytest.mark.parametrize("seed", range(40))
-def test_work_items_tile_every_replica_of_c_once(seed):
+def test_work_items_tile_every_replica_of_c_once(seed, mode):
     prob = helpers.random_problem(seed, max_dim=40, allow_empty=(seed % 2 == 0))
-    plan, want, (A, B, C) = _both(prob)
+    plan, want, (A, B, C) = _both(prob, mode)
     T = plan.macro_tile()
     hit = np.zeros((C.replication, prob["M"], prob["N"]), dtype=np.int32)
     groups = plan.group_offsets()
@@ -78,7 +111,13 @@ def test_work_items_tile_every_replica_of_c_once(seed):
             assert head.n0 <= it["n0"] and it["n0"] + it["n_ext"] <= head.n1
         else:
             r = it["c_rep"]
-            assert (r * prob["K"]) // C.replication == ((r + 1) * prob["K"]) // C.replication
+            if mode == "C":
+                assert (r * prob["K"]) // C.replication == ((r + 1) * prob["K"]) // C.replication
+            # a zero-fill item lies where no task writes in that replica
+            for t in want:
+                if t.c_rep == r:
+                    assert (t.m1 <= it["m0"] or it["m0"] + it["m_ext"] <= t.m0 or
+                            t.n1 <= it["n0"] or it["n0"] + it["n_ext"] <= t.n0)
     assert (hit == 1).all()
 
 
