@@ -136,6 +136,15 @@ def test_stationary_b_and_a_partials_per_replica(mode):
     prob.close()
 
 
+# ---- the MLP-shaped products of Section 5.2, four partitionings, reduced size ------------
+
+@pytest.mark.parametrize("name", ["mlp1-column", "mlp1-inner", "mlp1-outer", "mlp1-2d", "mlp2-outer", "mlp2-2d"])
+def test_mlp_partitionings_small(name):
+    base = workloads.config(name)
+    cfg = workloads.scaled_config(name, 520, base["K"] // 32 + 5, base["N"] // 32 + 3)
+    _run_full(cfg)
+
+
 # ---- full size, in the launch configuration the benchmark times -------------------
 
 @pytest.mark.parametrize("name", ["cfg2", "cfg4", "cfg5", "cfg3"])

@@ -376,6 +376,25 @@ def test_executing_stationary_b_and_a_lists_gives_the_product(seed, mode):
     helpers.check_reorder(tasks, order, offsets, C)
 
 
+@pytest.mark.parametrize("name", workloads.MLP_NAMES)
+def test_mlp_workloads_counts_and_pins(name):
+    """Section 5.2's MLP shapes over 8 ranks: task counts of the four partitionings
+    (closed forms: column block 8 products of full A; inner product 8 x 8 block pairs;
+    outer product 8 rank-(K/8) updates, one per C replica; 2-D 2 x 4 x lcm-refined k)."""
+    cfg = workloads.config(name)
+    small = workloads.scaled_config(name, 16, 24, 32)
+    A, B, C = dist(small["A"]), dist(small["B"]), dist(small["C"])
+    helpers.check_task_list(planner.plan(A, B, C, 8), A, B, C, 8)
+    A, B, C = dist(cfg["A"]), dist(cfg["B"]), dist(cfg["C"])
+    tasks = planner.plan(A, B, C, 8)
+    part = name.split("-")[1]
+    assert len(tasks) == dict(column=8, inner=64, outer=8, **{"2d": 32})[part]
+    assert sum((t.m1 - t.m0) * (t.k1 - t.k0) * (t.n1 - t.n0) for t in tasks) == cfg["M"] * cfg["K"] * cfg["N"]
+    if part == "outer":
+        assert sorted(t.c_rep for t in tasks) == list(range(8))
+        assert all(t.k1 - t.k0 == cfg["K"] // 8 for t in tasks)
+
+
 # --- grouping -----------------------------------------------------------------------
 
 @pytest.mark.parametrize("seed", range(40))

@@ -113,12 +113,50 @@ def _cfg5() -> Dict:
                 what="ragged: A 3x5 uneven, B 7 uneven row blocks, C 5x3 uneven")
 
 
+# ---------------------------------------------------------------------------
+# the MLP-shaped products of Section 5.2 (GPT-like MLP layer, hidden size 12K):
+# MLP-1 expands m x 12K to m x 48K, MLP-2 shrinks m x 48K back to m x 12K, over 8
+# ranks, in the partitionings that section compares.  m (the batch) is 8192 here.
+
+MLP_BATCH = 8192
+MLP_PARTITIONINGS = ("column", "inner", "outer", "2d")
+
+
+def _mlp(layer: int, part: str) -> Dict:
+    M = MLP_BATCH
+    K, N = (12288, 49152) if layer == 1 else (49152, 12288)
+    p = 8
+    if part == "column":      # B and C in column blocks, A on every rank (tensor-parallel linear layer)
+        A, B, C = block_desc(M, K, 1, 1, replication=p), block_desc(K, N, 1, p), block_desc(M, N, 1, p)
+        what = "column block: A replicated x8, B and C column-block x8"
+    elif part == "inner":     # row block times column block
+        A, B, C = block_desc(M, K, p, 1), block_desc(K, N, 1, p), block_desc(M, N, 4, 2)
+        what = "inner product: A row-block x8, B column-block x8, C 4x2"
+    elif part == "outer":     # column block times row block, every rank a partial C, then the replica sum
+        A, B, C = block_desc(M, K, 1, p), block_desc(K, N, p, 1), block_desc(M, N, 1, 1, replication=p)
+        what = "outer product: A column-block x8, B row-block x8, C replicated x8, replica sum"
+    elif part == "2d":
+        A, B, C = block_desc(M, K, 2, 4), block_desc(K, N, 2, 4), block_desc(M, N, 2, 4)
+        what = "2D: A, B, C in 2x4 blocks"
+    else:
+        raise KeyError(part)
+    return dict(name=f"mlp{layer}-{part}", M=M, K=K, N=N, dtype="bf16", nranks=p, A=A, B=B, C=C,
+                dist=("normal", 0.02), seeds=(6000 + 10 * layer, 6001 + 10 * layer),
+                what=f"MLP-{layer} ({what})")
+
+
 _BUILDERS = dict(cfg1=_cfg1, cfg2=_cfg2, cfg3=_cfg3, cfg4=_cfg4, cfg5=_cfg5)
 CONFIG_NAMES = tuple(_BUILDERS)
+MLP_NAMES = tuple(f"mlp{layer}-{part}" for layer in (1, 2) for part in MLP_PARTITIONINGS)
 
 
 def config(name: str) -> Dict:
-    return _BUILDERS[name]()
+    if name in _BUILDERS:
+        return _BUILDERS[name]()
+    if name in MLP_NAMES:
+        layer, part = name.split("-")
+        return _mlp(int(layer[3:]), part)
+    raise KeyError(name)
 
 
 def scaled_config(name: str, M: int, K: int, N: int) -> Dict:
