@@ -35,7 +35,10 @@ again in the design notes):
   op is emitted.
 * ``overlapping_tiles`` returns tiles in ascending (tile row, tile column).
 * the global list is the concatenation of the per-process lists by ascending
-  rank; the iteration offset of Section 4.2 is not applied.
+  rank.  The iteration offset of Section 4.2 is applied on request only: the ops
+  of the stationary tile (i, j) are rotated to start at position (i + j) modulo
+  their number ("add the two indices of the stationary tile"); tiles with one op
+  are unchanged.
 * Algorithm 2 names the op's B tile and C tile with identifiers it never
   defines; they are read as the stationary tile (k, j) and the C tile of the
   innermost loop.
@@ -309,7 +312,30 @@ def gen_ops_stationary_a(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, ra
 _GENERATORS = {"C": gen_ops_stationary_c, "B": gen_ops_stationary_b, "A": gen_ops_stationary_a}
 
 
-def plan(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, stationary: str = "C") -> List[Task]:
+def stationary_tile(t: Task, stationary: str) -> Tuple[int, int]:
+    return {"A": (t.a_ti, t.a_tj), "B": (t.b_ti, t.b_tj), "C": (t.c_ti, t.c_tj)}[stationary]
+
+
+def apply_iteration_offset(ops: Sequence[Task], stationary: str) -> List[Task]:
+    """Section 4.2, iteration offset, on one process' list: the ops of each
+    stationary tile (a contiguous run of the list) start (i + j) positions
+    later in their own cyclic order, i and j being the tile's grid indices."""
+    out: List[Task] = []
+    pos = 0
+    while pos < len(ops):
+        tile = stationary_tile(ops[pos], stationary)
+        end = pos
+        while end < len(ops) and stationary_tile(ops[end], stationary) == tile:
+            end += 1
+        run = list(ops[pos:end])
+        shift = (tile[0] + tile[1]) % len(run)
+        out.extend(run[shift:] + run[:shift])
+        pos = end
+    return out
+
+
+def plan(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, stationary: str = "C",
+         iteration_offset: bool = False) -> List[Task]:
     """Task list of the whole job: every rank's ops, ranks in ascending order.
 
     ``stationary`` names the data movement strategy of Section 4: the matrix
@@ -318,7 +344,10 @@ def plan(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, stationary: str = 
     gen = _GENERATORS[stationary]
     tasks: List[Task] = []
     for rank in range(p):
-        tasks.extend(gen(A, B, C, p, rank))
+        ops = gen(A, B, C, p, rank)
+        if iteration_offset:
+            ops = apply_iteration_offset(ops, stationary)
+        tasks.extend(ops)
     return tasks
 
 

@@ -376,6 +376,58 @@ def test_executing_stationary_b_and_a_lists_gives_the_product(seed, mode):
     helpers.check_reorder(tasks, order, offsets, C)
 
 
+# --- iteration offset (Section 4.2) -----------------------------------------------------------
+
+@pytest.mark.parametrize("g", [2, 3, 4, 5])
+def test_iteration_offset_staggers_a_process_row_and_column(g):
+    """What the offset is for: on an aligned g x g grid without it, at step s every process of
+    process row i fetches the same tile A(i, s) and every process of column j the same B(s, j);
+    with it, process (i, j) starts at l = (i + j) mod g, so at any step the g processes of a row
+    ask for g different tiles of A and those of a column for g different tiles of B (the skew of
+    Cannon's algorithm)."""
+    n = 6 * g
+    cuts = tuple(range(0, n + 1, 6))
+    X = DistMatrix(n, n, cuts, cuts, g, g, 1)
+    plain = planner.plan(X, X, X, g * g)
+    skew = planner.plan(X, X, X, g * g, iteration_offset=True)
+    per_rank = lambda tasks: [[t for t in tasks if t.rank == r] for r in range(g * g)]
+    for step in range(g):
+        for i in range(g):
+            row = [per_rank(plain)[i * g + j][step] for j in range(g)]
+            assert len({(t.a_ti, t.a_tj) for t in row}) == 1
+            row = [per_rank(skew)[i * g + j][step] for j in range(g)]
+            assert len({(t.a_ti, t.a_tj) for t in row}) == g
+        for j in range(g):
+            col = [per_rank(skew)[i * g + j][step] for i in range(g)]
+            assert len({(t.b_ti, t.b_tj) for t in col}) == g
+    for r in range(g * g):
+        i, j = divmod(r, g)
+        assert [t.a_tj for t in per_rank(skew)[r]] == [(i + j + s) % g for s in range(g)]
+
+
+@pytest.mark.parametrize("mode", ["C", "B", "A"])
+@pytest.mark.parametrize("seed", range(30))
+def test_iteration_offset_is_a_rotation_per_stationary_tile(seed, mode):
+    prob = helpers.random_problem(seed + 1300)
+    A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
+    p = prob["nranks"]
+    plain = planner.plan(A, B, C, p, stationary=mode)
+    skew = planner.plan(A, B, C, p, stationary=mode, iteration_offset=True)
+    helpers.check_task_list(skew, A, B, C, p, stationary=mode)
+    assert sorted(plain) == sorted(skew) and [t.rank for t in plain] == [t.rank for t in skew]
+    runs = {}
+    for lst, which in ((plain, 0), (skew, 1)):
+        for t in lst:
+            runs.setdefault((t.rank, planner.stationary_tile(t, mode)), ([], []))[which].append(t)
+    for (rank, (ti, tj)), (a, b) in runs.items():
+        k = (ti + tj) % len(a)
+        assert b == a[k:] + a[:k]
+    # the grouped order does not depend on it: same groups, same K-segments
+    o1, g1 = planner.reorder(plain)
+    o2, g2 = planner.reorder(skew)
+    assert g1 == g2 and [plain[i] for i in o1] == [skew[i] for i in o2]
+
+
 @pytest.mark.parametrize("name", workloads.MLP_NAMES)
 def test_mlp_workloads_counts_and_pins(name):
     """Section 5.2's MLP shapes over 8 ranks: task counts of the four partitionings
