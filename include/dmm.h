@@ -52,6 +52,10 @@ typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
  * and so decides which rank performs an op.  0 = Stationary C (Algorithm 1). */
 #define DMM_STATIONARY_B 1u /* Algorithm 2 */
 #define DMM_STATIONARY_A 2u /* its mirror image (Section 4.1: "analogous") */
+/* Iteration offset of Section 4.2: each rank's ops of stationary tile (i, j) start i + j
+ * positions later in their cyclic order.  It changes the order of the raw task list only
+ * (what a rank would fetch when); the grouped order and the results do not depend on it. */
+#define DMM_ITERATION_OFFSET 4u
 
 /* dmm_execute flags */
 #define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
@@ -113,8 +117,9 @@ typedef struct dmm_plan_s dmm_plan_t;
  * (Section 4.1), M for B, N for A.  An op's product goes to the C tile in the performing
  * rank's local replica of C; dmm_execute gives every C replica its partial sum and then
  * adds the replicas up.  Host only: makes no HIP call.  `nranks` is p, the number of
- * virtual ranks.  `flags`: 0, DMM_STATIONARY_B or DMM_STATIONARY_A (anything else, or
- * both: DMM_EINVAL).  On success *out owns the plan. */
+ * virtual ranks.  `flags`: 0, DMM_STATIONARY_B or DMM_STATIONARY_A, each optionally with
+ * DMM_ITERATION_OFFSET (anything else, or both stationary flags: DMM_EINVAL).  On success
+ * *out owns the plan. */
 int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C,
              int32_t nranks, uint32_t flags, dmm_plan_t **out);
 

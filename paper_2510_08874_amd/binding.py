@@ -20,6 +20,7 @@ DMM_NO_REDUCE = 1
 DMM_TIMING = 2
 DMM_STATIONARY_B = 1          # dmm_plan flags
 DMM_STATIONARY_A = 2
+DMM_ITERATION_OFFSET = 4
 STATIONARY_FLAGS = {"C": 0, "B": DMM_STATIONARY_B, "A": DMM_STATIONARY_A}
 STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EREPL", -4: "ENOMEM", -5: "EHIP", -6: "ELD"}
 

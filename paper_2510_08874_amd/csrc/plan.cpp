@@ -238,6 +238,32 @@ void generate_rank_a(const dmm_plan_t &P, int32_t rank, std::vector<dmm_task> *o
   }
 }
 
+// Iteration offset of Section 4.2 on one rank's ops [first, end): the ops of each stationary
+// tile (a contiguous run) are rotated to start (i + j) positions later in their cyclic order,
+// i and j being the tile's grid indices, so that the processes of a process row or column do
+// not ask for the same remote tile at the same time.
+void apply_iteration_offset(std::vector<dmm_task> *tasks, size_t first, uint32_t stationary) {
+  auto tile_of = [stationary](const dmm_task &t, int32_t *i, int32_t *j) {
+    if (stationary & DMM_STATIONARY_B) { *i = t.b_ti; *j = t.b_tj; }
+    else if (stationary & DMM_STATIONARY_A) { *i = t.a_ti; *j = t.a_tj; }
+    else { *i = t.c_ti; *j = t.c_tj; }
+  };
+  size_t pos = first;
+  const size_t end = tasks->size();
+  while (pos < end) {
+    int32_t i, j, i2, j2;
+    tile_of((*tasks)[pos], &i, &j);
+    size_t stop = pos + 1;
+    for (; stop < end; ++stop) {
+      tile_of((*tasks)[stop], &i2, &j2);
+      if (i2 != i || j2 != j) break;
+    }
+    const size_t shift = (size_t)(i + j) % (stop - pos);
+    std::rotate(tasks->begin() + pos, tasks->begin() + pos + shift, tasks->begin() + stop);
+    pos = stop;
+  }
+}
+
 struct GroupKey {
   int32_t rep, ti, tj;
   int64_t m0, n0;
@@ -374,7 +400,7 @@ extern "C" {
 int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C, int32_t nranks,
              uint32_t flags, dmm_plan_t **out) {
   if (!A || !B || !C || !out || nranks < 1) return DMM_EINVAL;
-  if (flags & ~(DMM_STATIONARY_B | DMM_STATIONARY_A)) return DMM_EINVAL;
+  if (flags & ~(DMM_STATIONARY_B | DMM_STATIONARY_A | DMM_ITERATION_OFFSET)) return DMM_EINVAL;
   if ((flags & DMM_STATIONARY_B) && (flags & DMM_STATIONARY_A)) return DMM_EINVAL;
   dmm_plan_t *P = new (std::nothrow) dmm_plan_t;
   if (!P) return DMM_ENOMEM;
@@ -391,9 +417,11 @@ int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matri
       return DMM_ESHAPE;
     }
     for (int32_t rank = 0; rank < nranks; ++rank) {
+      const size_t first = P->tasks.size();
       if (flags & DMM_STATIONARY_B) dmm::generate_rank_b(*P, rank, &P->tasks);
       else if (flags & DMM_STATIONARY_A) dmm::generate_rank_a(*P, rank, &P->tasks);
       else dmm::generate_rank(*P, rank, &P->tasks);
+      if (flags & DMM_ITERATION_OFFSET) dmm::apply_iteration_offset(&P->tasks, first, flags);
     }
     dmm::group_tasks(P);
     dmm::build_items(P);

@@ -106,7 +106,8 @@ class DeviceProblem:
         self.dtype_code = binding.DMM_BF16 if cfg["dtype"] == "bf16" else binding.DMM_F32
         tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
         self.plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"],
-                                 binding.STATIONARY_FLAGS[cfg.get("stationary", "C")])
+                                 binding.STATIONARY_FLAGS[cfg.get("stationary", "C")] |
+                                 (binding.DMM_ITERATION_OFFSET if cfg.get("iteration_offset") else 0))
         self.A = TileSet(cfg["A"], tdt, device, ld_multiple)
         self.B = TileSet(cfg["B"], tdt, device, ld_multiple)
         self.C = TileSet(cfg["C"], torch.float32, device, ld_multiple, fill=c_fill)

@@ -136,6 +136,18 @@ def test_stationary_b_and_a_partials_per_replica(mode):
     prob.close()
 
 
+def test_iteration_offset_leaves_the_result_bitwise_unchanged():
+    cfg = workloads.scaled_config("cfg5", 700, 900, 650)
+    A, B = workloads.make_operands(cfg)
+    outs = []
+    for flag in (False, True):
+        prob = _device_problem(dict(cfg, iteration_offset=flag), A, B, c_fill=float("nan"))
+        prob.execute()
+        outs.append(prob.c_global(0))
+        prob.close()
+    assert np.array_equal(outs[0], outs[1])
+
+
 # ---- the MLP-shaped products of Section 5.2, four partitionings, reduced size ------------
 
 @pytest.mark.parametrize("name", ["mlp1-column", "mlp1-inner", "mlp1-outer", "mlp1-2d", "mlp2-outer", "mlp2-2d"])

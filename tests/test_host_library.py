@@ -82,9 +82,27 @@ def test_random_problems_bit_exact_stationary_b_and_a(seed, mode):
     plan.destroy()
 
 
+@pytest.mark.parametrize("mode", ["C", "B", "A"])
+@pytest.mark.parametrize("seed", range(40))
+def test_iteration_offset_bit_exact(seed, mode):
+    prob = helpers.random_problem(seed + 3000, allow_empty=(seed % 4 == 0))
+    A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
+    want = oplanner.plan(A, B, C, prob["nranks"], stationary=mode, iteration_offset=True)
+    plan = binding.Plan(prob["A"], prob["B"], prob["C"], prob["nranks"],
+                        binding.STATIONARY_FLAGS[mode] | binding.DMM_ITERATION_OFFSET)
+    assert plan.tasks() == [tuple(t) for t in want]
+    order, offsets = oplanner.reorder(want)
+    assert plan.order() == order and plan.group_offsets() == offsets
+    # the work items do not depend on the flag
+    plain = binding.Plan(prob["A"], prob["B"], prob["C"], prob["nranks"], binding.STATIONARY_FLAGS[mode])
+    assert plan.items() == plain.items()
+    plan.destroy()
+    plain.destroy()
+
+
 def test_stationary_flags_exclusive():
     ok = dict(rows=8, cols=8, row_cuts=(0, 8), col_cuts=(0, 8), proc_rows=1, proc_cols=1, replication=1)
-    for flags in (3, 4, 8):
+    for flags in (3, 7, 8, 16):
         with pytest.raises(binding.DmmError) as e:
             binding.Plan(ok, ok, ok, 1, flags)
         assert e.value.kind == "EINVAL"
