@@ -58,15 +58,6 @@
 
 namespace dmm {
 
-#ifdef DMM_EXP_TRACE
-__device__ unsigned long long dmm_trace[4096 * 8];
-#define DMM_TRACE(slot)                                                                      \
-  do {                                                                                       \
-    if (threadIdx.x == 0) dmm_trace[blockIdx.x * 8 + (slot)] = __builtin_amdgcn_s_memtime(); \
-  } while (0)
-#else
-#define DMM_TRACE(slot)
-#endif
 
 struct SegDev {          // one K-segment of a group; pointers at the group's (m0, k0) / (k0, n0)
   const char *a;
@@ -169,9 +160,6 @@ __device__ __forceinline__ int b_lds_off(int k, int c) {
 // would wait for vmcnt(0) before every ds_read); completion is awaited explicitly with
 // s_waitcnt vmcnt before the barrier that publishes a stage.
 __device__ __forceinline__ void load_to_lds_16(gptr base, unsigned lane_off, unsigned lds_base) {
-#ifdef DMM_EXP_NODMA
-  return;
-#endif
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base)
@@ -186,9 +174,6 @@ __device__ __forceinline__ void load_to_lds_16(gptr base, unsigned lane_off, uns
 template <int IMM>
 __device__ __forceinline__ void load_to_lds_16_masked(gptr base, unsigned lane_off, unsigned lds_base,
                                                       unsigned lo, unsigned hi) {
-#ifdef DMM_EXP_NODMA
-  return;
-#endif
   asm volatile("s_add_u32 m0, %2, %3\n\ts_mov_b32 exec_lo, %4\n\ts_mov_b32 exec_hi, %5\n\t"
                "global_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1"
                :
@@ -514,9 +499,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       if constexpr (g % NW == ROT) {
         dma(std::integral_constant<int, g / NW>{}, ld_base);
       } else if (ES == 2) {
-#ifndef DMM_EXP_NOREAD
         read_op(rd_stage, rd_q, r, nxt);
-#endif
       }
       if (ES == 4 && n == 0) {                           // fp32: all reads up front (64 MFMAs follow)
 #pragma unroll
@@ -585,8 +568,6 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     lead_kpos += quiet * BK;
   };
   plan_quiet(NSTAGE - 1);
-
-  DMM_TRACE(1);
   // Two nested loops around ONE copy of the iteration: the inner loop runs the quiet iterations
   // and carries only s, the counter and the two addresses; the outer loop does the general
   // bookkeeping between runs.  (As a single loop with a rare branch at its end, every scalar the
@@ -608,9 +589,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (s + 1 < n) publish_fix(s + 1);
       }
-#ifndef DMM_EXP_NOBARRIER
       __syncthreads();                       // every wave has read stage s; step s + 1 is complete
-#endif
       sub_step(std::integral_constant<int, FM * FN>{}, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
       ++s;
       if (quiet == 0) break;
@@ -627,7 +606,6 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // nothing may land in LDS after the workgroup has gone; and the last MFMA results must have left
   // the matrix pipe before other instructions read the accumulators (18 wait states and more)
   asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 7" ::: "memory");
-  DMM_TRACE(2);
 }
 
 template <int ES>
@@ -638,13 +616,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-
-  DMM_TRACE(0);
-#ifdef DMM_EXP_TRACE
-  if (threadIdx.x == 0)
-    dmm_trace[blockIdx.x * 8 + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |
-                                    __builtin_amdgcn_s_getreg((31 << 11) | 4);
-#endif
   floatx16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -660,8 +631,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
     else if (wave == 2) run_item<ES, 2>(it, segs, lds, acc);
     else run_item<ES, 3>(it, segs, lds, acc);
   }
-
-  DMM_TRACE(3);
   // epilogue: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 tile.
   // Addresses are the item's base plus a 32-bit byte offset (the host rejects C pitches of 2^24
   // bytes and more): one add per row, the four column blocks of a row through the immediate offset.
@@ -688,11 +657,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
   };
   if (it.m_ext == BM && it.n_ext == BN) store_all(std::true_type{});
   else store_all(std::false_type{});
-  DMM_TRACE(4);
-#ifdef DMM_EXP_TRACE
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  DMM_TRACE(5);
-#endif
 }
 
 }  // namespace dmm
