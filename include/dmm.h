@@ -160,6 +160,14 @@ int dmm_execute(dmm_plan_t *p, int dtype,
 int dmm_reduce_replicas(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld,
                         int32_t origin_replica, void *hip_stream);
 
+/* broadcast_replica (Table 1): the tiles of every other replica of C become copies of the
+ * tiles of replica `origin_replica` (after dmm_execute that replica holds the product, so
+ * reduce + broadcast leaves the product in every replica).  Arguments, ownership and error
+ * behaviour as for dmm_reduce_replicas; asynchronous on `hip_stream`; a no-op when C is not
+ * replicated.  HBM-bound: c * 4 bytes per element of C. */
+int dmm_broadcast_replica(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld, int32_t origin_replica,
+                          void *hip_stream);
+
 /* Device time of the two kernels of the last dmm_execute(..., DMM_TIMING, ...) on this
  * plan, in milliseconds, excluding the work-table upload.  Blocks until those kernels
  * have finished.  A kernel that was not timed (or did not run) reports -1.  Either

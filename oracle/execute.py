@@ -68,3 +68,14 @@ def reduce_and_gather(c_tiles: Dict[TileKey, np.ndarray], C: DistMatrix, origin:
             (r0, r1), (c0, c1) = C.tile_bounds((ti, tj))
             out[r0:r1, c0:c1] = s
     return out
+
+
+def broadcast_replica(c_tiles: Dict[TileKey, np.ndarray], C: DistMatrix, origin: int = 0) -> None:
+    """Table 1, broadcast_replica: every other replica's tiles become copies of the
+    origin replica's tiles (in place, in the dictionary of tiles)."""
+    gr, gc = C.grid_shape()
+    for ti in range(gr):
+        for tj in range(gc):
+            for rep in range(C.replication):
+                if rep != origin:
+                    c_tiles[(rep, ti, tj)] = c_tiles[(origin, ti, tj)].copy()

@@ -96,6 +96,8 @@ def lib() -> C.CDLL:
         L.dmm_execute.argtypes = [P, C.c_int, P, P, P, P, P, P, C.c_uint32, P]
         L.dmm_reduce_replicas.restype = C.c_int
         L.dmm_reduce_replicas.argtypes = [P, P, P, C.c_int32, P]
+        L.dmm_broadcast_replica.restype = C.c_int
+        L.dmm_broadcast_replica.argtypes = [P, P, P, C.c_int32, P]
         L.dmm_plan_elapsed_ms.restype = C.c_int
         L.dmm_plan_elapsed_ms.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.dmm_plan_destroy.restype = None
@@ -112,7 +114,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
-           "dmm_execute", "dmm_reduce_replicas", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
+           "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
 
 
@@ -214,6 +216,14 @@ class Plan:
         rc = lib().dmm_reduce_replicas(self._h, ct, cl, origin, C.c_void_p(stream or 0))
         if rc != DMM_OK:
             raise DmmError(rc, "dmm_reduce_replicas")
+
+    def broadcast_replica(self, c_tiles: Sequence, c_ld: Sequence[int], origin: int = 0,
+                          stream: Optional[int] = None) -> None:
+        ct = _table([_ptr(t) for t in c_tiles], C.c_void_p)
+        cl = _table(list(c_ld), C.c_int64)
+        rc = lib().dmm_broadcast_replica(self._h, ct, cl, origin, C.c_void_p(stream or 0))
+        if rc != DMM_OK:
+            raise DmmError(rc, "dmm_broadcast_replica")
 
     def elapsed_ms(self):
         """(gemm_ms, reduce_ms) of the last execute with DMM_TIMING; -1 = not timed."""

@@ -101,6 +101,38 @@ __global__ __launch_bounds__(RED_NT) void reduce_replicas_kernel(const RedItem *
   }
 }
 
+// Every replica's tile except the origin's becomes a copy of the origin's (broadcast_replica,
+// Table 1).  Same work items and tables as the replica sum, `out` being the origin's tile.
+// HBM-bound: nparts * 4 bytes per element (one read, nparts - 1 writes).
+__global__ __launch_bounds__(RED_NT) void broadcast_replica_kernel(const RedItem *__restrict__ items,
+                                                                   const RedTile *__restrict__ tiles,
+                                                                   float *const *__restrict__ parts,
+                                                                   const int64_t *__restrict__ part_ld, int nparts,
+                                                                   int vec_ok) {
+  const RedItem it = items[blockIdx.x];
+  const RedTile t = tiles[it.tile];
+  float *const *pp = parts + t.part_begin;
+  const int64_t *pl = part_ld + t.part_begin;
+  if (vec_ok) {
+    const int c4 = t.cols >> 2;
+    const int total = it.nrows * c4;
+    for (int idx = threadIdx.x; idx < total; idx += RED_NT) {
+      const int r = it.row0 + idx / c4, c = (idx % c4) << 2;
+      const floatx4 v = __builtin_nontemporal_load((const floatx4 *)(t.out + (int64_t)r * t.ldo + c));
+      for (int q = 0; q < nparts; ++q)
+        if (pp[q] != t.out) __builtin_nontemporal_store(v, (floatx4 *)(pp[q] + (int64_t)r * pl[q] + c));
+    }
+  } else {
+    const int total = it.nrows * t.cols;
+    for (int idx = threadIdx.x; idx < total; idx += RED_NT) {
+      const int r = it.row0 + idx / t.cols, c = idx % t.cols;
+      const float v = t.out[(int64_t)r * t.ldo + c];
+      for (int q = 0; q < nparts; ++q)
+        if (pp[q] != t.out) pp[q][(int64_t)r * pl[q] + c] = v;
+    }
+  }
+}
+
 // ------------------------------------------------------------------ matrix-pipe rate probe
 
 // Eight independent accumulators per wave, operands held in registers: the MFMA pipe is never
@@ -637,6 +669,30 @@ int dmm_reduce_replicas(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld
     if ((rc = stage_reduce(P, c_tiles, c_ld, origin_replica, (hipStream_t)hip_stream, &red))) return rc;
     if ((rc = fire_reduce(P, red, (hipStream_t)hip_stream, false))) return rc;
     return P->C.c > 1 ? mark_use(P, (hipStream_t)hip_stream) : DMM_OK;
+  } catch (const std::bad_alloc &) {
+    return DMM_ENOMEM;
+  }
+}
+
+int dmm_broadcast_replica(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin_replica,
+                          void *hip_stream) {
+  using namespace dmm;
+  if (!P || !c_tiles || !c_ld) return DMM_EINVAL;
+  if (origin_replica < 0 || origin_replica >= P->C.c) return DMM_EINVAL;
+  int rc;
+  if ((rc = check_lds(P->C, c_ld))) return rc;
+  try {
+    if ((rc = ensure_state(P))) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    RedLaunch L;
+    if ((rc = stage_reduce(P, c_tiles, c_ld, origin_replica, stream, &L))) return rc;
+    if (L.n_items == 0) return DMM_OK;
+    char *d = P->dev->red_table.dev();
+    hipLaunchKernelGGL(broadcast_replica_kernel, dim3((unsigned)L.n_items), dim3(RED_NT), 0, stream,
+                       (const RedItem *)(d + L.o_items), (const RedTile *)(d + L.o_tiles),
+                       (float *const *)(d + L.o_parts), (const int64_t *)(d + L.o_lds), L.nparts, L.vec_ok ? 1 : 0);
+    DMM_HIP(hipGetLastError());
+    return mark_use(P, stream);
   } catch (const std::bad_alloc &) {
     return DMM_ENOMEM;
   }

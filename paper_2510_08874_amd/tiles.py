@@ -128,6 +128,11 @@ class DeviceProblem:
             stream = torch.cuda.current_stream().cuda_stream
         self.plan.reduce_replicas(self.C.tensors, self.C.ld, origin, stream)
 
+    def broadcast(self, origin: int = 0, stream: Optional[int] = None) -> None:
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        self.plan.broadcast_replica(self.C.tensors, self.C.ld, origin, stream)
+
     def c_global(self, rep: int = 0) -> np.ndarray:
         torch.cuda.synchronize()
         return self.C.gather(rep)

@@ -318,6 +318,42 @@ def test_reduce_replicas_exact(c, origin, ldm, shape):
     prob.close()
 
 
+@pytest.mark.parametrize("origin,ldm", [(0, 1), (2, 8)])
+def test_broadcast_replica_copies_the_origin_exactly(origin, ldm):
+    """reduce + broadcast = the product in every replica (Table 1), bit for bit the origin's."""
+    from oracle import execute as oexec
+    cfg = workloads.scaled_config("cfg4", 333, 280, 517)
+    cfg["C"] = dict(cfg["C"], replication=4)
+    cfg["A"] = dict(cfg["A"], replication=1)
+    cfg["B"] = dict(cfg["B"], replication=1)
+    cfg["nranks"] = 64
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
+    from paper_2510_08874_amd import binding
+    prob.execute(flags=binding.DMM_NO_REDUCE)
+    before = [prob.c_global(r) for r in range(4)]
+    prob.reduce(origin)
+    prob.broadcast(origin)
+    after = [prob.c_global(r) for r in range(4)]
+    # oracle: same partials through the oracle's reduce (ascending replica order) and broadcast
+    Cd = helpers.dist(cfg["C"])
+    want = omatmul.reduce_replicas(before)
+    tiles = {}
+    gr, gc = Cd.grid_shape()
+    for r in range(4):
+        for ti in range(gr):
+            for tj in range(gc):
+                (r0, r1), (c0, c1) = Cd.tile_bounds((ti, tj))
+                tiles[(r, ti, tj)] = (want if r == origin else before[r])[r0:r1, c0:c1]
+    oexec.broadcast_replica(tiles, Cd, origin)
+    for r in range(4):
+        for ti in range(gr):
+            for tj in range(gc):
+                (r0, r1), (c0, c1) = Cd.tile_bounds((ti, tj))
+                assert np.array_equal(after[r][r0:r1, c0:c1], tiles[(r, ti, tj)])
+    prob.close()
+
+
 def test_no_reduce_flag_leaves_partials():
     from paper_2510_08874_amd import DMM_NO_REDUCE
     cfg = workloads.scaled_config("cfg4", 512, 1024, 512)

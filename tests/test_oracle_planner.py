@@ -485,3 +485,20 @@ def test_executing_the_task_list_gives_the_product(seed):
     c_tiles = oexec.execute_tasks(tasks, A, B, C, oexec.split_tiles(Ag, A), oexec.split_tiles(Bg, B))
     got = oexec.reduce_and_gather(c_tiles, C)
     np.testing.assert_allclose(got, Ag @ Bg, rtol=0, atol=1e-12 * prob["K"])
+
+
+@pytest.mark.parametrize("origin", [0, 1])
+def test_reduce_then_broadcast_leaves_the_product_in_every_replica(origin):
+    A = DistMatrix(12, 16, (0, 5, 12), (0, 7, 16), 2, 2, 1)
+    B = DistMatrix(16, 10, (0, 3, 9, 16), (0, 4, 10), 3, 1, 1)
+    C = DistMatrix(12, 10, (0, 4, 12), (0, 6, 10), 2, 2, 2)
+    rng = np.random.default_rng(5)
+    Ag, Bg = rng.standard_normal((12, 16)), rng.standard_normal((16, 10))
+    tasks = planner.plan(A, B, C, 8)
+    c_tiles = oexec.execute_tasks(tasks, A, B, C, oexec.split_tiles(Ag, A), oexec.split_tiles(Bg, B))
+    oexec.reduce_and_gather(c_tiles, C, origin)
+    oexec.broadcast_replica(c_tiles, C, origin)
+    for rep in range(2):
+        for (ti, tj) in [(0, 0), (0, 1), (1, 0), (1, 1)]:
+            (r0, r1), (c0, c1) = C.tile_bounds((ti, tj))
+            np.testing.assert_allclose(c_tiles[(rep, ti, tj)], (Ag @ Bg)[r0:r1, c0:c1], rtol=0, atol=1e-12)
