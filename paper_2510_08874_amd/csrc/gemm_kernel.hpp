@@ -271,6 +271,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   bool lead_tail = false;                                // the segment's last step is a K tail
   bool lead_seg_safe = true;                             // no step of the segment can overrun a tile buffer
   unsigned ld_a_pitch = 0, ld_b_pitch = 0;               // row pitch in bytes of the lead segment's A and B tiles
+  unsigned ld_a_off[LOADS], ld_b_off[LOADS];             // this lane's byte offsets at those pitches (per segment)
   gptr ld_a = nullptr, ld_b = nullptr;                   // base addresses of the lead step
   gptr ld_a_next = nullptr, ld_b_next = nullptr;         // ... and of the step after it, if in the same segment
   int64_t ld_b_step = 0;                                 // bytes one K step advances in B
@@ -299,6 +300,11 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     lead_tail = sd.klen % BK != 0;
     ld_a_pitch = (unsigned)(sd.lda * ES);
     ld_b_pitch = (unsigned)(sd.ldb * ES);
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      ld_a_off[i] = a_offset(ld_a_pitch, i);
+      ld_b_off[i] = b_offset(ld_b_pitch, i);
+    }
     ld_b_step = (int64_t)BK * sd.ldb * ES;
     int64_t a_left, b_left, a_need, b_need;
     step_geometry(sd, 0, ld_a, ld_b, a_left, b_left);
@@ -339,12 +345,12 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
           const unsigned sa = lds_base + stage * STAGE + wave * 1024;
 #pragma unroll
           for (int i = 0; i < LOADS; ++i) {
-            const unsigned off = a_offset(ld_a_pitch, i);
+            const unsigned off = ld_a_off[i];
             if ((int64_t)off + 16 <= a_left) load_to_lds_16(ld_a, off, sa + i * (NW * 1024));
           }
 #pragma unroll
           for (int i = 0; i < LOADS; ++i) {
-            const unsigned off = b_offset(ld_b_pitch, i);
+            const unsigned off = ld_b_off[i];
             if ((int64_t)off + 16 <= b_left) load_to_lds_16(ld_b, off, sa + A_STAGE + i * (NW * 1024));
           }
         }
@@ -358,9 +364,9 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   auto dma = [&](auto jc, unsigned stage_base) {
     constexpr int j = decltype(jc)::value;
     if constexpr (j < LOADS)
-      load_to_lds_16_masked<j * (NW * 1024)>(ld_a, a_offset(ld_a_pitch, j), stage_base, ld_lo, ld_hi);
+      load_to_lds_16_masked<j * (NW * 1024)>(ld_a, ld_a_off[j], stage_base, ld_lo, ld_hi);
     else
-      load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, b_offset(ld_b_pitch, j - LOADS), stage_base,
+      load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, ld_b_off[j - LOADS], stage_base,
                                                                  ld_lo, ld_hi);
   };
 
