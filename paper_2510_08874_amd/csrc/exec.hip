@@ -374,14 +374,16 @@ int check_lds(const Grid &G, const int64_t *ld) {
 // The replica sum in two halves, so that dmm_execute can put the table upload in front of the
 // GEMM launch and nothing but the launch itself behind it.
 struct RedLaunch {
+  char *dev_base = nullptr;   // device address of the buffer the offsets below refer to
   size_t n_items = 0;
   size_t o_items = 0, o_tiles = 0, o_parts = 0, o_lds = 0;
   int nparts = 0;
   bool vec_ok = true;
 };
 
-int stage_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, hipStream_t stream,
-                 RedLaunch *L) {
+// Appends the replica sum's tables to *h at byte offset `base` (a multiple of 8).
+int build_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, std::vector<char> *hp,
+                 size_t base, RedLaunch *L) {
   const Grid &C = P->C;
   L->n_items = 0;
   if (C.c <= 1) return DMM_OK;
@@ -426,20 +428,18 @@ int stage_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32
       tiles.push_back(t);
     }
   if (items.empty()) return DMM_OK;
-  // one buffer: items | tiles | part pointers | part lds   (all 8-byte aligned)
-  const size_t o_items = 0;
+  // items | tiles | part pointers | part lds   (all 8-byte aligned)
+  const size_t o_items = base;
   const size_t o_tiles = o_items + items.size() * sizeof(RedItem);
   const size_t o_parts = o_tiles + tiles.size() * sizeof(RedTile);
   const size_t o_lds = o_parts + parts.size() * sizeof(void *);
   const size_t total = o_lds + part_ld.size() * sizeof(int64_t);
-  std::vector<char> &h = P->dev->host;
+  std::vector<char> &h = *hp;
   h.resize(total);
   std::memcpy(h.data() + o_items, items.data(), items.size() * sizeof(RedItem));
   std::memcpy(h.data() + o_tiles, tiles.data(), tiles.size() * sizeof(RedTile));
   std::memcpy(h.data() + o_parts, parts.data(), parts.size() * sizeof(void *));
   std::memcpy(h.data() + o_lds, part_ld.data(), part_ld.size() * sizeof(int64_t));
-  int rc = P->dev->red_table.upload(h.data(), total, stream);
-  if (rc) return rc;
   L->n_items = items.size();
   L->o_items = o_items;
   L->o_tiles = o_tiles;
@@ -450,10 +450,22 @@ int stage_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32
   return DMM_OK;
 }
 
+// The replica sum's (or the broadcast's) tables alone, uploaded through the plan's second buffer.
+int stage_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, hipStream_t stream,
+                 RedLaunch *L) {
+  std::vector<char> &h = P->dev->host;
+  h.clear();
+  int rc = build_reduce(P, c_tiles, c_ld, origin, &h, 0, L);
+  if (rc || L->n_items == 0) return rc;
+  if ((rc = P->dev->red_table.upload(h.data(), h.size(), stream))) return rc;
+  L->dev_base = P->dev->red_table.dev();
+  return DMM_OK;
+}
+
 int fire_reduce(dmm_plan_t *P, const RedLaunch &L, hipStream_t stream, bool timed) {
   if (L.n_items == 0) return DMM_OK;
   int rc;
-  char *d = P->dev->red_table.dev();
+  char *d = L.dev_base;
   const size_t o_items = L.o_items, o_tiles = L.o_tiles, o_parts = L.o_parts, o_lds = L.o_lds;
   const int nparts = L.nparts;
   const bool vec_ok = L.vec_ok;
@@ -558,16 +570,22 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   hipStream_t stream = (hipStream_t)hip_stream;
   try {
     if ((rc = ensure_state(P))) return rc;
-    // both work tables go up first, so that the replica sum follows the GEMM without a copy in between
+    // The tables of both kernels go up in one copy in front of the GEMM launch, so that nothing
+    // but the launch separates the replica sum from the GEMM.
     RedLaunch red;
-    if (!(flags & DMM_NO_REDUCE) && (rc = stage_reduce(P, c_tiles, c_ld, 0, stream, &red))) return rc;
     const size_t n_items = P->items.size();
     const size_t n_segs = P->tasks.size();
+    const size_t o_segs = n_items * sizeof(ItemDev);
+    const size_t total = n_items > 0 ? o_segs + n_segs * sizeof(SegDev) : 0;
+    std::vector<char> &h = P->dev->host;
+    h.clear();
+    h.resize(total);
+    if (!(flags & DMM_NO_REDUCE) && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, total, &red))) return rc;
+    if (n_items == 0 && red.n_items > 0) {
+      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream))) return rc;
+      red.dev_base = P->dev->gemm_table.dev();
+    }
     if (n_items > 0) {
-      const size_t o_segs = n_items * sizeof(ItemDev);
-      const size_t total = o_segs + n_segs * sizeof(SegDev);
-      std::vector<char> &h = P->dev->host;
-      h.resize(total);
       ItemDev *hi = (ItemDev *)h.data();
       SegDev *hs = (SegDev *)(h.data() + o_segs);
       // segments in grouped order: segment index = position in `order`
@@ -615,7 +633,8 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         d.n_ext = w.n_ext;
         hi[i] = d;
       }
-      if ((rc = P->dev->gemm_table.upload(h.data(), total, stream))) return rc;
+      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream))) return rc;
+      red.dev_base = P->dev->gemm_table.dev();
       const ItemDev *di = (const ItemDev *)P->dev->gemm_table.dev();
       const SegDev *ds = (const SegDev *)(P->dev->gemm_table.dev() + o_segs);
       if (timed) {
@@ -687,7 +706,7 @@ int dmm_broadcast_replica(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_
     RedLaunch L;
     if ((rc = stage_reduce(P, c_tiles, c_ld, origin_replica, stream, &L))) return rc;
     if (L.n_items == 0) return DMM_OK;
-    char *d = P->dev->red_table.dev();
+    char *d = L.dev_base;
     hipLaunchKernelGGL(broadcast_replica_kernel, dim3((unsigned)L.n_items), dim3(RED_NT), 0, stream,
                        (const RedItem *)(d + L.o_items), (const RedTile *)(d + L.o_tiles),
                        (float *const *)(d + L.o_parts), (const int64_t *)(d + L.o_lds), L.nparts, L.vec_ok ? 1 : 0);
