@@ -257,8 +257,25 @@ SlabPool &pool() {
   return *p;
 }
 
-// upload() copies host bytes to the slab's device buffer asynchronously on the
-// caller's stream, and skips the copy when those bytes are already resident.
+// One stream per device for work-table uploads (default priority, created on first use and
+// kept for the life of the process): a table copy then overlaps whatever the caller's stream
+// is still running, instead of queueing behind it.
+int copy_stream(hipStream_t *out) {
+  static std::mutex mu;
+  static hipStream_t streams[64] = {};
+  int dev = 0;
+  DMM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return DMM_EINVAL;
+  std::lock_guard<std::mutex> g(mu);
+  if (!streams[dev]) DMM_HIP(hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking));
+  *out = streams[dev];
+  return DMM_OK;
+}
+
+// upload() copies host bytes to the slab's device buffer on the copy stream and makes the
+// caller's stream wait for that copy; it skips the copy when those bytes are already resident.
+// `busy_until`, if given, is an event after which earlier readers of the device buffer (kernels
+// of a previous call on this plan) are done: the copy waits for it.
 struct Uploader {
   Slab slab;
   bool ev_used[2] = {false, false};
@@ -267,9 +284,13 @@ struct Uploader {
   bool valid = false;
 
   char *dev() const { return slab.dev; }
-  int upload(const void *src, size_t bytes, hipStream_t stream) {
-    if (valid && resident.size() == bytes && (bytes == 0 || std::memcmp(resident.data(), src, bytes) == 0))
+  int upload(const void *src, size_t bytes, hipStream_t stream, hipEvent_t busy_until = nullptr) {
+    if (valid && resident.size() == bytes && (bytes == 0 || std::memcmp(resident.data(), src, bytes) == 0)) {
+      // already resident; the caller's stream (possibly another one than last time) still has to
+      // be ordered behind the copy that put it there
+      if (bytes != 0 && ev_used[cur]) DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
       return DMM_OK;
+    }
     if (bytes == 0) return DMM_OK;
     if (bytes > slab.cap) {
       // growing: the old slab may still be read by enqueued work of this plan
@@ -285,8 +306,13 @@ struct Uploader {
     cur ^= 1;
     if (ev_used[cur]) DMM_HIP(hipEventSynchronize(slab.ev[cur]));  // slot last used two uploads ago
     std::memcpy(slab.pinned[cur], src, bytes);
-    DMM_HIP(hipMemcpyAsync(slab.dev, slab.pinned[cur], bytes, hipMemcpyHostToDevice, stream));
-    DMM_HIP(hipEventRecord(slab.ev[cur], stream));
+    hipStream_t cs = nullptr;
+    int rc = copy_stream(&cs);
+    if (rc) return rc;
+    if (busy_until) DMM_HIP(hipStreamWaitEvent(cs, busy_until, 0));
+    DMM_HIP(hipMemcpyAsync(slab.dev, slab.pinned[cur], bytes, hipMemcpyHostToDevice, cs));
+    DMM_HIP(hipEventRecord(slab.ev[cur], cs));
+    DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
     ev_used[cur] = true;
     resident.assign((const char *)src, (const char *)src + bytes);
     valid = true;
@@ -347,6 +373,9 @@ int ensure_state(dmm_plan_t *P) {
   }
   return DMM_OK;
 }
+
+// Event after which the kernels of this plan's earlier calls have finished (null: none yet).
+hipEvent_t busy_event(dmm_plan_t *P) { return P->dev->last_use_recorded ? P->dev->last_use : nullptr; }
 
 int mark_use(dmm_plan_t *P, hipStream_t stream) {
   DMM_HIP(hipEventRecord(P->dev->last_use, stream));
@@ -457,7 +486,7 @@ int stage_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32
   h.clear();
   int rc = build_reduce(P, c_tiles, c_ld, origin, &h, 0, L);
   if (rc || L->n_items == 0) return rc;
-  if ((rc = P->dev->red_table.upload(h.data(), h.size(), stream))) return rc;
+  if ((rc = P->dev->red_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
   L->dev_base = P->dev->red_table.dev();
   return DMM_OK;
 }
@@ -582,7 +611,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
     h.resize(total);
     if (!(flags & DMM_NO_REDUCE) && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, total, &red))) return rc;
     if (n_items == 0 && red.n_items > 0) {
-      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream))) return rc;
+      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
       red.dev_base = P->dev->gemm_table.dev();
     }
     if (n_items > 0) {
@@ -633,7 +662,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         d.n_ext = w.n_ext;
         hi[i] = d;
       }
-      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream))) return rc;
+      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
       red.dev_base = P->dev->gemm_table.dev();
       const ItemDev *di = (const ItemDev *)P->dev->gemm_table.dev();
       const SegDev *ds = (const SegDev *)(P->dev->gemm_table.dev() + o_segs);
