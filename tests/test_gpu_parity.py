@@ -83,6 +83,43 @@ def test_random_partitionings(seed, dtype):
     _run_full(cfg)
 
 
+# ---- the paper's own validation sweep (Section 5.2) ---------------------------------------------
+
+def _family(kind, rows, cols, p_rep, c):
+    """row block / column block / 2-D block over the ranks of one replica (p_rep of them)."""
+    if kind == "row":
+        return workloads.block_desc(rows, cols, p_rep, 1, replication=c)
+    if kind == "col":
+        return workloads.block_desc(rows, cols, 1, p_rep, replication=c)
+    g = 2 if p_rep >= 4 else 1
+    return workloads.block_desc(rows, cols, g, p_rep // g, replication=c)
+
+
+@pytest.mark.parametrize("reps", [(1, 1, 1), (2, 2, 2), (4, 1, 2), (1, 8, 4), (8, 8, 8)])
+def test_all_combinations_of_row_column_and_2d_blocks(reps):
+    """Every combination of row block, column block and 2-D block for A, B and C (27 of them)
+    under several replication triples, 8 ranks, sizes that split unevenly: all through one plan
+    + execute each, element by element against the fp64 product."""
+    p, M, K, N = 8, 141, 203, 167
+    A, B = None, None
+    worst = 0.0
+    for ka in ("row", "col", "2d"):
+        for kb in ("row", "col", "2d"):
+            for kc in ("row", "col", "2d"):
+                cfg = dict(name=f"{ka}-{kb}-{kc}/{reps}", M=M, K=K, N=N, nranks=p, dtype="bf16",
+                           A=_family(ka, M, K, p // reps[0], reps[0]), B=_family(kb, K, N, p // reps[1], reps[1]),
+                           C=_family(kc, M, N, p // reps[2], reps[2]), dist=("normal", 1.0), seeds=(31, 32))
+                if A is None:
+                    A, B = workloads.make_operands(cfg)
+                    A64, B64 = _to_f64(A, cfg), _to_f64(B, cfg)
+                    C_ref = A64 @ B64
+                prob = _device_problem(cfg, A, B, c_fill=float("nan"))
+                prob.execute()
+                worst = max(worst, _check(prob.c_global(0), C_ref, A64, B64, cfg, cfg["name"]))
+                prob.close()
+    assert worst <= TOL["bf16"]
+
+
 # ---- Stationary B and Stationary A plans through the same kernels -----------------------
 
 @pytest.mark.parametrize("mode", ["B", "A"])
