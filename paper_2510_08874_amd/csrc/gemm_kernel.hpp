@@ -657,7 +657,8 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
         if (FULL || row0 + dr < it.m_ext) {
 #pragma unroll
           for (int j = 0; j < FN; ++j)
-            if (FULL || col0 + j * 32 < it.n_ext) *(gfloat_ptr)(cbytes + o + j * 128) = acc[i][j][r];
+            if (FULL || col0 + j * 32 < it.n_ext)
+              __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(cbytes + o + j * 128));
         }
       }
   };
