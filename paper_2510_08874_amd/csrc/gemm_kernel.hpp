@@ -370,7 +370,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
                                                                  ld_lo, ld_hi);
   };
 
-  // After this wave's loads of the lag step have landed: every lane repairs its own slots of
+  // After this wave's loads of the step being published have landed: every lane repairs its own slots of
   // `stage`: chunks it was masked out of are read element by element, and everything at
   // k >= remaining segment length is zeroed on both operands (so that stale or non-finite
   // bytes cannot reach a sum).  Rare: K tails and tile-buffer ends only.
@@ -386,11 +386,11 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       ++seg;
     }
     const SegDev lsd = segs[it.seg_begin + seg];
-    const int lag_kpos = (t - first) * BK;
+    const int kpos = (t - first) * BK;
     gptr pa, pb;
     int64_t a_left, b_left;
-    step_geometry(lsd, lag_kpos, pa, pb, a_left, b_left);
-    const int krem = lsd.klen - lag_kpos;
+    step_geometry(lsd, kpos, pa, pb, a_left, b_left);
+    const int krem = lsd.klen - kpos;
     char *sa = lds + stage * STAGE + wave * 1024 + lane * 16;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
