@@ -145,9 +145,14 @@ int32_t dmm_plan_macro_tile(const dmm_plan_t *p);           /* edge of the squar
  * stay valid until the stream work completes.  Asynchronous: returns after
  * enqueueing.  Every element of every C replica is written exactly once with
  * that replica's partial sum; then, unless DMM_NO_REDUCE, replica 0 receives
- * the sum over replicas (other replicas keep their partials).  The first call
- * on a plan allocates the plan's device work table; later calls allocate
- * nothing and do not synchronise. */
+ * the sum over replicas (other replicas keep their partials).  When the number
+ * of macro-tiles leaves most of the device idle in the last round of workgroups,
+ * those macro-tiles are cut along K into runs whose partial sums go through a
+ * scratch buffer and are added in ascending k (fixed cut, fixed order: results
+ * stay bitwise reproducible on a given device).  The first call on a plan takes
+ * the plan's device work table (and, if needed, that scratch buffer) from a
+ * process-wide pool, allocating only when the pool has none that fits; later
+ * calls with the same arguments allocate nothing and do not synchronise. */
 int dmm_execute(dmm_plan_t *p, int dtype,
                 const void *const *a_tiles, const int64_t *a_ld,
                 const void *const *b_tiles, const int64_t *b_ld,

@@ -3,10 +3,12 @@
 // (gemm_kernel.hpp), and the replica-sum kernel (reduce_replicas of Table 1).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "gemm_kernel.hpp"
@@ -131,6 +133,52 @@ __global__ __launch_bounds__(RED_NT) void broadcast_replica_kernel(const RedItem
         if (pp[q] != t.out) pp[q][(int64_t)r * pl[q] + c] = v;
     }
   }
+}
+
+// ------------------------------------------------------------------ K-split of the last round
+
+// When the number of macro-tiles is not a multiple of the number of CUs, the last round of
+// workgroups leaves CUs idle.  The host then cuts each macro-tile of that round into runs of K
+// steps, one workgroup each, which write their partial sums into a scratch buffer (256 x 256
+// fp32 per run); this kernel adds the runs of a macro-tile up in ascending k and writes C.  Fixed
+// cut, fixed order, no atomics: the result is deterministic.
+struct FixItem {
+  float *dst;            // top-left of the macro-tile in the C tile
+  int64_t ldc;
+  const float *parts;    // nparts consecutive 256 x 256 tiles
+  int32_t m_ext, n_ext;
+  int32_t nparts, pad;
+};
+constexpr int FIX_ROWS = 4;           // rows of a macro-tile one workgroup sums: 4 rows x 64 float4 columns
+
+__global__ __launch_bounds__(256) void sum_parts_kernel(const FixItem *__restrict__ fixes) {
+  const FixItem f = fixes[blockIdx.x / (BM / FIX_ROWS)];
+  const int r = (blockIdx.x % (BM / FIX_ROWS)) * FIX_ROWS + (threadIdx.x >> 6);
+  const int c = (threadIdx.x & 63) << 2;
+  if (r >= f.m_ext || c >= f.n_ext) return;
+  const float *p = f.parts + (int64_t)r * BN + c;
+  floatx4 s = __builtin_nontemporal_load((const floatx4 *)p);
+  // eight runs' loads in flight at a time; the adds follow in ascending k (the order is part of the result)
+  constexpr int QB = 8;
+  for (int q0 = 1; q0 < f.nparts; q0 += QB) {
+    floatx4 v[QB];
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq)
+      if (q0 + qq < f.nparts) v[qq] = __builtin_nontemporal_load((const floatx4 *)(p + (int64_t)(q0 + qq) * (BM * BN)));
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq)
+      if (q0 + qq < f.nparts) {
+        s.x = s.x + v[qq].x;
+        s.y = s.y + v[qq].y;
+        s.z = s.z + v[qq].z;
+        s.w = s.w + v[qq].w;
+      }
+  }
+  float *d = f.dst + (int64_t)r * f.ldc + c;
+  const float e[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+  for (int x = 0; x < 4; ++x)
+    if (c + x < f.n_ext) __builtin_nontemporal_store(e[x], d + x);
 }
 
 // ------------------------------------------------------------------ matrix-pipe rate probe
@@ -324,7 +372,57 @@ struct Uploader {
   }
 };
 
+// Device-only buffers for the partial sums of K-split items, recycled like the slabs.
+class ScratchPool {
+ public:
+  int acquire(size_t bytes, char **out, size_t *cap) {
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      int best = -1;
+      for (size_t i = 0; i < free_.size(); ++i)
+        if (free_[i].second >= bytes && (best < 0 || free_[i].second < free_[(size_t)best].second)) best = (int)i;
+      if (best >= 0) {
+        *out = free_[(size_t)best].first;
+        *cap = free_[(size_t)best].second;
+        free_.erase(free_.begin() + best);
+        return DMM_OK;
+      }
+    }
+    size_t want = (size_t)4 << 20;
+    while (want < bytes) want *= 2;
+    char *p = nullptr;
+    hipError_t e = hipMalloc((void **)&p, want);
+    if (e != hipSuccess) {
+      g_last_hip_error = (int)e;
+      return e == hipErrorOutOfMemory ? DMM_ENOMEM : DMM_EHIP;
+    }
+    *out = p;
+    *cap = want;
+    return DMM_OK;
+  }
+  // The caller guarantees that no stream work still uses the buffer.
+  void release(char **p, size_t *cap) {
+    if (!*p) return;
+    std::lock_guard<std::mutex> g(mu_);
+    if (free_.size() < 8) free_.push_back({*p, *cap});
+    else (void)hipFree(*p);
+    *p = nullptr;
+    *cap = 0;
+  }
+
+ private:
+  std::mutex mu_;
+  std::vector<std::pair<char *, size_t>> free_;
+};
+
+ScratchPool &scratch_pool() {
+  static ScratchPool *p = new ScratchPool;   // never destroyed, like the slab pool
+  return *p;
+}
+
 struct DeviceState {
+  char *split_buf = nullptr;   // partial sums of K-split items
+  size_t split_cap = 0;
   Uploader gemm_table;   // [ItemDev x items][SegDev x segments]
   Uploader red_table;    // [RedItem][RedTile][part pointers][part lds]
   std::vector<char> host;  // scratch for table assembly
@@ -340,6 +438,7 @@ void destroy_device_state(DeviceState *d) {
   if (d->last_use_recorded) (void)hipEventSynchronize(d->last_use);
   d->gemm_table.release();
   d->red_table.release();
+  scratch_pool().release(&d->split_buf, &d->split_cap);
   if (d->last_use) (void)hipEventDestroy(d->last_use);
   for (int i = 0; i < 2; ++i) {
     if (d->t_gemm[i]) (void)hipEventDestroy(d->t_gemm[i]);
@@ -371,6 +470,23 @@ int ensure_state(dmm_plan_t *P) {
     if (!P->dev) return DMM_ENOMEM;
     DMM_HIP(hipEventCreateWithFlags(&P->dev->last_use, hipEventDisableTiming));
   }
+  return DMM_OK;
+}
+
+// Compute units of the current device (queried once per device).
+int device_cus(int *out) {
+  static std::mutex mu;
+  static int cus[64] = {};
+  int dev = 0;
+  DMM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return DMM_EINVAL;
+  std::lock_guard<std::mutex> g(mu);
+  if (!cus[dev]) {
+    hipDeviceProp_t prop;
+    DMM_HIP(hipGetDeviceProperties(&prop, dev));
+    cus[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+  }
+  *out = cus[dev];
   return DMM_OK;
 }
 
@@ -599,71 +715,144 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   hipStream_t stream = (hipStream_t)hip_stream;
   try {
     if ((rc = ensure_state(P))) return rc;
-    // The tables of both kernels go up in one copy in front of the GEMM launch, so that nothing
-    // but the launch separates the replica sum from the GEMM.
+    // The tables of all kernels go up in one copy in front of the GEMM launch, so that nothing
+    // but the launches separates them:  ItemDev[] | SegDev[] | FixItem[] | replica-sum tables.
     RedLaunch red;
-    const size_t n_items = P->items.size();
+    const size_t n_plan_items = P->items.size();
     const size_t n_segs = P->tasks.size();
+    std::vector<SegDev> hs(n_segs);
+    std::vector<ItemDev> hi(n_plan_items);
+    std::vector<FixItem> fixes;
+    // segments in grouped order: segment index = position in `order`
+    for (size_t pos = 0; pos < n_segs; ++pos) {
+      const dmm_task &t = P->tasks[P->order[pos]];
+      const int64_t ai = P->A.table_index(t.a_rep, t.a_ti, t.a_tj);
+      const int64_t bi = P->B.table_index(t.b_rep, t.b_ti, t.b_tj);
+      if (!a_tiles[ai] || !b_tiles[bi]) return DMM_EINVAL;
+      SegDev sg;
+      sg.lda = a_ld[ai];
+      sg.ldb = b_ld[bi];
+      sg.a = (const char *)a_tiles[ai] + ((t.m0 - P->A.rc[t.a_ti]) * sg.lda + (t.k0 - P->A.cc[t.a_tj])) * es;
+      sg.b = (const char *)b_tiles[bi] + ((t.k0 - P->B.rc[t.b_ti]) * sg.ldb + (t.n0 - P->B.cc[t.b_tj])) * es;
+      // bytes that may be read from the segment's origin to the end of the tile buffer
+      // ((rows - 1) * ld + cols elements are guaranteed to exist)
+      const int64_t a_h = P->A.rc[t.a_ti + 1] - P->A.rc[t.a_ti], a_w = P->A.cc[t.a_tj + 1] - P->A.cc[t.a_tj];
+      const int64_t b_h = P->B.rc[t.b_ti + 1] - P->B.rc[t.b_ti], b_w = P->B.cc[t.b_tj + 1] - P->B.cc[t.b_tj];
+      sg.a_bytes = ((a_h - 1) * sg.lda + a_w - ((t.m0 - P->A.rc[t.a_ti]) * sg.lda + (t.k0 - P->A.cc[t.a_tj]))) * es;
+      sg.b_bytes = ((b_h - 1) * sg.ldb + b_w - ((t.k0 - P->B.rc[t.b_ti]) * sg.ldb + (t.n0 - P->B.cc[t.b_tj]))) * es;
+      sg.klen = (int32_t)(t.k1 - t.k0);
+      sg.pad = 0;
+      hs[pos] = sg;
+    }
+    for (size_t i = 0; i < n_plan_items; ++i) {
+      const dmm_work_item &w = P->items[i];
+      const int64_t ci = P->C.table_index(w.c_rep, w.c_ti, w.c_tj);
+      if (!c_tiles[ci]) return DMM_EINVAL;
+      ItemDev d;
+      d.ldc = c_ld[ci];
+      d.c = (float *)c_tiles[ci] + (w.m0 - P->C.rc[w.c_ti]) * d.ldc + (w.n0 - P->C.cc[w.c_tj]);
+      if (w.group >= 0) {
+        const Group &G = P->groups[(size_t)w.group];
+        d.seg_begin = (int32_t)G.first;
+        d.nsteps = 0;
+        for (int64_t q = 0; q < G.count; ++q) d.nsteps += (int32_t)((hs[(size_t)(G.first + q)].klen + bk - 1) / bk);
+        d.m_off = (int32_t)(w.m0 - G.m0);
+        d.n_off = (int32_t)(w.n0 - G.n0);
+      } else {
+        d.seg_begin = 0;
+        d.nsteps = 0;
+        d.m_off = d.n_off = 0;
+      }
+      d.m_ext = w.m_ext;
+      d.n_ext = w.n_ext;
+      d.first_step = 0;
+      d.pad = 0;
+      hi[i] = d;
+    }
+    // K-split of the last round (see sum_parts_kernel): with W working items on `cus` CUs the
+    // last W % cus of them run alone; if they are few, each is cut into up to cus / (W % cus) runs
+    // of at least MIN_RUN K steps.  Run 0 takes the item's place in the launch order, the others
+    // go to the end; all of them write to the scratch buffer.  A run pays a prologue and an
+    // epilogue of its own (about 13 K steps' worth) and the pass that adds the runs up is one more
+    // launch: measured, runs of 32 steps lose (2048^3: 45 -> 66 us), so a run is 64 steps at least.
+    constexpr int32_t MIN_RUN = 64;
+    int cus = 0;
+    if ((rc = device_cus(&cus))) return rc;
+    size_t working = 0;
+    for (const ItemDev &d : hi) working += d.nsteps > 0;
+    const size_t tail = working % (size_t)cus;
+    size_t n_runs = 0;
+    if (tail > 0 && tail <= (size_t)cus / 2) {
+      const int32_t max_runs = (int32_t)((size_t)cus / tail);
+      size_t seen = 0;
+      for (size_t i = n_plan_items; i-- > 0 && seen < tail;) {
+        if (hi[i].nsteps <= 0) continue;
+        ++seen;
+        int32_t runs = std::min(max_runs, hi[i].nsteps / MIN_RUN);
+        if (runs < 2) continue;
+        const int32_t per = (hi[i].nsteps + runs - 1) / runs;
+        runs = (hi[i].nsteps + per - 1) / per;
+        const ItemDev whole = hi[i];
+        FixItem f;
+        f.dst = whole.c;
+        f.ldc = whole.ldc;
+        f.parts = (const float *)(uintptr_t)(n_runs * sizeof(float) * BM * BN);   // offset for now, base added below
+        f.m_ext = whole.m_ext;
+        f.n_ext = whole.n_ext;
+        f.nparts = runs;
+        f.pad = 0;
+        fixes.push_back(f);
+        for (int32_t j = 0; j < runs; ++j) {
+          ItemDev r = whole;
+          r.c = (float *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);       // offset for now
+          r.ldc = BN;
+          r.first_step = j * per;
+          r.nsteps = std::min(per, whole.nsteps - j * per);
+          r.pad = 1;                                                                          // marks "c is a scratch offset"
+          if (j == 0) hi[i] = r;
+          else hi.push_back(r);
+        }
+        n_runs += (size_t)runs;
+      }
+    }
+    if (n_runs > 0) {
+      // the scratch buffer is shared by all calls on this plan: order this call behind the last one
+      // (a no-op when both are on the same stream)
+      if (P->dev->last_use_recorded) DMM_HIP(hipStreamWaitEvent(stream, P->dev->last_use, 0));
+      const size_t need = n_runs * sizeof(float) * BM * BN;
+      if (need > P->dev->split_cap) {
+        // growing: earlier calls on this plan may still use the old buffer
+        if (P->dev->split_buf) {
+          DMM_HIP(hipStreamSynchronize(stream));
+          scratch_pool().release(&P->dev->split_buf, &P->dev->split_cap);
+        }
+        if ((rc = scratch_pool().acquire(need, &P->dev->split_buf, &P->dev->split_cap))) return rc;
+      }
+      for (ItemDev &d : hi)
+        if (d.pad == 1) {
+          d.c = (float *)(P->dev->split_buf + (uintptr_t)d.c);
+          d.pad = 0;
+        }
+      for (FixItem &f : fixes) f.parts = (const float *)(P->dev->split_buf + (uintptr_t)f.parts);
+    }
+    const size_t n_items = hi.size();
     const size_t o_segs = n_items * sizeof(ItemDev);
-    const size_t total = n_items > 0 ? o_segs + n_segs * sizeof(SegDev) : 0;
+    const size_t o_fix = o_segs + n_segs * sizeof(SegDev);
+    const size_t total = n_items > 0 ? o_fix + fixes.size() * sizeof(FixItem) : 0;
     std::vector<char> &h = P->dev->host;
     h.clear();
     h.resize(total);
+    if (n_items > 0) {
+      std::memcpy(h.data(), hi.data(), n_items * sizeof(ItemDev));
+      std::memcpy(h.data() + o_segs, hs.data(), n_segs * sizeof(SegDev));
+      if (!fixes.empty()) std::memcpy(h.data() + o_fix, fixes.data(), fixes.size() * sizeof(FixItem));
+    }
     if (!(flags & DMM_NO_REDUCE) && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, total, &red))) return rc;
-    if (n_items == 0 && red.n_items > 0) {
+    if (!h.empty()) {
       if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
       red.dev_base = P->dev->gemm_table.dev();
     }
     if (n_items > 0) {
-      ItemDev *hi = (ItemDev *)h.data();
-      SegDev *hs = (SegDev *)(h.data() + o_segs);
-      // segments in grouped order: segment index = position in `order`
-      for (size_t pos = 0; pos < n_segs; ++pos) {
-        const dmm_task &t = P->tasks[P->order[pos]];
-        const int64_t ai = P->A.table_index(t.a_rep, t.a_ti, t.a_tj);
-        const int64_t bi = P->B.table_index(t.b_rep, t.b_ti, t.b_tj);
-        if (!a_tiles[ai] || !b_tiles[bi]) return DMM_EINVAL;
-        SegDev s;
-        s.lda = a_ld[ai];
-        s.ldb = b_ld[bi];
-        s.a = (const char *)a_tiles[ai] + ((t.m0 - P->A.rc[t.a_ti]) * s.lda + (t.k0 - P->A.cc[t.a_tj])) * es;
-        s.b = (const char *)b_tiles[bi] + ((t.k0 - P->B.rc[t.b_ti]) * s.ldb + (t.n0 - P->B.cc[t.b_tj])) * es;
-        // bytes that may be read from the segment's origin to the end of the tile buffer
-        // ((rows - 1) * ld + cols elements are guaranteed to exist)
-        const int64_t a_h = P->A.rc[t.a_ti + 1] - P->A.rc[t.a_ti], a_w = P->A.cc[t.a_tj + 1] - P->A.cc[t.a_tj];
-        const int64_t b_h = P->B.rc[t.b_ti + 1] - P->B.rc[t.b_ti], b_w = P->B.cc[t.b_tj + 1] - P->B.cc[t.b_tj];
-        s.a_bytes = ((a_h - 1) * s.lda + a_w - ((t.m0 - P->A.rc[t.a_ti]) * s.lda + (t.k0 - P->A.cc[t.a_tj]))) * es;
-        s.b_bytes = ((b_h - 1) * s.ldb + b_w - ((t.k0 - P->B.rc[t.b_ti]) * s.ldb + (t.n0 - P->B.cc[t.b_tj]))) * es;
-        s.klen = (int32_t)(t.k1 - t.k0);
-        s.pad = 0;
-        hs[pos] = s;
-      }
-      for (size_t i = 0; i < n_items; ++i) {
-        const dmm_work_item &w = P->items[i];
-        const int64_t ci = P->C.table_index(w.c_rep, w.c_ti, w.c_tj);
-        if (!c_tiles[ci]) return DMM_EINVAL;
-        ItemDev d;
-        d.ldc = c_ld[ci];
-        d.c = (float *)c_tiles[ci] + (w.m0 - P->C.rc[w.c_ti]) * d.ldc + (w.n0 - P->C.cc[w.c_tj]);
-        if (w.group >= 0) {
-          const Group &G = P->groups[(size_t)w.group];
-          d.seg_begin = (int32_t)G.first;
-          d.nsteps = 0;
-          for (int64_t q = 0; q < G.count; ++q)
-            d.nsteps += (int32_t)((hs[G.first + q].klen + bk - 1) / bk);
-          d.m_off = (int32_t)(w.m0 - G.m0);
-          d.n_off = (int32_t)(w.n0 - G.n0);
-        } else {
-          d.seg_begin = 0;
-          d.nsteps = 0;
-          d.m_off = d.n_off = 0;
-        }
-        d.m_ext = w.m_ext;
-        d.n_ext = w.n_ext;
-        hi[i] = d;
-      }
-      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
-      red.dev_base = P->dev->gemm_table.dev();
       const ItemDev *di = (const ItemDev *)P->dev->gemm_table.dev();
       const SegDev *ds = (const SegDev *)(P->dev->gemm_table.dev() + o_segs);
       if (timed) {
@@ -675,6 +864,11 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       else
         hipLaunchKernelGGL(grouped_gemm_kernel<4>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
       DMM_HIP(hipGetLastError());
+      if (!fixes.empty()) {
+        hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(fixes.size() * (BM / FIX_ROWS))), dim3(256), 0, stream,
+                           (const FixItem *)(P->dev->gemm_table.dev() + o_fix));
+        DMM_HIP(hipGetLastError());
+      }
       if (timed) {
         DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
         P->dev->gemm_timed = true;

@@ -69,13 +69,16 @@ struct SegDev {          // one K-segment of a group; pointers at the group's (m
   int32_t pad;
 };
 
-struct ItemDev {         // one macro-tile
-  float *c;              // top-left of the macro-tile in the C tile
+struct ItemDev {         // one macro-tile, or a run of K steps of one
+  float *c;              // top-left of the macro-tile in the C tile (or in a partial-sum buffer)
   int64_t ldc;
   int32_t seg_begin;
-  int32_t nsteps;        // K steps of the item: sum over its segments of ceil(klen / K step); 0 = zero fill
+  int32_t nsteps;        // K steps this item performs; 0 = zero fill
   int32_t m_off, n_off;  // offset inside the group's sub-tile
   int32_t m_ext, n_ext;
+  int32_t first_step;    // where it starts in the group's step sequence (steps of a segment:
+                         // ceil(klen / K step); the sequence runs over the segments in order)
+  int32_t pad;
 };
 
 constexpr int BM = 256, BN = 256;
@@ -293,10 +296,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     a_need = ((int64_t)(rows - 1) * sd.lda + 3 * PER) * ES + 16;
     b_need = ((int64_t)(BK - 1) * sd.ldb + (S::B_CHUNKS - 1) * PER) * ES + 16;
   };
-  auto open_lead = [&]() {                               // lead enters segment lead_seg at kpos 0
+  auto open_lead = [&](int kpos0) {                      // lead enters segment lead_seg at kpos0 (a multiple of BK)
     const SegDev sd = segs[it.seg_begin + lead_seg];
-    lead_kpos = 0;
-    lead_left = (sd.klen + BK - 1) / BK;
+    lead_kpos = kpos0;
+    lead_left = (sd.klen - kpos0 + BK - 1) / BK;
     lead_tail = sd.klen % BK != 0;
     ld_a_pitch = (unsigned)(sd.lda * ES);
     ld_b_pitch = (unsigned)(sd.ldb * ES);
@@ -307,7 +310,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     }
     ld_b_step = (int64_t)BK * sd.ldb * ES;
     int64_t a_left, b_left, a_need, b_need;
-    step_geometry(sd, 0, ld_a, ld_b, a_left, b_left);
+    step_geometry(sd, kpos0, ld_a, ld_b, a_left, b_left);
     step_need(sd, a_need, b_need);
     // the last step of the segment reads furthest: if it is safe, all are
     lead_seg_safe = a_left - (int64_t)(lead_left - 1) * (BK * ES) >= a_need &&
@@ -316,7 +319,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   auto advance_lead = [&]() {                            // to the next K step (the caller knows one exists)
     if (__builtin_expect(--lead_left == 0, 0)) {
       ++lead_seg;
-      open_lead();
+      open_lead(0);
     } else {
       lead_kpos += BK;
       ld_a += BK * ES;
@@ -377,16 +380,17 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   auto publish_fix = [&](int t) {                        // t = number of the step being published
     if (__builtin_expect((fix_bits & 4u) == 0u, 1)) return;
     const int stage = t & 3;
-    // find the step's segment and position (t < nsteps = the sum of the segments' step counts)
+    // find the step's segment and position (the item's steps lie inside the group's sequence)
     int seg = 0, first = 0;
+    const int t_abs = it.first_step + t;
     for (;;) {
       const int cnt = (segs[it.seg_begin + seg].klen + BK - 1) / BK;
-      if (t < first + cnt) break;
+      if (t_abs < first + cnt) break;
       first += cnt;
       ++seg;
     }
     const SegDev lsd = segs[it.seg_begin + seg];
-    const int kpos = (t - first) * BK;
+    const int kpos = (t_abs - first) * BK;
     gptr pa, pb;
     int64_t a_left, b_left;
     step_geometry(lsd, kpos, pa, pb, a_left, b_left);
@@ -527,7 +531,17 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // Iteration s multiplies stage s % 4 while the loads of step s + 3 are issued into stage
   // (s + 3) % 4, which every wave finished reading before the barrier of iteration s - 1.
   const int n = it.nsteps;
-  open_lead();
+  {
+    // the item's first step: segment and position (first_step lies inside the group's sequence)
+    int first = 0;
+    for (;;) {
+      const int cnt = (segs[it.seg_begin + lead_seg].klen + BK - 1) / BK;
+      if (it.first_step < first + cnt) break;
+      first += cnt;
+      ++lead_seg;
+    }
+    open_lead((it.first_step - first) * BK);
+  }
   // prologue: steps 0, 1, 2 in flight; publish step 0
   int issued = 0;
 #pragma unroll

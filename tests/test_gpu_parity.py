@@ -173,6 +173,36 @@ def test_stationary_b_and_a_partials_per_replica(mode):
     prob.close()
 
 
+@pytest.mark.parametrize("dtype,dims,kcuts", [
+    ("bf16", (300, 8192, 300), None),             # 4 macro-tiles x 256 K steps -> 4 runs each
+    ("bf16", (515, 8200, 260), (0, 1000, 4100, 8200)),   # runs that start inside a segment, cross segments, end on a K tail
+    ("f32", (260, 2100, 515), None),              # 6 macro-tiles x 132 steps -> 2 runs each
+    ("bf16", (2048, 4096, 2048), None),           # 64 full macro-tiles, two runs each
+    ("bf16", (70, 18000, 40), (0, 4444, 18000)),  # one small macro-tile, 8 runs
+])
+def test_k_split_of_the_last_round(dtype, dims, kcuts):
+    """Few macro-tiles with long K: the library cuts them into runs of K steps that fill the
+    idle CUs and adds the partial sums up in a fixed order.  Parity as everywhere else, bitwise
+    identical from run to run, NaN-prefilled C fully overwritten."""
+    M, K, N = dims
+    kc = kcuts or (0, K)
+    cfg = dict(name=f"ksplit-{dtype}-{M}x{K}x{N}", M=M, K=K, N=N, nranks=2, dtype=dtype,
+               A=dict(rows=M, cols=K, row_cuts=(0, M), col_cuts=kc, proc_rows=1, proc_cols=min(2, len(kc) - 1), replication=1),
+               B=dict(rows=K, cols=N, row_cuts=(0, K), col_cuts=(0, N), proc_rows=1, proc_cols=1, replication=2),
+               C=dict(rows=M, cols=N, row_cuts=(0, M), col_cuts=(0, N), proc_rows=1, proc_cols=1, replication=1),
+               dist=("normal", 1.0), seeds=(41, 42))
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"))
+    prob.execute()
+    first = prob.c_global(0)
+    A64, B64 = _to_f64(A, cfg), _to_f64(B, cfg)
+    C_ref = omatmul.matmul(A, B, bf16=(dtype == "bf16"))
+    _check(first, C_ref, A64, B64, cfg, cfg["name"])
+    prob.execute()
+    assert np.array_equal(first, prob.c_global(0))
+    prob.close()
+
+
 def test_iteration_offset_leaves_the_result_bitwise_unchanged():
     cfg = workloads.scaled_config("cfg5", 700, 900, 650)
     A, B = workloads.make_operands(cfg)
