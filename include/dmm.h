@@ -108,6 +108,9 @@ typedef struct {
   int32_t reserved;
 } dmm_work_item;
 
+/* A plan may be used by one thread at a time (different plans: any threads).  The device
+ * entry points act on the calling thread's current HIP device; a plan stays with the device
+ * of its first dmm_execute / dmm_reduce_replicas / dmm_broadcast_replica. */
 typedef struct dmm_plan_s dmm_plan_t;
 
 /* Slicing planner (Algorithm 1, or Algorithm 2 / its mirror image when `flags` asks for

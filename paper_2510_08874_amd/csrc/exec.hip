@@ -241,6 +241,7 @@ thread_local int g_last_hip_error = 0;
 // Section 4.2: allocate once, sub-allocate from the CPU side), so creating and
 // destroying plans in a loop does not hit hipMalloc / hipHostMalloc each time.
 struct Slab {
+  int device = -1;       // the device its buffer and events belong to
   char *dev = nullptr;
   char *pinned[2] = {nullptr, nullptr};
   hipEvent_t ev[2] = {nullptr, nullptr};
@@ -250,11 +251,15 @@ struct Slab {
 class SlabPool {
  public:
   int acquire(size_t bytes, Slab *out) {
+    int device = 0;
+    DMM_HIP(hipGetDevice(&device));
     {
       std::lock_guard<std::mutex> g(mu_);
       int best = -1;
       for (size_t i = 0; i < free_.size(); ++i)
-        if (free_[i].cap >= bytes && (best < 0 || free_[i].cap < free_[(size_t)best].cap)) best = (int)i;
+        if (free_[i].device == device && free_[i].cap >= bytes &&
+            (best < 0 || free_[i].cap < free_[(size_t)best].cap))
+          best = (int)i;
       if (best >= 0) {
         *out = free_[(size_t)best];
         free_.erase(free_.begin() + best);
@@ -275,6 +280,7 @@ class SlabPool {
       return e == hipErrorOutOfMemory ? DMM_ENOMEM : DMM_EHIP;
     }
     s.cap = want;
+    s.device = device;
     *out = s;
     return DMM_OK;
   }
@@ -376,14 +382,18 @@ struct Uploader {
 class ScratchPool {
  public:
   int acquire(size_t bytes, char **out, size_t *cap) {
+    int device = 0;
+    DMM_HIP(hipGetDevice(&device));
     {
       std::lock_guard<std::mutex> g(mu_);
       int best = -1;
       for (size_t i = 0; i < free_.size(); ++i)
-        if (free_[i].second >= bytes && (best < 0 || free_[i].second < free_[(size_t)best].second)) best = (int)i;
+        if (free_[i].device == device && free_[i].cap >= bytes &&
+            (best < 0 || free_[i].cap < free_[(size_t)best].cap))
+          best = (int)i;
       if (best >= 0) {
-        *out = free_[(size_t)best].first;
-        *cap = free_[(size_t)best].second;
+        *out = free_[(size_t)best].p;
+        *cap = free_[(size_t)best].cap;
         free_.erase(free_.begin() + best);
         return DMM_OK;
       }
@@ -400,19 +410,26 @@ class ScratchPool {
     *cap = want;
     return DMM_OK;
   }
-  // The caller guarantees that no stream work still uses the buffer.
+  // The caller guarantees that no stream work still uses the buffer (and is on its device).
   void release(char **p, size_t *cap) {
     if (!*p) return;
+    int device = 0;
+    (void)hipGetDevice(&device);
     std::lock_guard<std::mutex> g(mu_);
-    if (free_.size() < 8) free_.push_back({*p, *cap});
+    if (free_.size() < 8) free_.push_back({*p, *cap, device});
     else (void)hipFree(*p);
     *p = nullptr;
     *cap = 0;
   }
 
  private:
+  struct Entry {
+    char *p;
+    size_t cap;
+    int device;
+  };
   std::mutex mu_;
-  std::vector<std::pair<char *, size_t>> free_;
+  std::vector<Entry> free_;
 };
 
 ScratchPool &scratch_pool() {
@@ -449,22 +466,23 @@ void destroy_device_state(DeviceState *d) {
 
 namespace {
 
-std::once_flag g_attr_once;
-int g_attr_status = DMM_OK;
-
 int ensure_state(dmm_plan_t *P) {
-  std::call_once(g_attr_once, [] {
-    hipError_t e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<2>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              LDS_BYTES);
-    if (e != hipSuccess) {
-      g_last_hip_error = (int)e;
-      g_attr_status = DMM_EHIP;
+  // the kernels' LDS size has to be allowed once per device
+  static std::mutex mu;
+  static bool done[64] = {};
+  int device = 0;
+  DMM_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= 64) return DMM_EINVAL;
+  {
+    std::lock_guard<std::mutex> g(mu);
+    if (!done[device]) {
+      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  LDS_BYTES));
+      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  LDS_BYTES));
+      done[device] = true;
     }
-  });
-  if (g_attr_status) return g_attr_status;
+  }
   if (!P->dev) {
     P->dev = new (std::nothrow) DeviceState;
     if (!P->dev) return DMM_ENOMEM;
