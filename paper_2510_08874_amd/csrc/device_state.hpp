@@ -1,0 +1,256 @@
+// Host-side device resources of the library (included by exec.hip): error bookkeeping, the
+// slab and scratch pools, the work-table uploader and the per-plan device state.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "dmm.h"
+
+namespace dmm {
+
+// ------------------------------------------------------------------ host state
+
+thread_local int g_last_hip_error = 0;
+
+#define DMM_HIP(call)                            \
+  do {                                           \
+    hipError_t e_ = (call);                      \
+    if (e_ != hipSuccess) {                      \
+      g_last_hip_error = (int)e_;                \
+      return DMM_EHIP;                           \
+    }                                            \
+  } while (0)
+
+// One device buffer plus two pinned staging slots and their events.  Slabs are
+// recycled through a process-wide pool (in the spirit of the memory pool of
+// Section 4.2: allocate once, sub-allocate from the CPU side), so creating and
+// destroying plans in a loop does not hit hipMalloc / hipHostMalloc each time.
+struct Slab {
+  int device = -1;       // the device its buffer and events belong to
+  char *dev = nullptr;
+  char *pinned[2] = {nullptr, nullptr};
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  size_t cap = 0;
+};
+
+class SlabPool {
+ public:
+  int acquire(size_t bytes, Slab *out) {
+    int device = 0;
+    DMM_HIP(hipGetDevice(&device));
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      int best = -1;
+      for (size_t i = 0; i < free_.size(); ++i)
+        if (free_[i].device == device && free_[i].cap >= bytes &&
+            (best < 0 || free_[i].cap < free_[(size_t)best].cap))
+          best = (int)i;
+      if (best >= 0) {
+        *out = free_[(size_t)best];
+        free_.erase(free_.begin() + best);
+        return DMM_OK;
+      }
+    }
+    size_t want = 64 * 1024;
+    while (want < bytes) want *= 2;
+    Slab s;
+    hipError_t e = hipMalloc((void **)&s.dev, want);
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+      e = hipHostMalloc((void **)&s.pinned[i], want, hipHostMallocDefault);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&s.ev[i], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+      destroy(&s);
+      g_last_hip_error = (int)e;
+      return e == hipErrorOutOfMemory ? DMM_ENOMEM : DMM_EHIP;
+    }
+    s.cap = want;
+    s.device = device;
+    *out = s;
+    return DMM_OK;
+  }
+  // The caller guarantees that no stream work still uses the slab.
+  void release(Slab *s) {
+    if (!s->dev) return;
+    std::lock_guard<std::mutex> g(mu_);
+    if (free_.size() < 16) free_.push_back(*s);
+    else destroy(s);
+    *s = Slab();
+  }
+
+ private:
+  static void destroy(Slab *s) {
+    if (s->dev) (void)hipFree(s->dev);
+    for (int i = 0; i < 2; ++i) {
+      if (s->pinned[i]) (void)hipHostFree(s->pinned[i]);
+      if (s->ev[i]) (void)hipEventDestroy(s->ev[i]);
+    }
+    *s = Slab();
+  }
+  std::mutex mu_;
+  std::vector<Slab> free_;
+};
+
+SlabPool &pool() {
+  static SlabPool *p = new SlabPool;   // never destroyed: outlives the HIP runtime teardown order
+  return *p;
+}
+
+// One stream per device for work-table uploads (default priority, created on first use and
+// kept for the life of the process): a table copy then overlaps whatever the caller's stream
+// is still running, instead of queueing behind it.
+int copy_stream(hipStream_t *out) {
+  static std::mutex mu;
+  static hipStream_t streams[64] = {};
+  int dev = 0;
+  DMM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return DMM_EINVAL;
+  std::lock_guard<std::mutex> g(mu);
+  if (!streams[dev]) DMM_HIP(hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking));
+  *out = streams[dev];
+  return DMM_OK;
+}
+
+// upload() copies host bytes to the slab's device buffer on the copy stream and makes the
+// caller's stream wait for that copy; it skips the copy when those bytes are already resident.
+// `busy_until`, if given, is an event after which earlier readers of the device buffer (kernels
+// of a previous call on this plan) are done: the copy waits for it.
+struct Uploader {
+  Slab slab;
+  bool ev_used[2] = {false, false};
+  int cur = 0;
+  std::vector<char> resident;
+  bool valid = false;
+
+  char *dev() const { return slab.dev; }
+  int upload(const void *src, size_t bytes, hipStream_t stream, hipEvent_t busy_until = nullptr) {
+    if (valid && resident.size() == bytes && (bytes == 0 || std::memcmp(resident.data(), src, bytes) == 0)) {
+      // already resident; the caller's stream (possibly another one than last time) still has to
+      // be ordered behind the copy that put it there
+      if (bytes != 0 && ev_used[cur]) DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
+      return DMM_OK;
+    }
+    if (bytes == 0) return DMM_OK;
+    if (bytes > slab.cap) {
+      // growing: the old slab may still be read by enqueued work of this plan
+      if (slab.dev) {
+        DMM_HIP(hipStreamSynchronize(stream));
+        pool().release(&slab);
+      }
+      int rc = pool().acquire(bytes, &slab);
+      if (rc) return rc;
+      ev_used[0] = ev_used[1] = false;
+      valid = false;
+    }
+    cur ^= 1;
+    if (ev_used[cur]) DMM_HIP(hipEventSynchronize(slab.ev[cur]));  // slot last used two uploads ago
+    std::memcpy(slab.pinned[cur], src, bytes);
+    hipStream_t cs = nullptr;
+    int rc = copy_stream(&cs);
+    if (rc) return rc;
+    if (busy_until) DMM_HIP(hipStreamWaitEvent(cs, busy_until, 0));
+    DMM_HIP(hipMemcpyAsync(slab.dev, slab.pinned[cur], bytes, hipMemcpyHostToDevice, cs));
+    DMM_HIP(hipEventRecord(slab.ev[cur], cs));
+    DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
+    ev_used[cur] = true;
+    resident.assign((const char *)src, (const char *)src + bytes);
+    valid = true;
+    return DMM_OK;
+  }
+  void release() {
+    pool().release(&slab);
+    valid = false;
+  }
+};
+
+// Device-only buffers for the partial sums of K-split items, recycled like the slabs.
+class ScratchPool {
+ public:
+  int acquire(size_t bytes, char **out, size_t *cap) {
+    int device = 0;
+    DMM_HIP(hipGetDevice(&device));
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      int best = -1;
+      for (size_t i = 0; i < free_.size(); ++i)
+        if (free_[i].device == device && free_[i].cap >= bytes &&
+            (best < 0 || free_[i].cap < free_[(size_t)best].cap))
+          best = (int)i;
+      if (best >= 0) {
+        *out = free_[(size_t)best].p;
+        *cap = free_[(size_t)best].cap;
+        free_.erase(free_.begin() + best);
+        return DMM_OK;
+      }
+    }
+    size_t want = (size_t)4 << 20;
+    while (want < bytes) want *= 2;
+    char *p = nullptr;
+    hipError_t e = hipMalloc((void **)&p, want);
+    if (e != hipSuccess) {
+      g_last_hip_error = (int)e;
+      return e == hipErrorOutOfMemory ? DMM_ENOMEM : DMM_EHIP;
+    }
+    *out = p;
+    *cap = want;
+    return DMM_OK;
+  }
+  // The caller guarantees that no stream work still uses the buffer (and is on its device).
+  void release(char **p, size_t *cap) {
+    if (!*p) return;
+    int device = 0;
+    (void)hipGetDevice(&device);
+    std::lock_guard<std::mutex> g(mu_);
+    if (free_.size() < 8) free_.push_back({*p, *cap, device});
+    else (void)hipFree(*p);
+    *p = nullptr;
+    *cap = 0;
+  }
+
+ private:
+  struct Entry {
+    char *p;
+    size_t cap;
+    int device;
+  };
+  std::mutex mu_;
+  std::vector<Entry> free_;
+};
+
+ScratchPool &scratch_pool() {
+  static ScratchPool *p = new ScratchPool;   // never destroyed, like the slab pool
+  return *p;
+}
+
+struct DeviceState {
+  char *split_buf = nullptr;   // partial sums of K-split items
+  size_t split_cap = 0;
+  Uploader gemm_table;   // [ItemDev x items][SegDev x segments]
+  Uploader red_table;    // [RedItem][RedTile][part pointers][part lds]
+  std::vector<char> host;  // scratch for table assembly
+  hipEvent_t last_use = nullptr;      // recorded after the last launch of every call
+  bool last_use_recorded = false;
+  hipEvent_t t_gemm[2] = {nullptr, nullptr}, t_red[2] = {nullptr, nullptr};  // DMM_TIMING
+  bool gemm_timed = false, red_timed = false;
+};
+
+void destroy_device_state(DeviceState *d) {
+  if (!d) return;
+  // wait for this plan's own work only, then hand the buffers back to the pool
+  if (d->last_use_recorded) (void)hipEventSynchronize(d->last_use);
+  d->gemm_table.release();
+  d->red_table.release();
+  scratch_pool().release(&d->split_buf, &d->split_cap);
+  if (d->last_use) (void)hipEventDestroy(d->last_use);
+  for (int i = 0; i < 2; ++i) {
+    if (d->t_gemm[i]) (void)hipEventDestroy(d->t_gemm[i]);
+    if (d->t_red[i]) (void)hipEventDestroy(d->t_red[i]);
+  }
+  delete d;
+}
+
+}  // namespace dmm

@@ -1,6 +1,7 @@
-// Device-facing half of the library (gfx950 only): the host code that turns a plan
-// plus tile pointers into device work tables and launches the grouped GEMM
-// (gemm_kernel.hpp), and the replica-sum kernel (reduce_replicas of Table 1).
+// Device-facing half of the library (gfx950 only): the entry points that turn a plan plus
+// tile pointers into device work tables and launch the grouped GEMM (gemm_kernel.hpp), the
+// replica sum, the replica broadcast and the measurement aids (aux_kernels.hpp), on top of the
+// pools and the uploader of device_state.hpp.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -11,458 +12,12 @@
 #include <utility>
 #include <vector>
 
+#include "aux_kernels.hpp"
+#include "device_state.hpp"
 #include "gemm_kernel.hpp"
 #include "plan_internal.h"
 
 namespace dmm {
-
-// ------------------------------------------------------------------ device tables (replica sum)
-
-struct RedTile {         // one C tile for the replica sum
-  float *out;
-  int64_t ldo;
-  int64_t part_begin;    // index into the parts arrays (nparts entries)
-  int32_t rows, cols;
-};
-
-struct RedItem {
-  int32_t tile;
-  int32_t row0, nrows;
-  int32_t pad;
-};
-
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-// ------------------------------------------------------------------ replica sum
-
-// out = ((p0 + p1) + p2) + ...  for a block of rows of one C tile (reduce_replicas, Table 1).
-// HBM-bound: (nparts + 1) * 4 bytes per element.  float4 path when every pointer and
-// leading dimension allows it.
-constexpr int RED_NT = 256;
-// Elements of C one workgroup sums: one trip of its 256 threads x 4 float4 columns.  Measured on
-// 16 tiles of 2048 x 2048 with two replicas: 4 K elements 6.4 TB/s, 16 K 5.8, 64 K 5.5, 1 K 6.3.
-constexpr int RED_ELEMS = 4096;
-
-__global__ __launch_bounds__(RED_NT) void reduce_replicas_kernel(const RedItem *__restrict__ items,
-                                                                 const RedTile *__restrict__ tiles,
-                                                                 const float *const *__restrict__ parts,
-                                                                 const int64_t *__restrict__ part_ld,
-                                                                 int nparts, int vec_ok) {
-  const RedItem it = items[blockIdx.x];
-  const RedTile t = tiles[it.tile];
-  const float *const *pp = parts + t.part_begin;
-  const int64_t *pl = part_ld + t.part_begin;
-  if (vec_ok) {
-    // Four independent float4 columns of work per thread and trip, all loads issued before the
-    // first add: (4 nparts) 16-byte loads in flight per thread keep HBM busy at modest occupancy.
-    const int c4 = t.cols >> 2;
-    const int total = it.nrows * c4;
-    constexpr int U = 4;
-    for (int base = threadIdx.x; base < total; base += U * RED_NT) {
-      floatx4 s[U];
-      int64_t oo[U];
-      bool ok[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int idx = base + u * RED_NT;
-        ok[u] = idx < total;
-        const int r = it.row0 + (ok[u] ? idx / c4 : 0), c = ok[u] ? (idx % c4) << 2 : 0;
-        oo[u] = (int64_t)r * t.ldo + c;
-        if (ok[u]) s[u] = __builtin_nontemporal_load((const floatx4 *)(pp[0] + (int64_t)r * pl[0] + c));
-      }
-      for (int q = 1; q < nparts; ++q) {
-        floatx4 v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int idx = base + u * RED_NT;
-          const int r = it.row0 + (ok[u] ? idx / c4 : 0), c = ok[u] ? (idx % c4) << 2 : 0;
-          if (ok[u]) v[u] = __builtin_nontemporal_load((const floatx4 *)(pp[q] + (int64_t)r * pl[q] + c));
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (ok[u]) {
-            s[u].x = s[u].x + v[u].x;
-            s[u].y = s[u].y + v[u].y;
-            s[u].z = s[u].z + v[u].z;
-            s[u].w = s[u].w + v[u].w;
-          }
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (ok[u]) __builtin_nontemporal_store(s[u], (floatx4 *)(t.out + oo[u]));
-    }
-  } else {
-    const int total = it.nrows * t.cols;
-    for (int idx = threadIdx.x; idx < total; idx += RED_NT) {
-      const int r = it.row0 + idx / t.cols, c = idx % t.cols;
-      float s = pp[0][(int64_t)r * pl[0] + c];
-      for (int q = 1; q < nparts; ++q) s = s + pp[q][(int64_t)r * pl[q] + c];
-      t.out[(int64_t)r * t.ldo + c] = s;
-    }
-  }
-}
-
-// Every replica's tile except the origin's becomes a copy of the origin's (broadcast_replica,
-// Table 1).  Same work items and tables as the replica sum, `out` being the origin's tile.
-// HBM-bound: nparts * 4 bytes per element (one read, nparts - 1 writes).
-__global__ __launch_bounds__(RED_NT) void broadcast_replica_kernel(const RedItem *__restrict__ items,
-                                                                   const RedTile *__restrict__ tiles,
-                                                                   float *const *__restrict__ parts,
-                                                                   const int64_t *__restrict__ part_ld, int nparts,
-                                                                   int vec_ok) {
-  const RedItem it = items[blockIdx.x];
-  const RedTile t = tiles[it.tile];
-  float *const *pp = parts + t.part_begin;
-  const int64_t *pl = part_ld + t.part_begin;
-  if (vec_ok) {
-    const int c4 = t.cols >> 2;
-    const int total = it.nrows * c4;
-    for (int idx = threadIdx.x; idx < total; idx += RED_NT) {
-      const int r = it.row0 + idx / c4, c = (idx % c4) << 2;
-      const floatx4 v = __builtin_nontemporal_load((const floatx4 *)(t.out + (int64_t)r * t.ldo + c));
-      for (int q = 0; q < nparts; ++q)
-        if (pp[q] != t.out) __builtin_nontemporal_store(v, (floatx4 *)(pp[q] + (int64_t)r * pl[q] + c));
-    }
-  } else {
-    const int total = it.nrows * t.cols;
-    for (int idx = threadIdx.x; idx < total; idx += RED_NT) {
-      const int r = it.row0 + idx / t.cols, c = idx % t.cols;
-      const float v = t.out[(int64_t)r * t.ldo + c];
-      for (int q = 0; q < nparts; ++q)
-        if (pp[q] != t.out) pp[q][(int64_t)r * pl[q] + c] = v;
-    }
-  }
-}
-
-// ------------------------------------------------------------------ K-split of the last round
-
-// When the number of macro-tiles is not a multiple of the number of CUs, the last round of
-// workgroups leaves CUs idle.  The host then cuts each macro-tile of that round into runs of K
-// steps, one workgroup each, which write their partial sums into a scratch buffer (256 x 256
-// fp32 per run); this kernel adds the runs of a macro-tile up in ascending k and writes C.  Fixed
-// cut, fixed order, no atomics: the result is deterministic.
-struct FixItem {
-  float *dst;            // top-left of the macro-tile in the C tile
-  int64_t ldc;
-  const float *parts;    // nparts consecutive 256 x 256 tiles
-  int32_t m_ext, n_ext;
-  int32_t nparts, pad;
-};
-constexpr int FIX_ROWS = 4;           // rows of a macro-tile one workgroup sums: 4 rows x 64 float4 columns
-
-__global__ __launch_bounds__(256) void sum_parts_kernel(const FixItem *__restrict__ fixes) {
-  const FixItem f = fixes[blockIdx.x / (BM / FIX_ROWS)];
-  const int r = (blockIdx.x % (BM / FIX_ROWS)) * FIX_ROWS + (threadIdx.x >> 6);
-  const int c = (threadIdx.x & 63) << 2;
-  if (r >= f.m_ext || c >= f.n_ext) return;
-  const float *p = f.parts + (int64_t)r * BN + c;
-  floatx4 s = __builtin_nontemporal_load((const floatx4 *)p);
-  // eight runs' loads in flight at a time; the adds follow in ascending k (the order is part of the result)
-  constexpr int QB = 8;
-  for (int q0 = 1; q0 < f.nparts; q0 += QB) {
-    floatx4 v[QB];
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq)
-      if (q0 + qq < f.nparts) v[qq] = __builtin_nontemporal_load((const floatx4 *)(p + (int64_t)(q0 + qq) * (BM * BN)));
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq)
-      if (q0 + qq < f.nparts) {
-        s.x = s.x + v[qq].x;
-        s.y = s.y + v[qq].y;
-        s.z = s.z + v[qq].z;
-        s.w = s.w + v[qq].w;
-      }
-  }
-  float *d = f.dst + (int64_t)r * f.ldc + c;
-  const float e[4] = {s.x, s.y, s.z, s.w};
-#pragma unroll
-  for (int x = 0; x < 4; ++x)
-    if (c + x < f.n_ext) __builtin_nontemporal_store(e[x], d + x);
-}
-
-// ------------------------------------------------------------------ matrix-pipe rate probe
-
-// Eight independent accumulators per wave, operands held in registers: the MFMA pipe is never
-// idle and nothing else on the chip is busy.  Reports elapsed shader cycles of wave 0 per block.
-__global__ __launch_bounds__(256) void mfma_rate_kernel(unsigned long long *cycles, float *sink, int iters,
-                                                        int random_operands) {
-  floatx16 acc[8];
-  bf16x8 a[8], b[8];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      unsigned h = (threadIdx.x * 977u + blockIdx.x * 131071u + s * 8u + e) * 2654435761u;
-      h ^= h >> 15;
-      h *= 0x846ca68bu;
-      h ^= h >> 16;
-      a[s][e] = (__bf16)(random_operands ? ((int)(h & 0xFFFFu) - 32768) * (1.0f / 32768.0f) : 1.0f);
-      b[s][e] = (__bf16)(random_operands ? ((int)(h >> 16) - 32768) * (1.0f / 32768.0f) : 0.5f);
-    }
-  }
-#pragma unroll
-  for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(a[s]), "+v"(b[s]));
-  const unsigned long long t0 = __builtin_amdgcn_s_memtime();
-  for (int it = 0; it < iters; it += 4) {
-#pragma unroll
-    for (int v = 0; v < 4; ++v)
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[(u + 3 * v) & 7], acc[u], 0, 0, 0);
-  }
-  const unsigned long long t1 = __builtin_amdgcn_s_memtime();
-  float s = 0.f;
-#pragma unroll
-  for (int u = 0; u < 8; ++u)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s += acc[u][r];
-  if (s == 12345.678f) sink[0] = s;       // keeps the accumulators alive; never true in practice
-  if (threadIdx.x == 0) cycles[blockIdx.x] = t1 - t0;
-}
-
-// ------------------------------------------------------------------ host state
-
-thread_local int g_last_hip_error = 0;
-
-#define DMM_HIP(call)                            \
-  do {                                           \
-    hipError_t e_ = (call);                      \
-    if (e_ != hipSuccess) {                      \
-      g_last_hip_error = (int)e_;                \
-      return DMM_EHIP;                           \
-    }                                            \
-  } while (0)
-
-// One device buffer plus two pinned staging slots and their events.  Slabs are
-// recycled through a process-wide pool (in the spirit of the memory pool of
-// Section 4.2: allocate once, sub-allocate from the CPU side), so creating and
-// destroying plans in a loop does not hit hipMalloc / hipHostMalloc each time.
-struct Slab {
-  int device = -1;       // the device its buffer and events belong to
-  char *dev = nullptr;
-  char *pinned[2] = {nullptr, nullptr};
-  hipEvent_t ev[2] = {nullptr, nullptr};
-  size_t cap = 0;
-};
-
-class SlabPool {
- public:
-  int acquire(size_t bytes, Slab *out) {
-    int device = 0;
-    DMM_HIP(hipGetDevice(&device));
-    {
-      std::lock_guard<std::mutex> g(mu_);
-      int best = -1;
-      for (size_t i = 0; i < free_.size(); ++i)
-        if (free_[i].device == device && free_[i].cap >= bytes &&
-            (best < 0 || free_[i].cap < free_[(size_t)best].cap))
-          best = (int)i;
-      if (best >= 0) {
-        *out = free_[(size_t)best];
-        free_.erase(free_.begin() + best);
-        return DMM_OK;
-      }
-    }
-    size_t want = 64 * 1024;
-    while (want < bytes) want *= 2;
-    Slab s;
-    hipError_t e = hipMalloc((void **)&s.dev, want);
-    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
-      e = hipHostMalloc((void **)&s.pinned[i], want, hipHostMallocDefault);
-      if (e == hipSuccess) e = hipEventCreateWithFlags(&s.ev[i], hipEventDisableTiming);
-    }
-    if (e != hipSuccess) {
-      destroy(&s);
-      g_last_hip_error = (int)e;
-      return e == hipErrorOutOfMemory ? DMM_ENOMEM : DMM_EHIP;
-    }
-    s.cap = want;
-    s.device = device;
-    *out = s;
-    return DMM_OK;
-  }
-  // The caller guarantees that no stream work still uses the slab.
-  void release(Slab *s) {
-    if (!s->dev) return;
-    std::lock_guard<std::mutex> g(mu_);
-    if (free_.size() < 16) free_.push_back(*s);
-    else destroy(s);
-    *s = Slab();
-  }
-
- private:
-  static void destroy(Slab *s) {
-    if (s->dev) (void)hipFree(s->dev);
-    for (int i = 0; i < 2; ++i) {
-      if (s->pinned[i]) (void)hipHostFree(s->pinned[i]);
-      if (s->ev[i]) (void)hipEventDestroy(s->ev[i]);
-    }
-    *s = Slab();
-  }
-  std::mutex mu_;
-  std::vector<Slab> free_;
-};
-
-SlabPool &pool() {
-  static SlabPool *p = new SlabPool;   // never destroyed: outlives the HIP runtime teardown order
-  return *p;
-}
-
-// One stream per device for work-table uploads (default priority, created on first use and
-// kept for the life of the process): a table copy then overlaps whatever the caller's stream
-// is still running, instead of queueing behind it.
-int copy_stream(hipStream_t *out) {
-  static std::mutex mu;
-  static hipStream_t streams[64] = {};
-  int dev = 0;
-  DMM_HIP(hipGetDevice(&dev));
-  if (dev < 0 || dev >= 64) return DMM_EINVAL;
-  std::lock_guard<std::mutex> g(mu);
-  if (!streams[dev]) DMM_HIP(hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking));
-  *out = streams[dev];
-  return DMM_OK;
-}
-
-// upload() copies host bytes to the slab's device buffer on the copy stream and makes the
-// caller's stream wait for that copy; it skips the copy when those bytes are already resident.
-// `busy_until`, if given, is an event after which earlier readers of the device buffer (kernels
-// of a previous call on this plan) are done: the copy waits for it.
-struct Uploader {
-  Slab slab;
-  bool ev_used[2] = {false, false};
-  int cur = 0;
-  std::vector<char> resident;
-  bool valid = false;
-
-  char *dev() const { return slab.dev; }
-  int upload(const void *src, size_t bytes, hipStream_t stream, hipEvent_t busy_until = nullptr) {
-    if (valid && resident.size() == bytes && (bytes == 0 || std::memcmp(resident.data(), src, bytes) == 0)) {
-      // already resident; the caller's stream (possibly another one than last time) still has to
-      // be ordered behind the copy that put it there
-      if (bytes != 0 && ev_used[cur]) DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
-      return DMM_OK;
-    }
-    if (bytes == 0) return DMM_OK;
-    if (bytes > slab.cap) {
-      // growing: the old slab may still be read by enqueued work of this plan
-      if (slab.dev) {
-        DMM_HIP(hipStreamSynchronize(stream));
-        pool().release(&slab);
-      }
-      int rc = pool().acquire(bytes, &slab);
-      if (rc) return rc;
-      ev_used[0] = ev_used[1] = false;
-      valid = false;
-    }
-    cur ^= 1;
-    if (ev_used[cur]) DMM_HIP(hipEventSynchronize(slab.ev[cur]));  // slot last used two uploads ago
-    std::memcpy(slab.pinned[cur], src, bytes);
-    hipStream_t cs = nullptr;
-    int rc = copy_stream(&cs);
-    if (rc) return rc;
-    if (busy_until) DMM_HIP(hipStreamWaitEvent(cs, busy_until, 0));
-    DMM_HIP(hipMemcpyAsync(slab.dev, slab.pinned[cur], bytes, hipMemcpyHostToDevice, cs));
-    DMM_HIP(hipEventRecord(slab.ev[cur], cs));
-    DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
-    ev_used[cur] = true;
-    resident.assign((const char *)src, (const char *)src + bytes);
-    valid = true;
-    return DMM_OK;
-  }
-  void release() {
-    pool().release(&slab);
-    valid = false;
-  }
-};
-
-// Device-only buffers for the partial sums of K-split items, recycled like the slabs.
-class ScratchPool {
- public:
-  int acquire(size_t bytes, char **out, size_t *cap) {
-    int device = 0;
-    DMM_HIP(hipGetDevice(&device));
-    {
-      std::lock_guard<std::mutex> g(mu_);
-      int best = -1;
-      for (size_t i = 0; i < free_.size(); ++i)
-        if (free_[i].device == device && free_[i].cap >= bytes &&
-            (best < 0 || free_[i].cap < free_[(size_t)best].cap))
-          best = (int)i;
-      if (best >= 0) {
-        *out = free_[(size_t)best].p;
-        *cap = free_[(size_t)best].cap;
-        free_.erase(free_.begin() + best);
-        return DMM_OK;
-      }
-    }
-    size_t want = (size_t)4 << 20;
-    while (want < bytes) want *= 2;
-    char *p = nullptr;
-    hipError_t e = hipMalloc((void **)&p, want);
-    if (e != hipSuccess) {
-      g_last_hip_error = (int)e;
-      return e == hipErrorOutOfMemory ? DMM_ENOMEM : DMM_EHIP;
-    }
-    *out = p;
-    *cap = want;
-    return DMM_OK;
-  }
-  // The caller guarantees that no stream work still uses the buffer (and is on its device).
-  void release(char **p, size_t *cap) {
-    if (!*p) return;
-    int device = 0;
-    (void)hipGetDevice(&device);
-    std::lock_guard<std::mutex> g(mu_);
-    if (free_.size() < 8) free_.push_back({*p, *cap, device});
-    else (void)hipFree(*p);
-    *p = nullptr;
-    *cap = 0;
-  }
-
- private:
-  struct Entry {
-    char *p;
-    size_t cap;
-    int device;
-  };
-  std::mutex mu_;
-  std::vector<Entry> free_;
-};
-
-ScratchPool &scratch_pool() {
-  static ScratchPool *p = new ScratchPool;   // never destroyed, like the slab pool
-  return *p;
-}
-
-struct DeviceState {
-  char *split_buf = nullptr;   // partial sums of K-split items
-  size_t split_cap = 0;
-  Uploader gemm_table;   // [ItemDev x items][SegDev x segments]
-  Uploader red_table;    // [RedItem][RedTile][part pointers][part lds]
-  std::vector<char> host;  // scratch for table assembly
-  hipEvent_t last_use = nullptr;      // recorded after the last launch of every call
-  bool last_use_recorded = false;
-  hipEvent_t t_gemm[2] = {nullptr, nullptr}, t_red[2] = {nullptr, nullptr};  // DMM_TIMING
-  bool gemm_timed = false, red_timed = false;
-};
-
-void destroy_device_state(DeviceState *d) {
-  if (!d) return;
-  // wait for this plan's own work only, then hand the buffers back to the pool
-  if (d->last_use_recorded) (void)hipEventSynchronize(d->last_use);
-  d->gemm_table.release();
-  d->red_table.release();
-  scratch_pool().release(&d->split_buf, &d->split_cap);
-  if (d->last_use) (void)hipEventDestroy(d->last_use);
-  for (int i = 0; i < 2; ++i) {
-    if (d->t_gemm[i]) (void)hipEventDestroy(d->t_gemm[i]);
-    if (d->t_red[i]) (void)hipEventDestroy(d->t_red[i]);
-  }
-  delete d;
-}
 
 namespace {
 
