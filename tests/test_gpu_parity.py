@@ -203,6 +203,30 @@ def test_k_split_of_the_last_round(dtype, dims, kcuts):
     prob.close()
 
 
+def test_one_plan_alternating_streams_and_output_sets():
+    """The same plan run back to back on two streams into two different sets of C tiles (so the
+    work table changes every call while the previous call may still be running): the library
+    has to order its table uploads and its scratch buffer behind the earlier call itself."""
+    from paper_2510_08874_amd.tiles import TileSet
+    cfg = workloads.scaled_config("cfg4", 700, 8400, 520)      # long K (132 steps per share): the K-split path and its scratch too
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"))
+    other = TileSet(cfg["C"], torch.float32, "cuda", 1, fill=float("nan"))
+    args = [prob.args, prob.plan.marshal(prob.A.tensors, prob.A.ld, prob.B.tensors, prob.B.ld, other.tensors, other.ld)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for it in range(6):
+        prob.plan.execute_marshalled(prob.dtype_code, args[it % 2], 0, streams[it % 2].cuda_stream)
+    torch.cuda.synchronize()
+    C_ref = omatmul.matmul(A, B, bf16=True)
+    A64, B64 = _to_f64(A, cfg), _to_f64(B, cfg)
+    first = prob.C.gather(0)
+    second = other.gather(0)
+    _check(first, C_ref, A64, B64, cfg, "stream 0")
+    assert np.array_equal(first, second)
+    prob.close()
+
+
 def test_iteration_offset_leaves_the_result_bitwise_unchanged():
     cfg = workloads.scaled_config("cfg5", 700, 900, 650)
     A, B = workloads.make_operands(cfg)
