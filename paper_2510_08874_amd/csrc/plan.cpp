@@ -13,8 +13,8 @@
 //    regrouped by output sub-tile so one workgroup accumulates all K-segments of
 //    a C region in ascending k and writes it once, without atomics.
 //  - work items: every group is cut into macro-tiles; the launch order deals
-//    contiguous runs of neighbouring macro-tiles to each of the 8 XCDs
-//    (workgroup id modulo 8 selects the XCD, each XCD has its own L2).
+//    blocks of 32 neighbouring macro-tiles to the 8 XCDs in turn (workgroup id
+//    modulo 8 selects the XCD, each XCD has its own L2).
 #include <algorithm>
 #include <cstring>
 #include <new>
@@ -378,18 +378,24 @@ void build_items(dmm_plan_t *P) {
             j = e;
           }
       }
-  // Deal 8 contiguous runs of the sequence to the 8 XCDs: launch slot i goes to
-  // XCD i % 8, so run x occupies the slots congruent to x.
-  const int64_t n = (int64_t)seq.size(), X = 8;
+  // Deal the sequence to the 8 XCDs in blocks of 32 (the CUs of one XCD), round-robin: launch
+  // slot i goes to XCD i % 8, so block b occupies 32 slots congruent to b % 8, and at any time the
+  // 8 XCDs work on 8 consecutive blocks: neighbouring macro-tile blocks of the same output
+  // region, which read the same B column panels (and the same replica of A) at about the same
+  // time, so that what one XCD pulled into the last-level cache serves the other seven.  Dealing
+  // 8 contiguous runs instead (each XCD on a region of its own) streams 8 regions' operands at
+  // once: measured -6 % on cfg3, -10 % on cfg5, -24 % on the column-block MLP-2 shape, +5 % on the
+  // inner-product MLP-1 shape, no difference on cfg4.
+  const int64_t n = (int64_t)seq.size(), X = 8, BLK = 32;
   P->items.clear();
   P->items.reserve(n);
-  int64_t longest = 0;
-  for (int64_t x = 0; x < X; ++x) longest = std::max(longest, (x + 1) * n / X - x * n / X);
-  for (int64_t j = 0; j < longest; ++j)
-    for (int64_t x = 0; x < X; ++x) {
-      const int64_t b = x * n / X, e = (x + 1) * n / X;
-      if (b + j < e) P->items.push_back(seq[b + j]);
-    }
+  const int64_t nblk = (n + BLK - 1) / BLK;
+  for (int64_t b0 = 0; b0 < nblk; b0 += X)
+    for (int64_t j = 0; j < BLK; ++j)
+      for (int64_t x = 0; x < X; ++x) {
+        const int64_t idx = (b0 + x) * BLK + j;
+        if (idx < n) P->items.push_back(seq[idx]);
+      }
 }
 
 }  // namespace
