@@ -378,24 +378,44 @@ void build_items(dmm_plan_t *P) {
             j = e;
           }
       }
-  // Deal the sequence to the 8 XCDs in blocks of 32 (the CUs of one XCD), round-robin: launch
-  // slot i goes to XCD i % 8, so block b occupies 32 slots congruent to b % 8, and at any time the
-  // 8 XCDs work on 8 consecutive blocks: neighbouring macro-tile blocks of the same output
-  // region, which read the same B column panels (and the same replica of A) at about the same
-  // time, so that what one XCD pulled into the last-level cache serves the other seven.  Dealing
-  // 8 contiguous runs instead (each XCD on a region of its own) streams 8 regions' operands at
-  // once: measured -6 % on cfg3, -10 % on cfg5, -24 % on the column-block MLP-2 shape, +5 % on the
-  // inner-product MLP-1 shape, no difference on cfg4.
+  // Launch slot i goes to XCD i % 8.  Two ways of dealing the sequence to the 8 XCDs:
+  //  - round-robin in blocks of 32 (the CUs of one XCD): at any time the 8 XCDs work on 8
+  //    consecutive blocks, i.e. on neighbouring bands of the same column strip of one output
+  //    region, which read the same B column panels (and the same replica of A) at about the same
+  //    time, so that what one XCD pulled into the last-level cache serves the other seven;
+  //  - 8 contiguous runs: each XCD on a region of its own.
+  // The first wins where strips hold several bands (against the second: cfg3 +6 %, cfg5 +10 %,
+  // column-block MLP-2 +24 %, cfg4 the same); where every strip is a single band, consecutive
+  // blocks share no B panel and streaming separate regions is the better of the two (inner-
+  // product MLP-1: +5 %).  So: round-robin if at least half of the blocks are followed by a
+  // block of the same strip.
   const int64_t n = (int64_t)seq.size(), X = 8, BLK = 32;
+  int64_t blocks = 0, followed = 0;
+  for (const Group &G : P->groups) {
+    const int64_t T = kMacroTile;
+    const int64_t bands = ((G.m1 - G.m0 + T - 1) / T + 3) / 4, strips = ((G.n1 - G.n0 + T - 1) / T + 7) / 8;
+    blocks += bands * strips;
+    followed += (bands - 1) * strips;
+  }
   P->items.clear();
   P->items.reserve(n);
-  const int64_t nblk = (n + BLK - 1) / BLK;
-  for (int64_t b0 = 0; b0 < nblk; b0 += X)
-    for (int64_t j = 0; j < BLK; ++j)
+  if (2 * followed >= blocks) {
+    const int64_t nblk = (n + BLK - 1) / BLK;
+    for (int64_t b0 = 0; b0 < nblk; b0 += X)
+      for (int64_t j = 0; j < BLK; ++j)
+        for (int64_t x = 0; x < X; ++x) {
+          const int64_t idx = (b0 + x) * BLK + j;
+          if (idx < n) P->items.push_back(seq[idx]);
+        }
+  } else {
+    int64_t longest = 0;
+    for (int64_t x = 0; x < X; ++x) longest = std::max(longest, (x + 1) * n / X - x * n / X);
+    for (int64_t j = 0; j < longest; ++j)
       for (int64_t x = 0; x < X; ++x) {
-        const int64_t idx = (b0 + x) * BLK + j;
-        if (idx < n) P->items.push_back(seq[idx]);
+        const int64_t b0 = x * n / X, e = (x + 1) * n / X;
+        if (b0 + j < e) P->items.push_back(seq[b0 + j]);
       }
+  }
 }
 
 }  // namespace
