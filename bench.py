@@ -137,6 +137,14 @@ def main() -> int:
     t1 = time.perf_counter()
     while inflight:
         retire()
+
+    # the same step without re-planning (one plan, tables already resident), for the record
+    torch.cuda.synchronize()
+    te0 = time.perf_counter()
+    for _ in range(args.steps):
+        prob.plan.execute_marshalled(prob.dtype_code, prob.args, 0, stream)
+    torch.cuda.synchronize()
+    exec_only_ms = (time.perf_counter() - te0) * 1e3 / args.steps
     gc.enable()
 
     # host-only cost of planning, for the record
@@ -167,6 +175,8 @@ def main() -> int:
                    "virtual_ranks": cfg["nranks"], "tasks": prob.plan.num_tasks(), "groups": prob.plan.num_groups(),
                    "work_items": prob.plan.num_items(), "ld_multiple": args.ld_multiple,
                    "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "plan_host_us": round(plan_us, 1),
+                   "execute_only_ms_per_step": round(exec_only_ms, 4),
+                   "execute_only_tflops": round(workloads.flops(cfg) / (exec_only_ms * 1e-3) / 1e12, 2),
                    "host_issue_us_per_step": round(host_s[0] / args.steps * 1e6, 1),
                    "host_wait_us_per_step": round(host_s[1] / args.steps * 1e6, 1)},
         "pct_of_mfma_peak": round(100.0 * value / peak, 2),
