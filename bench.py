@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (default: the 8192^3 2.5D configuration)")
     ap.add_argument("--dtype", choices=["bf16", "f32"], default=None,
                     help="element type of A and B (default: the workload's own)")
+    ap.add_argument("--c-dtype", choices=["f32", "bf16"], default="f32",
+                    help="element type of the C tiles (bf16: DMM_C_BF16, only for a C with one replica)")
     ap.add_argument("--ld-multiple", type=int, default=1, help="pad leading dimensions to this many elements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
@@ -85,7 +87,7 @@ def main() -> int:
     if args.dtype and args.dtype != cfg["dtype"]:
         cfg = dict(cfg, dtype=args.dtype, name=f"{cfg['name']}/{args.dtype}")
     A, B = workloads.make_operands(cfg)
-    prob = DeviceProblem(cfg, A, B, ld_multiple=args.ld_multiple)
+    prob = DeviceProblem(cfg, A, B, ld_multiple=args.ld_multiple, c_dtype=args.c_dtype)
     stream = torch.cuda.current_stream().cuda_stream
     c_rep = cfg["C"]["replication"]
 
@@ -104,7 +106,7 @@ def main() -> int:
     def step(record):
         h0 = time.perf_counter()
         plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])      # slicing + grouping (host)
-        plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING, stream)  # upload + GEMM + replica sum
+        plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING | prob.c_flags, stream)  # upload + GEMM + replica sum
         h1 = time.perf_counter()
         inflight.append((plan, record))
         if len(inflight) > DEPTH:
@@ -142,7 +144,7 @@ def main() -> int:
     torch.cuda.synchronize()
     te0 = time.perf_counter()
     for _ in range(args.steps):
-        prob.plan.execute_marshalled(prob.dtype_code, prob.args, 0, stream)
+        prob.plan.execute_marshalled(prob.dtype_code, prob.args, prob.c_flags, stream)
     torch.cuda.synchronize()
     exec_only_ms = (time.perf_counter() - te0) * 1e3 / args.steps
     gc.enable()
@@ -173,7 +175,7 @@ def main() -> int:
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: M={cfg['M']} K={cfg['K']} N={cfg['N']} {cfg['dtype']}, {cfg['what']}",
                    "virtual_ranks": cfg["nranks"], "tasks": prob.plan.num_tasks(), "groups": prob.plan.num_groups(),
-                   "work_items": prob.plan.num_items(), "ld_multiple": args.ld_multiple,
+                   "work_items": prob.plan.num_items(), "ld_multiple": args.ld_multiple, "c_dtype": args.c_dtype,
                    "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "plan_host_us": round(plan_us, 1),
                    "execute_only_ms_per_step": round(exec_only_ms, 4),
                    "execute_only_tflops": round(workloads.flops(cfg) / (exec_only_ms * 1e-3) / 1e12, 2),

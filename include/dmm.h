@@ -45,7 +45,8 @@ typedef enum {
                       dimension times element size) of an A, B or C tile is 2^24 bytes or more */
 } dmm_status;
 
-/* Element type of the A and B tiles.  C tiles and all partial sums are fp32. */
+/* Element type of the A and B tiles.  All partial sums are fp32, and so are the C tiles unless
+ * dmm_execute is given DMM_C_BF16. */
 typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
 
 /* dmm_plan flags: the data movement strategy of Section 4, i.e. which matrix stays in place
@@ -61,6 +62,10 @@ typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
 #define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
 #define DMM_TIMING 2u    /* record events around the GEMM launch and around the replica-sum launch
                             on the given stream; read them with dmm_plan_elapsed_ms */
+#define DMM_C_BF16 4u    /* the C tiles are bf16 buffers (c_ld in bf16 elements): every element receives
+                            its fp32 sum rounded to nearest even, once.  Only for a C with one replica
+                            (DMM_EINVAL otherwise): the partial sums of a replicated C stay fp32, since one
+                            rounding to bf16 already costs a relative error of up to 2^-8 per element */
 
 /* Distributed matrix descriptor (Section 3): shape, partition object, replication
  * factor.  The partition is a tile grid given by cut points (a uniform tile
@@ -140,9 +145,9 @@ int32_t dmm_plan_macro_tile(const dmm_plan_t *p);           /* edge of the squar
 /* Run the plan: C = A B (overwrite; C need not be initialised).
  *   dtype                 element type of every A and B tile
  *   a_tiles, b_tiles      host arrays of device pointers, one per (replica, tile) in table order
- *   c_tiles               host array of device pointers to fp32 tiles
+ *   c_tiles               host array of device pointers to fp32 tiles (bf16 tiles with DMM_C_BF16)
  *   a_ld, b_ld, c_ld      host arrays, leading dimension in elements, >= the tile's width
- *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING
+ *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING, DMM_C_BF16
  *   hip_stream            hipStream_t, may be null (default stream)
  * Pointers of empty tiles may be null.  Tile buffers are caller-owned and must
  * stay valid until the stream work completes.  Asynchronous: returns after

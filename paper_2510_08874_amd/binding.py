@@ -18,6 +18,7 @@ DMM_OK, DMM_EINVAL, DMM_ESHAPE, DMM_EREPL, DMM_ENOMEM, DMM_EHIP, DMM_ELD = 0, -1
 DMM_BF16, DMM_F32 = 1, 2
 DMM_NO_REDUCE = 1
 DMM_TIMING = 2
+DMM_C_BF16 = 4
 DMM_STATIONARY_B = 1          # dmm_plan flags
 DMM_STATIONARY_A = 2
 DMM_ITERATION_OFFSET = 4

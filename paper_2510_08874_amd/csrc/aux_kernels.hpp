@@ -137,11 +137,12 @@ __global__ __launch_bounds__(RED_NT) void broadcast_replica_kernel(const RedItem
 // fp32 per run); this kernel adds the runs of a macro-tile up in ascending k and writes C.  Fixed
 // cut, fixed order, no atomics: the result is deterministic.
 struct FixItem {
-  float *dst;            // top-left of the macro-tile in the C tile
-  int64_t ldc;
-  const float *parts;    // nparts consecutive 256 x 256 tiles
+  void *dst;             // top-left of the macro-tile in the C tile
+  int64_t ldc;           // elements
+  const float *parts;    // nparts consecutive 256 x 256 fp32 tiles
   int32_t m_ext, n_ext;
-  int32_t nparts, pad;
+  int32_t nparts;
+  int32_t c_es;          // bytes per element of dst: 4 = fp32, 2 = bf16 (the sum rounded to nearest even)
 };
 constexpr int FIX_ROWS = 4;           // rows of a macro-tile one workgroup sums: 4 rows x 64 float4 columns
 
@@ -168,11 +169,18 @@ __global__ __launch_bounds__(256) void sum_parts_kernel(const FixItem *__restric
         s.w = s.w + v[qq].w;
       }
   }
-  float *d = f.dst + (int64_t)r * f.ldc + c;
   const float e[4] = {s.x, s.y, s.z, s.w};
+  if (f.c_es == 4) {
+    float *d = (float *)f.dst + (int64_t)r * f.ldc + c;
 #pragma unroll
-  for (int x = 0; x < 4; ++x)
-    if (c + x < f.n_ext) __builtin_nontemporal_store(e[x], d + x);
+    for (int x = 0; x < 4; ++x)
+      if (c + x < f.n_ext) __builtin_nontemporal_store(e[x], d + x);
+  } else {
+    unsigned short *d = (unsigned short *)f.dst + (int64_t)r * f.ldc + c;
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+      if (c + x < f.n_ext) __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)e[x]), d + x);
+  }
 }
 
 // ------------------------------------------------------------------ matrix-pipe rate probe

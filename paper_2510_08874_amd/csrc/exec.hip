@@ -270,8 +270,11 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   using namespace dmm;
   if (!P || !a_tiles || !a_ld || !b_tiles || !b_ld || !c_tiles || !c_ld) return DMM_EINVAL;
   if (dtype != DMM_BF16 && dtype != DMM_F32) return DMM_EINVAL;
-  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING)) return DMM_EINVAL;
+  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING | DMM_C_BF16)) return DMM_EINVAL;
   const bool timed = (flags & DMM_TIMING) != 0;
+  // bf16 C tiles only where a tile receives a final sum: partial sums of a replicated C stay fp32
+  if ((flags & DMM_C_BF16) && P->C.c != 1) return DMM_EINVAL;
+  const int64_t c_es = (flags & DMM_C_BF16) ? 2 : 4;
   int rc;
   if ((rc = check_lds(P->A, a_ld)) || (rc = check_lds(P->B, b_ld)) || (rc = check_lds(P->C, c_ld))) return rc;
   const int64_t es = dtype == DMM_BF16 ? 2 : 4;
@@ -284,7 +287,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   for (int64_t i = 0; i < P->B.c * P->B.tiles_per_rep(); ++i)
     if (b_ld[i] * es >= MAX_PITCH) return DMM_ELD;
   for (int64_t i = 0; i < P->C.c * P->C.tiles_per_rep(); ++i)
-    if (c_ld[i] * 4 >= MAX_PITCH) return DMM_ELD;
+    if (c_ld[i] * c_es >= MAX_PITCH) return DMM_ELD;
   hipStream_t stream = (hipStream_t)hip_stream;
   try {
     if ((rc = ensure_state(P))) return rc;
@@ -323,7 +326,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       if (!c_tiles[ci]) return DMM_EINVAL;
       ItemDev d;
       d.ldc = c_ld[ci];
-      d.c = (float *)c_tiles[ci] + (w.m0 - P->C.rc[w.c_ti]) * d.ldc + (w.n0 - P->C.cc[w.c_tj]);
+      d.c = (char *)c_tiles[ci] + ((w.m0 - P->C.rc[w.c_ti]) * d.ldc + (w.n0 - P->C.cc[w.c_tj])) * c_es;
       if (w.group >= 0) {
         const Group &G = P->groups[(size_t)w.group];
         d.seg_begin = (int32_t)G.first;
@@ -339,7 +342,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       d.m_ext = w.m_ext;
       d.n_ext = w.n_ext;
       d.first_step = 0;
-      d.pad = 0;
+      d.c_es = (int32_t)c_es;
       hi[i] = d;
     }
     // K-split of the last round (see sum_parts_kernel): with W working items on `cus` CUs the
@@ -373,15 +376,15 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         f.m_ext = whole.m_ext;
         f.n_ext = whole.n_ext;
         f.nparts = runs;
-        f.pad = 0;
+        f.c_es = whole.c_es;
         fixes.push_back(f);
         for (int32_t j = 0; j < runs; ++j) {
           ItemDev r = whole;
-          r.c = (float *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);       // offset for now
+          r.c = (void *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);        // offset for now
           r.ldc = BN;
           r.first_step = j * per;
           r.nsteps = std::min(per, whole.nsteps - j * per);
-          r.pad = 1;                                                                          // marks "c is a scratch offset"
+          r.c_es = -4;                                                                        // fp32; negative marks "c is a scratch offset"
           if (j == 0) hi[i] = r;
           else hi.push_back(r);
         }
@@ -402,9 +405,9 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         if ((rc = scratch_pool().acquire(need, &P->dev->split_buf, &P->dev->split_cap))) return rc;
       }
       for (ItemDev &d : hi)
-        if (d.pad == 1) {
-          d.c = (float *)(P->dev->split_buf + (uintptr_t)d.c);
-          d.pad = 0;
+        if (d.c_es < 0) {
+          d.c = (void *)(P->dev->split_buf + (uintptr_t)d.c);
+          d.c_es = 4;
         }
       for (FixItem &f : fixes) f.parts = (const float *)(P->dev->split_buf + (uintptr_t)f.parts);
     }

@@ -70,15 +70,15 @@ struct SegDev {          // one K-segment of a group; pointers at the group's (m
 };
 
 struct ItemDev {         // one macro-tile, or a run of K steps of one
-  float *c;              // top-left of the macro-tile in the C tile (or in a partial-sum buffer)
-  int64_t ldc;
+  void *c;               // top-left of the macro-tile in the C tile (or in a partial-sum buffer)
+  int64_t ldc;           // elements
   int32_t seg_begin;
   int32_t nsteps;        // K steps this item performs; 0 = zero fill
   int32_t m_off, n_off;  // offset inside the group's sub-tile
   int32_t m_ext, n_ext;
   int32_t first_step;    // where it starts in the group's step sequence (steps of a segment:
                          // ceil(klen / K step); the sequence runs over the segments in order)
-  int32_t pad;
+  int32_t c_es;          // bytes per element of the destination: 4 = fp32, 2 = bf16 (rounded to nearest even)
 };
 
 constexpr int BM = 256, BN = 256;
@@ -107,6 +107,7 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 // Pointers read from the work table would otherwise be treated as generic (flat) addresses.
 typedef const __attribute__((address_space(1))) char *gptr;
 typedef __attribute__((address_space(1))) float *gfloat_ptr;
+typedef __attribute__((address_space(1))) unsigned short *gushort_ptr;
 
 template <int ES>
 struct Shape;
@@ -654,14 +655,16 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
   // epilogue: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 tile.
   // Addresses are the item's base plus a 32-bit byte offset (the host rejects C pitches of 2^24
   // bytes and more): one add per row, the four column blocks of a row through the immediate offset.
-  // A full 256 x 256 item stores without predicates.
+  // A full 256 x 256 item stores without predicates.  A bf16 destination receives the fp32 sum
+  // rounded to nearest even, one 2-byte store per element.
   const __attribute__((address_space(1))) char *cbytes = (const __attribute__((address_space(1))) char *)it.c;
-  const unsigned pitch = (unsigned)it.ldc * 4u;
   const int row0 = wm * WTM + 4 * (lane >> 5);
   const int col0 = wn * WTN + (lane & 31);
-  const unsigned voff = (unsigned)row0 * pitch + (unsigned)col0 * 4u;
-  auto store_all = [&](auto full_tag) {
+  auto store_all = [&](auto full_tag, auto es_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
+    constexpr int CES = decltype(es_tag)::value;
+    const unsigned pitch = (unsigned)it.ldc * (unsigned)CES;
+    const unsigned voff = (unsigned)row0 * pitch + (unsigned)col0 * (unsigned)CES;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -671,13 +674,25 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
         if (FULL || row0 + dr < it.m_ext) {
 #pragma unroll
           for (int j = 0; j < FN; ++j)
-            if (FULL || col0 + j * 32 < it.n_ext)
-              __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(cbytes + o + j * 128));
+            if (FULL || col0 + j * 32 < it.n_ext) {
+              if constexpr (CES == 4) {
+                __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(cbytes + o + j * 128));
+              } else {
+                const __bf16 h = (__bf16)acc[i][j][r];
+                __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, h), (gushort_ptr)(cbytes + o + j * 64));
+              }
+            }
         }
       }
   };
-  if (it.m_ext == BM && it.n_ext == BN) store_all(std::true_type{});
-  else store_all(std::false_type{});
+  const bool full = it.m_ext == BM && it.n_ext == BN;
+  if (it.c_es == 4) {
+    if (full) store_all(std::true_type{}, std::integral_constant<int, 4>{});
+    else store_all(std::false_type{}, std::integral_constant<int, 4>{});
+  } else {
+    if (full) store_all(std::true_type{}, std::integral_constant<int, 2>{});
+    else store_all(std::false_type{}, std::integral_constant<int, 2>{});
+  }
 }
 
 }  // namespace dmm

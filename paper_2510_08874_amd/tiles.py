@@ -99,7 +99,7 @@ class DeviceProblem:
     sets and the marshalled argument arrays of ``dmm_execute``."""
 
     def __init__(self, cfg: Dict, A_host: Optional[np.ndarray] = None, B_host: Optional[np.ndarray] = None,
-                 ld_multiple: int = 1, c_fill: Optional[float] = None, device="cuda"):
+                 ld_multiple: int = 1, c_fill: Optional[float] = None, device="cuda", c_dtype: str = "f32"):
         from . import binding
         self.cfg = cfg
         self.binding = binding
@@ -110,7 +110,10 @@ class DeviceProblem:
                                  (binding.DMM_ITERATION_OFFSET if cfg.get("iteration_offset") else 0))
         self.A = TileSet(cfg["A"], tdt, device, ld_multiple)
         self.B = TileSet(cfg["B"], tdt, device, ld_multiple)
-        self.C = TileSet(cfg["C"], torch.float32, device, ld_multiple, fill=c_fill)
+        # C tiles are fp32, or bf16 when asked for (DMM_C_BF16 then goes with every execute)
+        self.c_flags = binding.DMM_C_BF16 if c_dtype == "bf16" else 0
+        self.C = TileSet(cfg["C"], torch.bfloat16 if c_dtype == "bf16" else torch.float32, device, ld_multiple,
+                         fill=c_fill)
         if A_host is not None:
             self.A.scatter(A_host)
         if B_host is not None:
@@ -121,7 +124,7 @@ class DeviceProblem:
     def execute(self, flags: int = 0, stream: Optional[int] = None) -> None:
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
-        self.plan.execute_marshalled(self.dtype_code, self.args, flags, stream)
+        self.plan.execute_marshalled(self.dtype_code, self.args, flags | self.c_flags, stream)
 
     def reduce(self, origin: int = 0, stream: Optional[int] = None) -> None:
         if stream is None:

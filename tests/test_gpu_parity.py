@@ -459,6 +459,89 @@ def test_no_reduce_flag_leaves_partials():
     prob.close()
 
 
+# ---- bf16 C tiles (DMM_C_BF16) -------------------------------------------------------------
+
+U16 = 2.0 ** -8          # half an ulp of bf16, relative: the most one rounding to nearest can move a value
+
+
+def _check_bf16_out(C_gpu, C_ref, A64, B64, what):
+    """A bf16 C element is the fp32 sum rounded to nearest: it may differ from the exact value by
+    the fp32 accumulation bound plus half a bf16 ulp of the (bounded) sum.  Truncation instead of
+    rounding, or rounding twice, breaks the element bound; the Frobenius bar is the stated one."""
+    got = C_gpu.astype(np.float64)
+    acc = 4.0 * A64.shape[1] * U32 * np.outer(np.linalg.norm(A64, axis=1), np.linalg.norm(B64, axis=0)) + 1e-30
+    bound = acc + U16 * (np.abs(C_ref) + acc) * (1.0 + 1e-6) + 2.0 ** -133      # + half the smallest subnormal step
+    worst = np.max(np.abs(got - C_ref) / bound)
+    assert worst <= 1.0, f"{what}: element error {worst:.3f} x (accumulation bound + half a bf16 ulp)"
+    err = np.linalg.norm(got - C_ref) / max(np.linalg.norm(C_ref), 1e-300)
+    assert err <= TOL["bf16"], f"{what}: relative Frobenius error {err:.3e}"
+
+
+@pytest.mark.parametrize("name,dims,ldm", [
+    ("cfg2", (768, 520, 640), 1),
+    ("cfg3", (300, 333, 1100), 1),     # odd leading dimensions: 2-byte aligned rows of C
+    ("cfg5", (1229, 997, 1100), 1),
+    ("cfg5", (1229, 997, 1100), 8),
+    ("cfg1", (260, 130, 515), 1),      # fp32 operands, bf16 result
+])
+def test_bf16_c_tiles(name, dims, ldm):
+    """C tiles in bf16: against the fp64 oracle within the stated bar and the element bound, bitwise
+    equal to the fp32-C run of the same plan rounded to nearest even, padding columns untouched."""
+    cfg = workloads.scaled_config(name, *dims)
+    A, B = workloads.make_operands(cfg)
+    A64, B64 = _to_f64(A, cfg), _to_f64(B, cfg)
+    C_ref = omatmul.matmul(A, B, bf16=(cfg["dtype"] == "bf16"))
+    prob = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"), c_dtype="bf16")
+    prob.execute()
+    got = prob.c_global(0)
+    _check_bf16_out(got, C_ref, A64, B64, cfg["name"])
+    for t, ld, (ti, tj) in zip(prob.C.tensors, prob.C.ld, [(i, j) for i in range(prob.C.gr) for j in range(prob.C.gc)]):
+        r0, r1, c0, c1 = prob.C.bounds(ti, tj)
+        if t is not None and ld > c1 - c0:
+            assert torch.isnan(t[:, c1 - c0:]).all(), "padding of a bf16 C tile was written"
+    prob.close()
+    wide = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
+    wide.execute()
+    want = workloads.bf16_to_f32(workloads.bf16_round(wide.c_global(0)))
+    wide.close()
+    assert np.array_equal(got, want)
+
+
+def test_bf16_c_tiles_k_split_and_zero_fill():
+    """The two other writers of C honour the element type: the pass that adds up K-split runs, and zero fill."""
+    M, K, N = 300, 8192, 300
+    cfg = dict(name="ksplit-bf16out", M=M, K=K, N=N, nranks=1, dtype="bf16",
+               A=workloads.block_desc(M, K, 1, 1), B=workloads.block_desc(K, N, 1, 1), C=workloads.block_desc(M, N, 1, 1),
+               dist=("normal", 1.0), seeds=(41, 42))
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"), c_dtype="bf16")
+    prob.execute()
+    got = prob.c_global(0)
+    _check_bf16_out(got, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg["name"])
+    prob.execute()
+    assert np.array_equal(got, prob.c_global(0))
+    prob.close()
+    cfg = dict(name="k0-bf16out", M=40, K=0, N=30, dtype="f32", nranks=2,
+               A=workloads.block_desc(40, 0, 2, 1), B=workloads.block_desc(0, 30, 1, 2),
+               C=workloads.block_desc(40, 30, 2, 1), dist=("normal", 1.0), seeds=(5, 6))
+    prob = _device_problem(cfg, np.zeros((40, 0), np.float32), np.zeros((0, 30), np.float32), c_fill=float("nan"),
+                           c_dtype="bf16")
+    prob.execute()
+    assert (prob.c_global(0) == 0).all()
+    prob.close()
+
+
+def test_bf16_c_tiles_need_an_unreplicated_c():
+    from paper_2510_08874_amd import binding
+    cfg = workloads.scaled_config("cfg4", 128, 128, 128)
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B)
+    with pytest.raises(binding.DmmError) as e:
+        prob.execute(flags=binding.DMM_C_BF16)
+    assert e.value.kind == "EINVAL"
+    prob.close()
+
+
 # ---- error paths that reach the device entry points ---------------------------------
 
 def test_execute_rejects_bad_arguments():
