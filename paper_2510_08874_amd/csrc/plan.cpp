@@ -17,6 +17,7 @@
 //    modulo 8 selects the XCD, each XCD has its own L2).
 #include <algorithm>
 #include <cstring>
+#include <initializer_list>
 #include <new>
 
 #include "plan_internal.h"
@@ -274,12 +275,26 @@ struct GroupKey {
 
 inline GroupKey key_of(const dmm_task &t) { return {t.c_rep, t.c_ti, t.c_tj, t.m0, t.n0}; }
 
-void group_tasks(dmm_plan_t *P) {
+// Sorted, duplicate-free union of cut lists.
+std::vector<int64_t> merged_cuts(std::initializer_list<const std::vector<int64_t> *> lists) {
+  std::vector<int64_t> out;
+  for (const std::vector<int64_t> *l : lists) out.insert(out.end(), l->begin(), l->end());
+  std::sort(out.begin(), out.end());
+  out.erase(std::unique(out.begin(), out.end()), out.end());
+  return out;
+}
+
+// position of every cut of `cuts` in `merged` (which contains them all)
+std::vector<int32_t> ranks_in(const std::vector<int64_t> &merged, const std::vector<int64_t> &cuts) {
+  std::vector<int32_t> r(cuts.size());
+  for (size_t i = 0; i < cuts.size(); ++i)
+    r[i] = (int32_t)(std::lower_bound(merged.begin(), merged.end(), cuts[i]) - merged.begin());
+  return r;
+}
+
+// The general grouping: a comparison sort on (output sub-tile, k, original position).
+void sort_order_by_comparison(dmm_plan_t *P) {
   const auto &T = P->tasks;
-  const int64_t n = (int64_t)T.size();
-  P->order.resize(n);
-  for (int64_t i = 0; i < n; ++i) P->order[i] = i;
-  // total order: output sub-tile, then k, then original position (= stable)
   std::sort(P->order.begin(), P->order.end(), [&T](int64_t x, int64_t y) {
     const dmm_task &a = T[x], &b = T[y];
     if (a.c_rep != b.c_rep) return a.c_rep < b.c_rep;
@@ -290,6 +305,82 @@ void group_tasks(dmm_plan_t *P) {
     if (a.k0 != b.k0) return a.k0 < b.k0;
     return x < y;
   });
+}
+
+// The same order without comparing tasks: an op's m0 is the largest of a few cut points (the
+// lower cuts of its C tile row and A tile row, and of its replica's share of M with Stationary
+// B), so its position among the merged row cuts is the largest of their positions, read from
+// small tables; likewise n0.  That numbers every possible output sub-tile densely; a table walks
+// them in (replica, tile row, tile column, m0, n0) order, a counting sort (stable) puts the ops
+// into their groups, and a group whose ops did not arrive in ascending k is sorted on its own.
+// Returns false (nothing done) when the dense numbering would be much larger than the op list.
+bool sort_order_by_counting(dmm_plan_t *P, uint32_t flags) {
+  const auto &T = P->tasks;
+  const size_t n = T.size();
+  const Grid &A = P->A, &B = P->B, &C = P->C;
+  std::vector<int64_t> m_share, n_share;                 // share boundaries of a replicated stationary B / A
+  if (flags & DMM_STATIONARY_B)
+    for (int32_t r = 0; r <= B.c; ++r) m_share.push_back((int64_t)r * A.rows / B.c);
+  if (flags & DMM_STATIONARY_A)
+    for (int32_t r = 0; r <= A.c; ++r) n_share.push_back((int64_t)r * B.cols / A.c);
+  const std::vector<int64_t> mc = merged_cuts({&A.rc, &C.rc, &m_share}), nc = merged_cuts({&B.cc, &C.cc, &n_share});
+  const size_t MR = mc.size(), NR = nc.size();
+  const size_t dense = (size_t)C.c * MR * NR;
+  if (dense > 4 * n + 4096) return false;
+  const std::vector<int32_t> ra = ranks_in(mc, A.rc), rcr = ranks_in(mc, C.rc), rms = ranks_in(mc, m_share);
+  const std::vector<int32_t> rb = ranks_in(nc, B.cc), rcc = ranks_in(nc, C.cc), rns = ranks_in(nc, n_share);
+  std::vector<uint32_t> gid(n);
+  std::vector<int64_t> count(dense + 1, 0);
+  for (size_t i = 0; i < n; ++i) {
+    const dmm_task &t = T[i];
+    int32_t mr = std::max(ra[(size_t)t.a_ti], rcr[(size_t)t.c_ti]);
+    int32_t nr = std::max(rb[(size_t)t.b_tj], rcc[(size_t)t.c_tj]);
+    if (!rms.empty()) mr = std::max(mr, rms[(size_t)t.b_rep]);
+    if (!rns.empty()) nr = std::max(nr, rns[(size_t)t.a_rep]);
+    if (mc[(size_t)mr] != t.m0 || nc[(size_t)nr] != t.n0) return false;   // not of the expected form: general sort
+    const size_t g = ((size_t)t.c_rep * MR + (size_t)mr) * NR + (size_t)nr;
+    gid[i] = (uint32_t)g;
+    ++count[g];
+  }
+  // first position of every dense number, walking them in group order
+  std::vector<int64_t> start(dense, 0);
+  int64_t run = 0;
+  for (int32_t rep = 0; rep < C.c; ++rep)
+    for (int32_t ti = 0; ti < C.gr; ++ti)
+      for (int32_t tj = 0; tj < C.gc; ++tj)
+        for (int32_t mr = rcr[(size_t)ti]; mr < rcr[(size_t)ti + 1]; ++mr)
+          for (int32_t nr = rcc[(size_t)tj]; nr < rcc[(size_t)tj + 1]; ++nr) {
+            const size_t g = ((size_t)rep * MR + (size_t)mr) * NR + (size_t)nr;
+            start[g] = run;
+            run += count[g];
+          }
+  if (run != (int64_t)n) return false;
+  for (size_t i = 0; i < n; ++i) P->order[(size_t)start[gid[i]]++] = (int64_t)i;
+  // inside a group: ascending k, ties (none in a valid plan) by original position
+  size_t pos = 0;
+  while (pos < n) {
+    const uint32_t g = gid[(size_t)P->order[pos]];
+    size_t end = pos + 1;
+    bool ascending = true;
+    for (; end < n && gid[(size_t)P->order[end]] == g; ++end)
+      if (T[(size_t)P->order[end]].k0 < T[(size_t)P->order[end - 1]].k0) ascending = false;
+    if (!ascending)
+      std::stable_sort(P->order.begin() + pos, P->order.begin() + end,
+                       [&T](int64_t x, int64_t y) { return T[(size_t)x].k0 < T[(size_t)y].k0; });
+    pos = end;
+  }
+  return true;
+}
+
+void group_tasks(dmm_plan_t *P, uint32_t flags) {
+  const auto &T = P->tasks;
+  const int64_t n = (int64_t)T.size();
+  P->order.resize(n);
+  // total order: output sub-tile, then k, then original position (= stable)
+  if (n > (int64_t)UINT32_MAX || !sort_order_by_counting(P, flags)) {
+    for (int64_t i = 0; i < n; ++i) P->order[i] = i;
+    sort_order_by_comparison(P);
+  }
   P->group_offsets.clear();
   P->groups.clear();
   for (int64_t pos = 0; pos < n; ++pos) {
@@ -442,6 +533,14 @@ int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matri
       delete P;
       return DMM_ESHAPE;
     }
+    {
+      // room for the op list up front: the boxes are cells of the merged cut grids (at most one
+      // more k interval per replica share), so their number is known to within that
+      const size_t mi = dmm::merged_cuts({&P->A.rc, &P->C.rc}).size(), ni = dmm::merged_cuts({&P->B.cc, &P->C.cc}).size();
+      const size_t ki = dmm::merged_cuts({&P->A.cc, &P->B.rc}).size() + (size_t)P->C.c;
+      const double est = (double)mi * (double)ni * (double)ki;
+      if (est < 5.0e7) P->tasks.reserve((size_t)est);
+    }
     for (int32_t rank = 0; rank < nranks; ++rank) {
       const size_t first = P->tasks.size();
       if (flags & DMM_STATIONARY_B) dmm::generate_rank_b(*P, rank, &P->tasks);
@@ -449,7 +548,7 @@ int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matri
       else dmm::generate_rank(*P, rank, &P->tasks);
       if (flags & DMM_ITERATION_OFFSET) dmm::apply_iteration_offset(&P->tasks, first, flags);
     }
-    dmm::group_tasks(P);
+    dmm::group_tasks(P, flags);
     dmm::build_items(P);
   } catch (const std::bad_alloc &) {
     delete P;

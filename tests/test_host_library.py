@@ -176,3 +176,69 @@ def test_null_arguments_rejected():
     assert L.dmm_execute(None, 1, None, None, None, None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_reduce_replicas(None, None, None, 0, None) == binding.DMM_EINVAL
     L.dmm_plan_destroy(None)
+
+
+# ---- block-cyclic layouts: tile grid much larger than the process grid (Section 2.1) ----------
+
+@pytest.mark.parametrize("mode", ["C", "B", "A"])
+@pytest.mark.parametrize("dims,nb", [((768, 512, 640), 64), ((700, 333, 517), 96)])
+def test_block_cyclic_bit_exact(dims, nb, mode):
+    """Up to 12 x 12 tiles dealt to a 2 x 4 process grid, ragged last tiles in the second case:
+    every rank owns many scattered tiles, and the list, its grouped order and the group offsets
+    still equal the oracle's."""
+    cfg = workloads._block_cyclic(nb, *dims)
+    plan, want, (A, B, C) = _both(cfg, mode)
+    got = plan.tasks()
+    assert got == [tuple(t) for t in want]
+    order, offsets = oplanner.reorder(want)
+    assert plan.order() == order and plan.group_offsets() == offsets
+    owners = {t[0] for t in got}
+    assert owners == set(range(8))
+    plan.destroy()
+
+
+@pytest.mark.parametrize("name", workloads.BLOCK_CYCLIC_NAMES)
+def test_block_cyclic_full_size_counts(name):
+    """At the benchmark size (up to 64^3 = 262144 ops) the properties that hold at any size:
+    g^3 ops, g^2 groups of g ascending K-segments each, every op a full nb^3 box, every rank g^3 / 8 ops."""
+    cfg = workloads.config(name)
+    nb = int(name[2:])
+    g = 8192 // nb
+    plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])
+    assert plan.num_tasks() == g ** 3 and plan.num_groups() == g * g
+    n = plan.num_tasks()
+    T = np.ctypeslib.as_array(ctypes.cast(binding.lib().dmm_plan_tasks(plan.handle), ctypes.POINTER(ctypes.c_int32)),
+                              shape=(n, ctypes.sizeof(binding.dmm_task) // 4))
+    ranks = T[:, 0]
+    assert (np.bincount(ranks, minlength=8) == g ** 3 // 8).all()
+    box = T[:, 10:].copy().view(np.int64)                     # m0 m1 k0 k1 n0 n1
+    assert ((box[:, 1] - box[:, 0] == nb) & (box[:, 3] - box[:, 2] == nb) & (box[:, 5] - box[:, 4] == nb)).all()
+    order = np.ctypeslib.as_array(binding.lib().dmm_plan_order(plan.handle), shape=(n,))
+    off = np.ctypeslib.as_array(binding.lib().dmm_plan_group_offsets(plan.handle), shape=(g * g + 1,))
+    assert (np.diff(off) == g).all() and sorted(order.tolist()) == list(range(n))
+    k0 = box[order, 2].reshape(g * g, g)
+    assert (k0 == np.arange(g) * nb).all()                  # every group walks k = 0, nb, 2 nb, ...
+    mn = box[order][:, [0, 4]].reshape(g * g, g, 2)
+    assert (mn == mn[:, :1, :]).all()                         # one output sub-tile per group
+    # owner of C tile (i, j) on the 2 x 4 process grid
+    ti, tj = mn[:, 0, 0] // nb, mn[:, 0, 1] // nb
+    assert (ranks[order].reshape(g * g, g) == ((ti % 2) * 4 + tj % 4)[:, None]).all()
+    plan.destroy()
+
+
+def test_grouping_falls_back_when_output_sub_tiles_outnumber_ops():
+    """Eight C replicas but a single k value: seven replicas get no op at all, so a dense numbering of
+    (replica, row interval, column interval) is much larger than the op list and the library takes
+    its comparison sort; the result still equals the oracle's."""
+    M, K, N, p = 70, 1, 66, 8
+    cuts_m, cuts_n = tuple(range(0, M + 1, 2)), tuple(range(0, N + 1, 2))
+    prob = dict(nranks=p,
+                A=dict(rows=M, cols=K, row_cuts=cuts_m, col_cuts=(0, K), proc_rows=1, proc_cols=1, replication=8),
+                B=dict(rows=K, cols=N, row_cuts=(0, K), col_cuts=cuts_n, proc_rows=1, proc_cols=1, replication=8),
+                C=dict(rows=M, cols=N, row_cuts=(0, M), col_cuts=(0, N), proc_rows=1, proc_cols=1, replication=8))
+    plan, want, _ = _both(prob)
+    assert len(want) == 35 * 33
+    assert plan.tasks() == [tuple(t) for t in want]
+    order, offsets = oplanner.reorder(want)
+    assert plan.order() == order and plan.group_offsets() == offsets
+    plan.destroy()

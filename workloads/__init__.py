@@ -145,8 +145,33 @@ def _mlp(layer: int, part: str) -> Dict:
                 what=f"MLP-{layer} ({what})")
 
 
+# ---------------------------------------------------------------------------
+# ScaLAPACK-style block-cyclic layouts (Section 2.1): one tile shape nb x nb per matrix,
+# the tile grid much larger than the process grid, tiles dealt to the ranks cyclically.
+
+BLOCK_CYCLIC_NB = (512, 256, 128)
+
+
+def block_cyclic_desc(rows: int, cols: int, nb_rows: int, nb_cols: int, proc_rows: int, proc_cols: int,
+                      replication: int = 1) -> Dict:
+    """Tiles of nb_rows x nb_cols (the last row / column of tiles may be ragged) on a
+    proc_rows x proc_cols process grid."""
+    return desc(rows, cols, uniform_cuts(rows, -(-rows // nb_rows)), uniform_cuts(cols, -(-cols // nb_cols)),
+                proc_rows, proc_cols, replication)
+
+
+def _block_cyclic(nb: int, M: int = 8192, K: int = 8192, N: int = 8192) -> Dict:
+    p, pr, pc = 8, 2, 4
+    return dict(name=f"bc{nb}", M=M, K=K, N=N, dtype="bf16", nranks=p,
+                A=block_cyclic_desc(M, K, nb, nb, pr, pc), B=block_cyclic_desc(K, N, nb, nb, pr, pc),
+                C=block_cyclic_desc(M, N, nb, nb, pr, pc),
+                dist=("normal", 1.0 / np.sqrt(float(K))), seeds=(7000 + nb, 7001 + nb),
+                what=f"block-cyclic: A, B, C in {nb} x {nb} tiles dealt to a 2x4 process grid")
+
+
 _BUILDERS = dict(cfg1=_cfg1, cfg2=_cfg2, cfg3=_cfg3, cfg4=_cfg4, cfg5=_cfg5)
 CONFIG_NAMES = tuple(_BUILDERS)
+BLOCK_CYCLIC_NAMES = tuple(f"bc{nb}" for nb in BLOCK_CYCLIC_NB)
 MLP_NAMES = tuple(f"mlp{layer}-{part}" for layer in (1, 2) for part in MLP_PARTITIONINGS)
 
 
@@ -156,12 +181,16 @@ def config(name: str) -> Dict:
     if name in MLP_NAMES:
         layer, part = name.split("-")
         return _mlp(int(layer[3:]), part)
+    if name in BLOCK_CYCLIC_NAMES:
+        return _block_cyclic(int(name[2:]))
     raise KeyError(name)
 
 
 def scaled_config(name: str, M: int, K: int, N: int) -> Dict:
     """Same partitioning family as ``name`` at another size (for quick tests):
     uniform grids are rebuilt for the new shape, jittered ones re-drawn."""
+    if name in BLOCK_CYCLIC_NAMES:
+        return dict(_block_cyclic(int(name[2:]), M, K, N), name=f"{name}@{M}x{K}x{N}")
     base = config(name)
     out = dict(base, M=M, K=K, N=N, name=f"{name}@{M}x{K}x{N}")
     dims = dict(A=(M, K), B=(K, N), C=(M, N))
