@@ -4,6 +4,7 @@ or through ``__graft_entry__.build()``."""
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -21,15 +22,42 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+def check_resources(remarks: str) -> None:
+    """The grouped GEMM keeps 256 accumulators per lane in the accumulator file and needs every
+    other register to stay out of memory: fail the build if the compiler reports scratch use or
+    spills for it (a change to its epilogue once cost 36 bytes of scratch per lane unnoticed)."""
+    blocks = re.split(r"remark: Function Name: ", remarks)[1:]
+    seen = 0
+    for b in blocks:
+        name = b.split()[0]
+        if "grouped_gemm_kernel" not in name:
+            continue
+        seen += 1
+        usage = {k: int(v) for k, v in re.findall(r"remark:\s+(ScratchSize \[bytes/lane\]|VGPRs Spill|SGPRs Spill|AGPRs): (\d+)", b)}
+        if usage.get("ScratchSize [bytes/lane]", 0) or usage.get("VGPRs Spill", 0) or usage.get("AGPRs") != 256:
+            raise RuntimeError(f"{name}: unexpected register use {usage}")
+    if seen == 0:
+        raise RuntimeError("no resource report for grouped_gemm_kernel in the compiler's remarks")
+
+
 def build(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc, *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        if src.endswith(".hip"):
+            cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
         if verbose:
             print(" ".join(cmd), flush=True)
-        subprocess.run(cmd, check=True)
+        if src.endswith(".hip"):
+            done = subprocess.run(cmd, check=False, stderr=subprocess.PIPE, text=True)
+            sys.stderr.write("".join(l + "\n" for l in done.stderr.splitlines()
+                                     if "kernel-resource-usage" not in l and not re.match(r"^\s+(\d+ )?\|", l)))
+            done.check_returncode()
+            check_resources(done.stderr)
+        else:
+            subprocess.run(cmd, check=True)
         objs.append(obj)
     cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
     if verbose:

@@ -660,11 +660,11 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
   const __attribute__((address_space(1))) char *cbytes = (const __attribute__((address_space(1))) char *)it.c;
   const int row0 = wm * WTM + 4 * (lane >> 5);
   const int col0 = wn * WTN + (lane & 31);
-  auto store_all = [&](auto full_tag, auto es_tag) {
+  const bool wide = it.c_es == 4;
+  const unsigned pitch = (unsigned)it.ldc * (unsigned)it.c_es;
+  const unsigned voff = (unsigned)row0 * pitch + (unsigned)col0 * (unsigned)it.c_es;
+  auto store_all = [&](auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
-    constexpr int CES = decltype(es_tag)::value;
-    const unsigned pitch = (unsigned)it.ldc * (unsigned)CES;
-    const unsigned voff = (unsigned)row0 * pitch + (unsigned)col0 * (unsigned)CES;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -672,27 +672,29 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
         const int dr = i * 32 + 8 * (r >> 2) + (r & 3);
         const unsigned o = voff + (unsigned)dr * pitch;
         if (FULL || row0 + dr < it.m_ext) {
+          if (wide) {
 #pragma unroll
-          for (int j = 0; j < FN; ++j)
-            if (FULL || col0 + j * 32 < it.n_ext) {
-              if constexpr (CES == 4) {
+            for (int j = 0; j < FN; ++j)
+              if (FULL || col0 + j * 32 < it.n_ext)
                 __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(cbytes + o + j * 128));
-              } else {
-                const __bf16 h = (__bf16)acc[i][j][r];
-                __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, h), (gushort_ptr)(cbytes + o + j * 64));
+          } else {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+              if (FULL || col0 + j * 32 < it.n_ext)
+              {
+                // the copy out of the accumulator file is written out, next to its use: left to the
+                // compiler, all 256 sums are moved to ordinary registers ahead of the first store
+                float v;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
+                __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)v),
+                                            (gushort_ptr)(cbytes + o + j * 64));
               }
-            }
+          }
         }
       }
   };
-  const bool full = it.m_ext == BM && it.n_ext == BN;
-  if (it.c_es == 4) {
-    if (full) store_all(std::true_type{}, std::integral_constant<int, 4>{});
-    else store_all(std::false_type{}, std::integral_constant<int, 4>{});
-  } else {
-    if (full) store_all(std::true_type{}, std::integral_constant<int, 2>{});
-    else store_all(std::false_type{}, std::integral_constant<int, 2>{});
-  }
+  if (it.m_ext == BM && it.n_ext == BN) store_all(std::true_type{});
+  else store_all(std::false_type{});
 }
 
 }  // namespace dmm
