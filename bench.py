@@ -54,6 +54,9 @@ def main() -> int:
                     help="element type of A and B (default: the workload's own)")
     ap.add_argument("--c-dtype", choices=["f32", "bf16"], default="f32",
                     help="element type of the C tiles (bf16: DMM_C_BF16, only for a C with one replica)")
+    ap.add_argument("--merge", choices=["auto", "always", "never"], default="auto",
+                    help="merged macro-tiles: where they save a tenth of the macro-tiles (auto), wherever the plan "
+                         "can have them (DMM_MERGE_ALWAYS), or not at all (DMM_NO_MERGE)")
     ap.add_argument("--ld-multiple", type=int, default=1, help="pad leading dimensions to this many elements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
@@ -86,6 +89,10 @@ def main() -> int:
     cfg = workloads.config(args.workload)
     if args.dtype and args.dtype != cfg["dtype"]:
         cfg = dict(cfg, dtype=args.dtype, name=f"{cfg['name']}/{args.dtype}")
+    if args.merge == "always":
+        cfg = dict(cfg, merge_always=True)
+    plan_flags = binding.DMM_MERGE_ALWAYS if args.merge == "always" else 0
+    exec_flags = binding.DMM_NO_MERGE if args.merge == "never" else 0
     A, B = workloads.make_operands(cfg)
     prob = DeviceProblem(cfg, A, B, ld_multiple=args.ld_multiple, c_dtype=args.c_dtype)
     stream = torch.cuda.current_stream().cuda_stream
@@ -105,8 +112,8 @@ def main() -> int:
 
     def step(record):
         h0 = time.perf_counter()
-        plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])      # slicing + grouping (host)
-        plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING | prob.c_flags, stream)  # upload + GEMM + replica sum
+        plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], plan_flags)      # slicing + grouping (host)
+        plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING | prob.c_flags | exec_flags, stream)  # upload + GEMM + replica sum
         h1 = time.perf_counter()
         inflight.append((plan, record))
         if len(inflight) > DEPTH:
@@ -144,7 +151,7 @@ def main() -> int:
     torch.cuda.synchronize()
     te0 = time.perf_counter()
     for _ in range(args.steps):
-        prob.plan.execute_marshalled(prob.dtype_code, prob.args, prob.c_flags, stream)
+        prob.plan.execute_marshalled(prob.dtype_code, prob.args, prob.c_flags | exec_flags, stream)
     torch.cuda.synchronize()
     exec_only_ms = (time.perf_counter() - te0) * 1e3 / args.steps
     gc.enable()
@@ -152,8 +159,17 @@ def main() -> int:
     # host-only cost of planning, for the record
     tp0 = time.perf_counter()
     for _ in range(20):
-        binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"]).destroy()
+        binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], plan_flags).destroy()
     plan_us = (time.perf_counter() - tp0) / 20 * 1e6
+    # ... and of writing out the op list, its grouped order and the per-group macro-tiles (a plan with
+    # merged macro-tiles runs without them and leaves that to the first accessor call)
+    tp0 = time.perf_counter()
+    for _ in range(5):
+        pl = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], plan_flags)
+        pl.num_tasks()
+        pl.destroy()
+    list_us = (time.perf_counter() - tp0) / 5 * 1e6
+    ran_merged = prob.plan.ran_merged()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     fl = workloads.flops(cfg)
@@ -175,8 +191,10 @@ def main() -> int:
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: M={cfg['M']} K={cfg['K']} N={cfg['N']} {cfg['dtype']}, {cfg['what']}",
                    "virtual_ranks": cfg["nranks"], "tasks": prob.plan.num_tasks(), "groups": prob.plan.num_groups(),
-                   "work_items": prob.plan.num_items(), "ld_multiple": args.ld_multiple, "c_dtype": args.c_dtype,
+                   "work_items": prob.plan.num_items(), "merged_work_items": prob.plan.num_merged_items(),
+                   "ran_merged": ran_merged, "merge": args.merge, "ld_multiple": args.ld_multiple, "c_dtype": args.c_dtype,
                    "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "plan_host_us": round(plan_us, 1),
+                   "plan_with_op_list_host_us": round(list_us, 1),
                    "execute_only_ms_per_step": round(exec_only_ms, 4),
                    "execute_only_tflops": round(workloads.flops(cfg) / (exec_only_ms * 1e-3) / 1e12, 2),
                    "host_issue_us_per_step": round(host_s[0] / args.steps * 1e6, 1),

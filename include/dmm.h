@@ -57,11 +57,15 @@ typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
  * positions later in their cyclic order.  It changes the order of the raw task list only
  * (what a rank would fetch when); the grouped order and the results do not depend on it. */
 #define DMM_ITERATION_OFFSET 4u
+/* Keep the merged work list (see dmm_plan_merged_items) whenever the plan can have one, also
+ * where it saves no macro-tiles. */
+#define DMM_MERGE_ALWAYS 8u
 
 /* dmm_execute flags */
 #define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
 #define DMM_TIMING 2u    /* record events around the GEMM launch and around the replica-sum launch
                             on the given stream; read them with dmm_plan_elapsed_ms */
+#define DMM_NO_MERGE 8u  /* run the macro-tiles of dmm_plan_items even where the plan has merged ones */
 #define DMM_C_BF16 4u    /* the C tiles are bf16 buffers (c_ld in bf16 elements): every element receives
                             its fp32 sum rounded to nearest even, once.  Only for a C with one replica
                             (DMM_EINVAL otherwise): the partial sums of a replicated C stay fp32, since one
@@ -113,6 +117,21 @@ typedef struct {
   int32_t reserved;
 } dmm_work_item;
 
+/* A merged macro-tile: the C region rows [m0, m0 + m_ext) x cols [n0, n0 + n_ext) of replica
+ * c_rep, cut from the replica as a whole, so that it may cover several output sub-tiles, i.e.
+ * meet several tiles of A, B and C.  Its rows fall into row_pieces intervals of the merged row
+ * cuts of A and C, its columns into col_pieces intervals of the merged column cuts of B and C;
+ * inside the macro-tile a column piece starts at a multiple of 8 columns.  One workgroup
+ * accumulates it over the K-segments of the replica's share of k in ascending k, exactly as the
+ * macro-tiles of dmm_plan_items do for their group, so both lists give bitwise the same C. */
+typedef struct {
+  int64_t m0, n0;
+  int32_t m_ext, n_ext;
+  int32_t c_rep;
+  int32_t row_pieces, col_pieces;
+  int32_t reserved;
+} dmm_merged_item;
+
 /* A plan may be used by one thread at a time (different plans: any threads).  The device
  * entry points act on the calling thread's current HIP device; a plan stays with the device
  * of its first dmm_execute / dmm_reduce_replicas / dmm_broadcast_replica. */
@@ -126,8 +145,13 @@ typedef struct dmm_plan_s dmm_plan_t;
  * rank's local replica of C; dmm_execute gives every C replica its partial sum and then
  * adds the replicas up.  Host only: makes no HIP call.  `nranks` is p, the number of
  * virtual ranks.  `flags`: 0, DMM_STATIONARY_B or DMM_STATIONARY_A, each optionally with
- * DMM_ITERATION_OFFSET (anything else, or both stationary flags: DMM_EINVAL).  On success
- * *out owns the plan. */
+ * DMM_ITERATION_OFFSET and DMM_MERGE_ALWAYS (anything else, or both stationary flags:
+ * DMM_EINVAL).  On success *out owns the plan.
+ * A plan that holds a merged work list (dmm_plan_merged_items) keeps the slicing in factored
+ * form, as the three merged cut lists whose cells the ops are, and runs from that; its op list,
+ * grouped order and per-group macro-tiles are written out on first use (by the accessors below, or
+ * by dmm_execute when it is to run the per-group macro-tiles), not by dmm_plan.  If memory runs
+ * out then, the accessors return 0 / NULL and dmm_execute DMM_ENOMEM. */
 int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C,
              int32_t nranks, uint32_t flags, dmm_plan_t **out);
 
@@ -141,13 +165,21 @@ const int64_t *dmm_plan_group_offsets(const dmm_plan_t *p); /* num_groups + 1 of
 int64_t dmm_plan_num_items(const dmm_plan_t *p);
 const dmm_work_item *dmm_plan_items(const dmm_plan_t *p);   /* launch order (workgroup id -> item) */
 int32_t dmm_plan_macro_tile(const dmm_plan_t *p);           /* edge of the square macro-tile, elements */
+/* The alternative work list of merged macro-tiles, in launch order; 0 / NULL when the plan has
+ * none.  A plan has one when (a) it is a Stationary C plan in which all ranks of a C replica read
+ * the same replica of A and of B (the replication factor of C is a multiple of those of A and
+ * B), so that the ops of a replica are the cells of one grid, (b) no replica has an empty share
+ * of k, and (c) merging saves at least a tenth of the macro-tiles (tile grids much finer than the
+ * macro-tile: block-cyclic layouts).  dmm_execute then runs this list instead of dmm_plan_items. */
+int64_t dmm_plan_num_merged_items(const dmm_plan_t *p);
+const dmm_merged_item *dmm_plan_merged_items(const dmm_plan_t *p);
 
 /* Run the plan: C = A B (overwrite; C need not be initialised).
  *   dtype                 element type of every A and B tile
  *   a_tiles, b_tiles      host arrays of device pointers, one per (replica, tile) in table order
  *   c_tiles               host array of device pointers to fp32 tiles (bf16 tiles with DMM_C_BF16)
  *   a_ld, b_ld, c_ld      host arrays, leading dimension in elements, >= the tile's width
- *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING, DMM_C_BF16
+ *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING, DMM_C_BF16, DMM_NO_MERGE
  *   hip_stream            hipStream_t, may be null (default stream)
  * Pointers of empty tiles may be null.  Tile buffers are caller-owned and must
  * stay valid until the stream work completes.  Asynchronous: returns after
@@ -180,6 +212,11 @@ int dmm_reduce_replicas(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld
  * replicated.  HBM-bound: c * 4 bytes per element of C. */
 int dmm_broadcast_replica(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld, int32_t origin_replica,
                           void *hip_stream);
+
+/* 1 if the last dmm_execute on this plan ran the merged macro-tiles (the plan has such a list,
+ * DMM_NO_MERGE was not given and the device grants a workgroup the 160 KB of LDS their kernel
+ * asks for), else 0. */
+int dmm_plan_ran_merged(const dmm_plan_t *p);
 
 /* Device time of the two kernels of the last dmm_execute(..., DMM_TIMING, ...) on this
  * plan, in milliseconds, excluding the work-table upload.  Blocks until those kernels

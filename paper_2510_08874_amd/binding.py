@@ -19,9 +19,11 @@ DMM_BF16, DMM_F32 = 1, 2
 DMM_NO_REDUCE = 1
 DMM_TIMING = 2
 DMM_C_BF16 = 4
+DMM_NO_MERGE = 8
 DMM_STATIONARY_B = 1          # dmm_plan flags
 DMM_STATIONARY_A = 2
 DMM_ITERATION_OFFSET = 4
+DMM_MERGE_ALWAYS = 8
 STATIONARY_FLAGS = {"C": 0, "B": DMM_STATIONARY_B, "A": DMM_STATIONARY_A}
 STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EREPL", -4: "ENOMEM", -5: "EHIP", -6: "ELD"}
 
@@ -50,6 +52,12 @@ class dmm_work_item(C.Structure):
     _fields_ = [("group", C.c_int64), ("m0", C.c_int64), ("n0", C.c_int64),
                 ("m_ext", C.c_int32), ("n_ext", C.c_int32),
                 ("c_rep", C.c_int32), ("c_ti", C.c_int32), ("c_tj", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class dmm_merged_item(C.Structure):
+    _fields_ = [("m0", C.c_int64), ("n0", C.c_int64), ("m_ext", C.c_int32), ("n_ext", C.c_int32),
+                ("c_rep", C.c_int32), ("row_pieces", C.c_int32), ("col_pieces", C.c_int32),
                 ("reserved", C.c_int32)]
 
 
@@ -91,6 +99,12 @@ def lib() -> C.CDLL:
         L.dmm_plan_num_items.argtypes = [P]
         L.dmm_plan_items.restype = C.POINTER(dmm_work_item)
         L.dmm_plan_items.argtypes = [P]
+        L.dmm_plan_num_merged_items.restype = C.c_int64
+        L.dmm_plan_num_merged_items.argtypes = [P]
+        L.dmm_plan_merged_items.restype = C.POINTER(dmm_merged_item)
+        L.dmm_plan_merged_items.argtypes = [P]
+        L.dmm_plan_ran_merged.restype = C.c_int
+        L.dmm_plan_ran_merged.argtypes = [P]
         L.dmm_plan_macro_tile.restype = C.c_int32
         L.dmm_plan_macro_tile.argtypes = [P]
         L.dmm_execute.restype = C.c_int
@@ -115,6 +129,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
+           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged",
            "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
 
@@ -186,6 +201,17 @@ class Plan:
         p = lib().dmm_plan_items(self._h)
         return [{f: int(getattr(p[i], f)) for f, _ in dmm_work_item._fields_ if f != "reserved"}
                 for i in range(self.num_items())]
+
+    def num_merged_items(self) -> int:
+        return int(lib().dmm_plan_num_merged_items(self._h))
+
+    def merged_items(self) -> List[Dict]:
+        p = lib().dmm_plan_merged_items(self._h)
+        return [{f: int(getattr(p[i], f)) for f, _ in dmm_merged_item._fields_ if f != "reserved"}
+                for i in range(self.num_merged_items())]
+
+    def ran_merged(self) -> bool:
+        return bool(lib().dmm_plan_ran_merged(self._h))
 
     def macro_tile(self) -> int:
         return int(lib().dmm_plan_macro_tile(self._h))

@@ -236,6 +236,7 @@ struct DeviceState {
   bool last_use_recorded = false;
   hipEvent_t t_gemm[2] = {nullptr, nullptr}, t_red[2] = {nullptr, nullptr};  // DMM_TIMING
   bool gemm_timed = false, red_timed = false;
+  bool ran_merged = false;            // the last dmm_execute ran the merged macro-tiles
 };
 
 void destroy_device_state(DeviceState *d) {

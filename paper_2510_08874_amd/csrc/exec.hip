@@ -21,6 +21,14 @@ namespace dmm {
 
 namespace {
 
+static_assert(kMaxPieces == PMAX && kDescBytes == DESC_LDS - DESC_GEO && sizeof(PieceDev) == 24 &&
+                  kPieceAlign * 2 >= 16 && 2 * (PMAX + 1) * 4 <= DESC_GEO && kMacroTile == BM && kMacroTile == BN,
+              "the planner's limits for merged macro-tiles describe the kernel's descriptor area");
+
+// Whether the current device lets one workgroup have the stages plus the descriptor area (the
+// merged macro-tile kernels); decided in ensure_state.
+bool g_comp_ok[64] = {};
+
 int ensure_state(dmm_plan_t *P) {
   // the kernels' LDS size has to be allowed once per device
   static std::mutex mu;
@@ -35,6 +43,13 @@ int ensure_state(dmm_plan_t *P) {
                                   LDS_BYTES));
       DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   LDS_BYTES));
+      const bool ok =
+             hipFuncSetAttribute((const void *)grouped_gemm_comp_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 LDS_BYTES + DESC_LDS) == hipSuccess &&
+             hipFuncSetAttribute((const void *)grouped_gemm_comp_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 LDS_BYTES + DESC_LDS) == hipSuccess;
+      if (!ok) (void)hipGetLastError();
+      g_comp_ok[device] = ok;
       done[device] = true;
     }
   }
@@ -202,6 +217,120 @@ int fire_reduce(dmm_plan_t *P, const RedLaunch &L, hipStream_t stream, bool time
   return DMM_OK;
 }
 
+// Device tables of the merged macro-tiles, appended to *hp (empty on entry):
+//   CompItemDev[items] | PieceDev a[...] | PieceDev b[...] | PieceDev c[...] | int32 klen[...]
+// A slices are numbered (replica, row interval, segment), B slices (replica, segment, column
+// interval), C slices (replica, row interval, column interval).
+struct MergedLaunch {
+  size_t n_items = 0, o_a = 0, o_b = 0, o_c = 0, o_k = 0, total = 0;
+};
+
+int build_merged_tables(const dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, const void *const *a_tiles,
+                        const int64_t *a_ld, const void *const *b_tiles, const int64_t *b_ld, void *const *c_tiles,
+                        const int64_t *c_ld, std::vector<char> *hp, MergedLaunch *L) {
+  const Merged &G = P->merged;
+  const Grid &A = P->A, &B = P->B, &C = P->C;
+  const size_t MR = G.mc.size() - 1, NR = G.nc.size() - 1;
+  // tile that holds a cut point (the last tile whose lower cut is not above it: skips empty tiles)
+  auto holder = [](const std::vector<int64_t> &cuts, int64_t x) {
+    return (int32_t)(std::upper_bound(cuts.begin(), cuts.end() - 1, x) - cuts.begin()) - 1;
+  };
+  std::vector<int32_t> a_ti(MR), c_ti(MR), b_tj(NR), c_tj(NR);
+  for (size_t i = 0; i < MR; ++i) { a_ti[i] = holder(A.rc, G.mc[i]); c_ti[i] = holder(C.rc, G.mc[i]); }
+  for (size_t j = 0; j < NR; ++j) { b_tj[j] = holder(B.cc, G.nc[j]); c_tj[j] = holder(C.cc, G.nc[j]); }
+  std::vector<PieceDev> pa, pb, pc;
+  std::vector<int32_t> klen;
+  std::vector<int32_t> a0(G.reps.size()), b0(G.reps.size()), c0(G.reps.size()), k0(G.reps.size()), steps(G.reps.size());
+  auto piece = [](const void *base, int64_t ld, int64_t r, int64_t c, int64_t h, int64_t w, int64_t esz) {
+    PieceDev d;
+    const int64_t off = r * ld + c;
+    d.ptr = (const char *)base + off * esz;
+    d.room = ((h - 1) * ld + w - off) * esz;
+    d.pitch = (uint32_t)(ld * esz);
+    d.pad = 0;
+    return d;
+  };
+  for (size_t rep = 0; rep < G.reps.size(); ++rep) {
+    const MergedRep &R = G.reps[rep];
+    const size_t S = R.kc.size() - 1;
+    a0[rep] = (int32_t)pa.size();
+    b0[rep] = (int32_t)pb.size();
+    c0[rep] = (int32_t)pc.size();
+    k0[rep] = (int32_t)klen.size();
+    std::vector<int32_t> a_tj(S), b_ti(S);
+    int32_t nsteps = 0;
+    for (size_t s = 0; s < S; ++s) {
+      a_tj[s] = holder(A.cc, R.kc[s]);
+      b_ti[s] = holder(B.rc, R.kc[s]);
+      klen.push_back((int32_t)(R.kc[s + 1] - R.kc[s]));
+      nsteps += (int32_t)((R.kc[s + 1] - R.kc[s] + bk - 1) / bk);
+    }
+    steps[rep] = nsteps;
+    for (size_t i = 0; i < MR; ++i)
+      for (size_t s = 0; s < S; ++s) {
+        const int32_t ti = a_ti[i], tj = a_tj[s];
+        const int64_t idx = A.table_index(R.a_rep, ti, tj);
+        if (!a_tiles[idx]) return DMM_EINVAL;
+        pa.push_back(piece(a_tiles[idx], a_ld[idx], G.mc[i] - A.rc[ti], R.kc[s] - A.cc[tj], A.rc[ti + 1] - A.rc[ti],
+                           A.cc[tj + 1] - A.cc[tj], es));
+      }
+    for (size_t s = 0; s < S; ++s)
+      for (size_t j = 0; j < NR; ++j) {
+        const int32_t ti = b_ti[s], tj = b_tj[j];
+        const int64_t idx = B.table_index(R.b_rep, ti, tj);
+        if (!b_tiles[idx]) return DMM_EINVAL;
+        pb.push_back(piece(b_tiles[idx], b_ld[idx], R.kc[s] - B.rc[ti], G.nc[j] - B.cc[tj], B.rc[ti + 1] - B.rc[ti],
+                           B.cc[tj + 1] - B.cc[tj], es));
+      }
+    for (size_t i = 0; i < MR; ++i)
+      for (size_t j = 0; j < NR; ++j) {
+        const int32_t ti = c_ti[i], tj = c_tj[j];
+        const int64_t idx = C.table_index((int32_t)rep, ti, tj);
+        if (!c_tiles[idx]) return DMM_EINVAL;
+        pc.push_back(piece(c_tiles[idx], c_ld[idx], G.mc[i] - C.rc[ti], G.nc[j] - C.cc[tj], C.rc[ti + 1] - C.rc[ti],
+                           C.cc[tj + 1] - C.cc[tj], c_es));
+      }
+  }
+  std::vector<CompItemDev> items(G.items.size());
+  for (size_t x = 0; x < G.items.size(); ++x) {
+    const MergedItem &w = G.items[x];
+    const size_t S = G.reps[(size_t)w.rep].kc.size() - 1;
+    CompItemDev d;
+    std::memset(&d, 0, sizeof(d));
+    d.m_ext = w.m_ext;
+    d.n_ext = w.n_ext;
+    d.R = w.R;
+    d.Q = w.Q;
+    d.S = (int32_t)S;
+    d.nsteps = steps[(size_t)w.rep];
+    d.c_es = (int32_t)c_es;
+    d.a_first = a0[(size_t)w.rep] + w.mr0 * (int32_t)S;
+    d.a_stride = (int32_t)S;
+    d.b_first = b0[(size_t)w.rep] + w.nr0;
+    d.b_stride = (int32_t)NR;
+    d.c_first = c0[(size_t)w.rep] + w.mr0 * (int32_t)NR + w.nr0;
+    d.c_stride = (int32_t)NR;
+    d.k_first = k0[(size_t)w.rep];
+    for (int32_t p = 0; p <= w.R; ++p) d.rb[p] = (int32_t)(G.mc[(size_t)(w.mr0 + p)] - w.m0);
+    for (int32_t q = 0; q <= w.Q; ++q) d.cb[q] = (int32_t)(G.nc[(size_t)(w.nr0 + q)] - w.n0);
+    items[x] = d;
+  }
+  L->n_items = items.size();
+  L->o_a = items.size() * sizeof(CompItemDev);
+  L->o_b = L->o_a + pa.size() * sizeof(PieceDev);
+  L->o_c = L->o_b + pb.size() * sizeof(PieceDev);
+  L->o_k = L->o_c + pc.size() * sizeof(PieceDev);
+  L->total = (L->o_k + klen.size() * sizeof(int32_t) + 7) & ~(size_t)7;
+  std::vector<char> &h = *hp;
+  h.assign(L->total, 0);
+  std::memcpy(h.data(), items.data(), items.size() * sizeof(CompItemDev));
+  std::memcpy(h.data() + L->o_a, pa.data(), pa.size() * sizeof(PieceDev));
+  std::memcpy(h.data() + L->o_b, pb.data(), pb.size() * sizeof(PieceDev));
+  std::memcpy(h.data() + L->o_c, pc.data(), pc.size() * sizeof(PieceDev));
+  std::memcpy(h.data() + L->o_k, klen.data(), klen.size() * sizeof(int32_t));
+  return DMM_OK;
+}
+
 }  // namespace
 }  // namespace dmm
 
@@ -270,7 +399,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   using namespace dmm;
   if (!P || !a_tiles || !a_ld || !b_tiles || !b_ld || !c_tiles || !c_ld) return DMM_EINVAL;
   if (dtype != DMM_BF16 && dtype != DMM_F32) return DMM_EINVAL;
-  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING | DMM_C_BF16)) return DMM_EINVAL;
+  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING | DMM_C_BF16 | DMM_NO_MERGE)) return DMM_EINVAL;
   const bool timed = (flags & DMM_TIMING) != 0;
   // bf16 C tiles only where a tile receives a final sum: partial sums of a replicated C stay fp32
   if ((flags & DMM_C_BF16) && P->C.c != 1) return DMM_EINVAL;
@@ -291,6 +420,42 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   hipStream_t stream = (hipStream_t)hip_stream;
   try {
     if ((rc = ensure_state(P))) return rc;
+    int device = 0;
+    DMM_HIP(hipGetDevice(&device));
+    if (P->merged.valid && !(flags & DMM_NO_MERGE) && g_comp_ok[device]) {
+      // merged macro-tiles:  merged tables | replica-sum tables, one copy, then the launches
+      RedLaunch red;
+      MergedLaunch ml;
+      std::vector<char> &h = P->dev->host;
+      h.clear();
+      if ((rc = build_merged_tables(P, es, bk, c_es, a_tiles, a_ld, b_tiles, b_ld, c_tiles, c_ld, &h, &ml))) return rc;
+      if (!(flags & DMM_NO_REDUCE) && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, ml.total, &red))) return rc;
+      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
+      char *d = P->dev->gemm_table.dev();
+      red.dev_base = d;
+      if (timed) {
+        if ((rc = timing_events(P->dev->t_gemm))) return rc;
+        DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
+      }
+      if (dtype == DMM_BF16)
+        hipLaunchKernelGGL(grouped_gemm_comp_kernel<2>, dim3((unsigned)ml.n_items), dim3(NT), LDS_BYTES + DESC_LDS, stream,
+                           (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a), (const PieceDev *)(d + ml.o_b),
+                           (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
+      else
+        hipLaunchKernelGGL(grouped_gemm_comp_kernel<4>, dim3((unsigned)ml.n_items), dim3(NT), LDS_BYTES + DESC_LDS, stream,
+                           (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a), (const PieceDev *)(d + ml.o_b),
+                           (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
+      DMM_HIP(hipGetLastError());
+      if (timed) {
+        DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
+        P->dev->gemm_timed = true;
+      }
+      P->dev->ran_merged = true;
+      if ((rc = fire_reduce(P, red, stream, timed))) return rc;
+      return mark_use(P, stream);
+    }
+    P->dev->ran_merged = false;
+    if ((rc = materialize(P))) return rc;
     // The tables of all kernels go up in one copy in front of the GEMM launch, so that nothing
     // but the launches separates them:  ItemDev[] | SegDev[] | FixItem[] | replica-sum tables.
     RedLaunch red;
@@ -456,6 +621,8 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
     return DMM_ENOMEM;
   }
 }
+
+int dmm_plan_ran_merged(const dmm_plan_t *P) { return P && P->dev && P->dev->ran_merged ? 1 : 0; }
 
 int dmm_plan_elapsed_ms(dmm_plan_t *P, float *gemm_ms, float *reduce_ms) {
   using namespace dmm;

@@ -81,6 +81,43 @@ struct ItemDev {         // one macro-tile, or a run of K steps of one
   int32_t c_es;          // bytes per element of the destination: 4 = fp32, 2 = bf16 (rounded to nearest even)
 };
 
+// Merged macro-tiles.  Where the tiles of A, B and C are small against 256 x 256, a macro-tile may
+// cover several output sub-tiles at once: its rows fall into up to PMAX row pieces (rows of one
+// A tile and one C tile each), its columns into up to PMAX column pieces (one B tile, one C
+// tile), and every K-segment then names one A slice per row piece and one B slice per column
+// piece.  A lane's loads go to whichever piece holds its row or its 16-byte chunk of columns
+// (column pieces start at multiples of eight columns, so a chunk never straddles two B tiles).
+constexpr int PMAX = 8;
+
+struct PieceDev {        // one slice of a tile: where it starts, how far one may read, its row pitch
+  const char *ptr;
+  int64_t room;          // readable bytes from ptr to the end of the tile buffer
+  uint32_t pitch;        // bytes
+  uint32_t pad;
+};
+
+struct CompItemDev {     // one merged macro-tile
+  int32_t m_ext, n_ext;
+  int32_t R, Q, S;       // row pieces, column pieces, K-segments
+  int32_t nsteps;        // K steps over all segments
+  int32_t c_es;          // bytes per element of C
+  int32_t a_first, a_stride;   // A slice of (row piece p, segment s): a_pieces[a_first + p * a_stride + s]
+  int32_t b_first, b_stride;   // B slice of (segment s, column piece q): b_pieces[b_first + s * b_stride + q]
+  int32_t c_first, c_stride;   // C slice of (p, q): c_pieces[c_first + p * c_stride + q]
+  int32_t k_first;             // length of segment s: klen[k_first + s]
+  int32_t rb[PMAX + 1];        // first row of every row piece relative to the macro-tile (rb[0] <= 0: the
+                               // first piece may begin above it), rb[R] >= m_ext
+  int32_t cb[PMAX + 1];        // likewise for the column pieces
+};
+
+struct CompCtx {         // a merged macro-tile's descriptors, staged in LDS behind the stages
+  const int32_t *klen;   // [S]
+  const PieceDev *ad;    // [S][R]
+  const PieceDev *bd;    // [S][Q]
+  const int32_t *rb, *cb;
+  int R, Q;
+};
+
 constexpr int BM = 256, BN = 256;
 constexpr int A_ROW = 64;                     // bytes of an A row per K step
 constexpr int A_STAGE = BM * A_ROW;           // 16 KB
@@ -88,6 +125,8 @@ constexpr int B_STAGE = 16 * 1024;            // 32 x 512 B (bf16) or 16 x 1024 
 constexpr int STAGE = A_STAGE + B_STAGE;      // 32 KB
 constexpr int NSTAGE = 4;
 constexpr int LDS_BYTES = NSTAGE * STAGE;     // 128 KB
+constexpr int DESC_LDS = 32 * 1024;           // behind the stages: a merged macro-tile's descriptors
+constexpr int DESC_GEO = 128;                 // ... of which the piece boundaries take the first bytes
 constexpr int NW = 4;                         // waves per workgroup, 2 x 2
 constexpr int NT = 64 * NW;
 constexpr int WAVES_N = 2;
@@ -185,6 +224,23 @@ __device__ __forceinline__ void load_to_lds_16_masked(gptr base, unsigned lane_o
                : "memory", "scc");
 }
 
+// The same two forms with a full 64-bit address per lane (merged macro-tiles: the lanes of one
+// instruction read from different tile buffers).
+__device__ __forceinline__ void load_to_lds_16_v(gptr addr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(addr), "s"(lds_base)
+               : "memory");
+}
+template <int IMM>
+__device__ __forceinline__ void load_to_lds_16_masked_v(gptr addr, unsigned lds_base, unsigned lo, unsigned hi) {
+  asm volatile("s_add_u32 m0, %1, %2\n\ts_mov_b32 exec_lo, %3\n\ts_mov_b32 exec_hi, %4\n\t"
+               "global_load_lds_dwordx4 %0, off\n\ts_mov_b64 exec, -1"
+               :
+               : "v"(addr), "s"(lds_base), "n"(IMM), "s"(lo), "s"(hi)
+               : "memory", "scc");
+}
+
 // The first `n` (< 16 / ES) elements at p, the rest zero; n <= 0 reads nothing.
 template <int ES>
 __device__ __forceinline__ u32x4 load_partial(gptr p, int n) {
@@ -224,9 +280,9 @@ __device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
 
 // The work of one wave on one item.  ROT = this wave's index: it selects the MFMA slots
 // in which the wave issues its global->LDS loads (slot % 4 == ROT).
-template <int ES, int ROT>
+template <int ES, int ROT, bool COMP = false>
 __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__restrict__ segs, char *lds,
-                                         floatx16 (&acc)[FM][FN]) {
+                                         floatx16 (&acc)[FM][FN], const CompCtx &cx = CompCtx{}) {
   using S = Shape<ES>;
   constexpr int BK = S::BK;
   constexpr int PER = 16 / ES;                          // elements per 16-byte chunk
@@ -263,6 +319,68 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   }
   auto a_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(a_srow[i], pitch) + a_c16[i]; };
   auto b_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(b_srow[i], pitch) + b_c16[i]; };
+  // Merged macro-tiles: the piece that holds each of this lane's four A rows and four B chunks, the
+  // row inside that piece and the byte column inside that piece; then, per segment, a full address
+  // per load (ca, cbv), advanced by the load slot itself after every load, and the bytes one K
+  // step advances in B (the pitch of the lane's own B tile).
+  int ap[LOADS], bp[LOADS];
+  unsigned a_lrow[LOADS], b_lcol[LOADS];
+  gptr ca[LOADS], cbv[LOADS];
+  uint64_t bstep[LOADS];
+  if constexpr (COMP) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int crow = (int)a_srow[i];
+      int p = 0, base = cx.rb[0];
+#pragma unroll
+      for (int x = 1; x < PMAX; ++x)
+        if (x < cx.R && cx.rb[x] <= crow) { p = x; base = cx.rb[x]; }
+      ap[i] = p;
+      a_lrow[i] = (unsigned)(crow - base);
+      const int col = (int)(b_c16[i] >> 4) * PER;
+      int q = 0, cbase = cx.cb[0];
+#pragma unroll
+      for (int x = 1; x < PMAX; ++x)
+        if (x < cx.Q && cx.cb[x] <= col) { q = x; cbase = cx.cb[x]; }
+      bp[i] = q;
+      b_lcol[i] = (unsigned)(col - cbase) * ES;
+      ca[i] = cbv[i] = nullptr;
+      bstep[i] = 0;
+    }
+  }
+  auto seg_klen = [&](int seg) -> int {
+    if constexpr (COMP) return cx.klen[seg];
+    else return segs[it.seg_begin + seg].klen;
+  };
+  // address of, and readable bytes at, this lane's chunk of load i in the K step at (seg, kpos)
+  auto a_chunk = [&](int seg, int kpos, int i, gptr &p, int64_t &room) {
+    if constexpr (COMP) {
+      const PieceDev d = cx.ad[seg * cx.R + ap[i]];
+      const int64_t off = (int64_t)a_lrow[i] * d.pitch + a_c16[i] + (int64_t)kpos * ES;
+      p = (gptr)d.ptr + off;
+      room = d.room - off;
+    } else {
+      const SegDev sd = segs[it.seg_begin + seg];
+      const int64_t o0 = ((int64_t)it.m_off * sd.lda + kpos) * ES;
+      const unsigned off = a_offset((unsigned)(sd.lda * ES), i);
+      p = (gptr)sd.a + o0 + off;
+      room = sd.a_bytes - o0 - (int64_t)off;
+    }
+  };
+  auto b_chunk = [&](int seg, int kpos, int i, gptr &p, int64_t &room) {
+    if constexpr (COMP) {
+      const PieceDev d = cx.bd[seg * cx.Q + bp[i]];
+      const int64_t off = (int64_t)(kpos + (int)b_srow[i]) * d.pitch + b_lcol[i];
+      p = (gptr)d.ptr + off;
+      room = d.room - off;
+    } else {
+      const SegDev sd = segs[it.seg_begin + seg];
+      const int64_t o0 = ((int64_t)kpos * sd.ldb + it.n_off) * ES;
+      const unsigned off = b_offset((unsigned)(sd.ldb * ES), i);
+      p = (gptr)sd.b + o0 + off;
+      room = sd.b_bytes - o0 - (int64_t)off;
+    }
+  };
 
   // `lead` is the K step whose loads are being issued (three steps ahead of the one being
   // multiplied).  Whatever is done between two K steps is exposed (nothing hides it), so the loop
@@ -298,6 +416,29 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     b_need = ((int64_t)(BK - 1) * sd.ldb + (S::B_CHUNKS - 1) * PER) * ES + 16;
   };
   auto open_lead = [&](int kpos0) {                      // lead enters segment lead_seg at kpos0 (a multiple of BK)
+    if constexpr (COMP) {
+      const int klen = seg_klen(lead_seg);
+      lead_kpos = kpos0;
+      lead_left = (klen - kpos0 + BK - 1) / BK;
+      lead_tail = klen % BK != 0;
+      const int64_t more = lead_left - 1;                // the segment's last step reads furthest
+      bool overrun = false;
+#pragma unroll
+      for (int i = 0; i < LOADS; ++i) {
+        int64_t room;
+        a_chunk(lead_seg, kpos0, i, ca[i], room);
+        overrun |= room - more * (BK * ES) < 16;
+      }
+#pragma unroll
+      for (int i = 0; i < LOADS; ++i) {
+        int64_t room;
+        b_chunk(lead_seg, kpos0, i, cbv[i], room);
+        bstep[i] = (uint64_t)BK * cx.bd[lead_seg * cx.Q + bp[i]].pitch;
+        overrun |= room - more * (int64_t)bstep[i] < 16;
+      }
+      lead_seg_safe = __builtin_amdgcn_ballot_w64(overrun) == 0;
+      return;
+    }
     const SegDev sd = segs[it.seg_begin + lead_seg];
     lead_kpos = kpos0;
     lead_left = (sd.klen - kpos0 + BK - 1) / BK;
@@ -323,8 +464,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       open_lead(0);
     } else {
       lead_kpos += BK;
-      ld_a += BK * ES;
-      ld_b += ld_b_step;
+      if constexpr (!COMP) {                             // (a merged item's addresses advance in the load slots)
+        ld_a += BK * ES;
+        ld_b += ld_b_step;
+      }
     }
   };
   // Make the lead step ready for the load slots and push its repair flag.  An ordinary step is
@@ -338,6 +481,30 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       fix = lead_tail && lead_left == 1 ? 1u : 0u;
       all = ~0u;
       if (__builtin_expect(!lead_seg_safe, 0)) {
+        if constexpr (COMP) {
+          bool a_ok[LOADS], b_ok[LOADS], bad = false;
+#pragma unroll
+          for (int i = 0; i < LOADS; ++i) {
+            gptr p;
+            int64_t room;
+            a_chunk(lead_seg, lead_kpos, i, p, room);
+            a_ok[i] = room >= 16;
+            b_chunk(lead_seg, lead_kpos, i, p, room);
+            b_ok[i] = room >= 16;
+            bad |= !a_ok[i] || !b_ok[i];
+          }
+          if (__builtin_amdgcn_ballot_w64(bad) != 0) {
+            all = 0u;
+            fix = 1u;
+            const unsigned sa = lds_base + stage * STAGE + wave * 1024;
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i)
+              if (a_ok[i]) load_to_lds_16_v(ca[i], sa + i * (NW * 1024));
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i)
+              if (b_ok[i]) load_to_lds_16_v(cbv[i], sa + A_STAGE + i * (NW * 1024));
+          }
+        } else {
         const SegDev sd = segs[it.seg_begin + lead_seg];
         gptr pa, pb;
         int64_t a_left, b_left, a_need, b_need;
@@ -358,6 +525,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
             if ((int64_t)off + 16 <= b_left) load_to_lds_16(ld_b, off, sa + A_STAGE + i * (NW * 1024));
           }
         }
+        }
       }
     }
     fix_bits = (fix_bits << 1) | fix;
@@ -367,11 +535,21 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // whose base address (plus this wave's KB offset) is `stage_base`
   auto dma = [&](auto jc, unsigned stage_base) {
     constexpr int j = decltype(jc)::value;
-    if constexpr (j < LOADS)
-      load_to_lds_16_masked<j * (NW * 1024)>(ld_a, ld_a_off[j], stage_base, ld_lo, ld_hi);
-    else
-      load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, ld_b_off[j - LOADS], stage_base,
-                                                                 ld_lo, ld_hi);
+    if constexpr (COMP) {
+      if constexpr (j < LOADS) {
+        load_to_lds_16_masked_v<j * (NW * 1024)>(ca[j], stage_base, ld_lo, ld_hi);
+        ca[j] += BK * ES;
+      } else {
+        load_to_lds_16_masked_v<A_STAGE + (j - LOADS) * (NW * 1024)>(cbv[j - LOADS], stage_base, ld_lo, ld_hi);
+        cbv[j - LOADS] += bstep[j - LOADS];
+      }
+    } else {
+      if constexpr (j < LOADS)
+        load_to_lds_16_masked<j * (NW * 1024)>(ld_a, ld_a_off[j], stage_base, ld_lo, ld_hi);
+      else
+        load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, ld_b_off[j - LOADS], stage_base,
+                                                                   ld_lo, ld_hi);
+    }
   };
 
   // After this wave's loads of the step being published have landed: every lane repairs its own slots of
@@ -385,30 +563,27 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     int seg = 0, first = 0;
     const int t_abs = it.first_step + t;
     for (;;) {
-      const int cnt = (segs[it.seg_begin + seg].klen + BK - 1) / BK;
+      const int cnt = (seg_klen(seg) + BK - 1) / BK;
       if (t_abs < first + cnt) break;
       first += cnt;
       ++seg;
     }
-    const SegDev lsd = segs[it.seg_begin + seg];
     const int kpos = (t_abs - first) * BK;
-    gptr pa, pb;
-    int64_t a_left, b_left;
-    step_geometry(lsd, kpos, pa, pb, a_left, b_left);
-    const int krem = lsd.klen - kpos;
+    const int krem = seg_klen(seg) - kpos;
     char *sa = lds + stage * STAGE + wave * 1024 + lane * 16;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int row = (i * NW + wave) * 16 + a_slot_row;
       const int c = a_slot_pos ^ a_swizzle(row);
-      const unsigned off = a_offset((unsigned)(lsd.lda * ES), i);
+      gptr pc;
+      int64_t room;                                       // readable bytes at the chunk
+      a_chunk(seg, kpos, i, pc, room);
       int keep = krem - c * PER;                          // elements of the chunk inside the segment
       keep = keep > PER ? PER : keep;
       u32x4 *slot = (u32x4 *)(sa + i * (NW * 1024));
-      const int64_t room = a_left - (int64_t)off;         // readable bytes at the chunk
       if (room < 16) {
         const int avail = (int)(room > 0 ? room / ES : 0);
-        *slot = load_partial<ES>(pa + off, keep < avail ? keep : avail);
+        *slot = load_partial<ES>(pc, keep < avail ? keep : avail);
       } else if (keep <= 0) {
         *slot = u32x4{0u, 0u, 0u, 0u};
       } else if (keep < PER) {
@@ -418,13 +593,14 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int k = (i * NW + wave) * B_ROWS_PER_KB + b_slot_k;
-      const unsigned off = b_offset((unsigned)(lsd.ldb * ES), i);
+      gptr pc;
+      int64_t room;
+      b_chunk(seg, kpos, i, pc, room);
       u32x4 *slot = (u32x4 *)(sa + A_STAGE + i * (NW * 1024));
-      const int64_t room = b_left - (int64_t)off;
       if (k >= krem) {
         *slot = u32x4{0u, 0u, 0u, 0u};
       } else if (room < 16) {
-        *slot = load_partial<ES>(pb + off, (int)(room > 0 ? room / ES : 0));
+        *slot = load_partial<ES>(pc, (int)(room > 0 ? room / ES : 0));
       }
     }
   };
@@ -503,7 +679,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       constexpr int r = n - (n + NW - 1 - ROT) / NW;    // LDS reads issued in earlier slots of this sub-step
       mfma_op(cur, n);
       constexpr int g = first + n;
-      if constexpr (g == NW + ((ROT + 1) % NW)) {          // a slot without a load: addresses of the next step
+      if constexpr (!COMP && g == NW + ((ROT + 1) % NW)) {   // a slot without a load: addresses of the next step
         ld_a_next = ld_a + BK * ES;
         ld_b_next = ld_b + ld_b_step;
       }
@@ -536,7 +712,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     // the item's first step: segment and position (first_step lies inside the group's sequence)
     int first = 0;
     for (;;) {
-      const int cnt = (segs[it.seg_begin + lead_seg].klen + BK - 1) / BK;
+      const int cnt = (seg_klen(lead_seg) + BK - 1) / BK;
       if (it.first_step < first + cnt) break;
       first += cnt;
       ++lead_seg;
@@ -615,8 +791,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       ++s;
       if (quiet == 0) break;
       --quiet;
-      ld_a = ld_a_next;
-      ld_b = ld_b_next;
+      if constexpr (!COMP) {
+        ld_a = ld_a_next;
+        ld_b = ld_b_next;
+      }
     }
     if (s >= n) break;
     loads_on = s - 1 + NSTAGE < n;           // step s + 3 exists (s is the coming iteration)
@@ -695,6 +873,125 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
   };
   if (it.m_ext == BM && it.n_ext == BN) store_all(std::true_type{});
   else store_all(std::false_type{});
+}
+
+// The same multiplication for merged macro-tiles.  The item's descriptors (segment lengths, one A
+// slice per row piece and segment, one B slice per segment and column piece) are first copied
+// into LDS behind the stages, where a segment switch reads them without touching the counter
+// that tracks the loads in flight.  The epilogue writes through a table of row addresses (one
+// per row and column piece, built in the stage area once the K loop is done), since the rows
+// and columns of the macro-tile end up in different C tiles.
+template <int ES>
+__global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev *__restrict__ items,
+                                                               const PieceDev *__restrict__ a_pieces,
+                                                               const PieceDev *__restrict__ b_pieces,
+                                                               const PieceDev *__restrict__ c_pieces,
+                                                               const int32_t *__restrict__ klen) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const CompItemDev *ci = items + blockIdx.x;
+  const int R = ci->R, Q = ci->Q, S = ci->S;
+  const int m_ext = ci->m_ext, n_ext = ci->n_ext;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  int32_t *geo = (int32_t *)(lds + LDS_BYTES);            // piece boundaries, where lanes can index them
+  int32_t *klen_s = geo + DESC_GEO / 4;
+  PieceDev *ad = (PieceDev *)(klen_s + ((S + 3) & ~3));
+  PieceDev *bd = ad + S * R;
+  for (int x = threadIdx.x; x < S; x += NT) klen_s[x] = klen[ci->k_first + x];
+  for (int x = threadIdx.x; x < S * R; x += NT) ad[x] = a_pieces[ci->a_first + (x % R) * ci->a_stride + x / R];
+  for (int x = threadIdx.x; x < S * Q; x += NT) bd[x] = b_pieces[ci->b_first + (x / Q) * ci->b_stride + x % Q];
+  if (threadIdx.x <= PMAX) {
+    geo[threadIdx.x] = ci->rb[threadIdx.x];
+    geo[PMAX + 1 + threadIdx.x] = ci->cb[threadIdx.x];
+  }
+  __syncthreads();
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  if (ci->nsteps > 0) {
+    ItemDev it;
+    it.c = nullptr;
+    it.ldc = 0;
+    it.seg_begin = 0;
+    it.nsteps = ci->nsteps;
+    it.m_off = it.n_off = 0;
+    it.m_ext = m_ext;
+    it.n_ext = n_ext;
+    it.first_step = 0;
+    it.c_es = ci->c_es;
+    CompCtx cx;
+    cx.klen = klen_s;
+    cx.ad = ad;
+    cx.bd = bd;
+    cx.rb = geo;
+    cx.cb = geo + PMAX + 1;
+    cx.R = R;
+    cx.Q = Q;
+    if (wave == 0) run_item<ES, 0, true>(it, nullptr, lds, acc, cx);
+    else if (wave == 1) run_item<ES, 1, true>(it, nullptr, lds, acc, cx);
+    else if (wave == 2) run_item<ES, 2, true>(it, nullptr, lds, acc, cx);
+    else run_item<ES, 3, true>(it, nullptr, lds, acc, cx);
+  }
+
+  // ---- epilogue ------------------------------------------------------------------------------
+  __syncthreads();                                        // every wave is out of the K loop: the stages are free
+  uint64_t *rowbase = (uint64_t *)lds;                    // [256][PMAX]: address of (row, first column of piece q)
+  {
+    const int row = threadIdx.x;
+    if (row < m_ext) {
+      int p = 0, base = geo[0];
+      for (int x = 1; x < R; ++x)
+        if (geo[x] <= row) { p = x; base = geo[x]; }
+      for (int q = 0; q < Q; ++q) {
+        const PieceDev d = c_pieces[ci->c_first + p * ci->c_stride + q];
+        rowbase[row * PMAX + q] = (uint64_t)(uintptr_t)d.ptr + (uint64_t)(row - base) * d.pitch;
+      }
+    }
+  }
+  __syncthreads();
+  const int ces = ci->c_es;
+  const bool wide = ces == 4;
+  const int row0 = wm * WTM + 4 * (lane >> 5);
+  const int col0 = wn * WTN + (lane & 31);
+  int qj[FN];
+  unsigned lcol[FN];                                      // byte column inside the piece
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int col = col0 + j * 32;
+    int q = 0, base = geo[PMAX + 1];
+    for (int x = 1; x < Q; ++x)
+      if (geo[PMAX + 1 + x] <= col) { q = x; base = geo[PMAX + 1 + x]; }
+    qj[j] = q;
+    lcol[j] = (unsigned)(col - base) * (unsigned)ces;
+  }
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
+      if (row < m_ext) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          if (col0 + j * 32 < n_ext) {
+            const uint64_t a = rowbase[row * PMAX + qj[j]] + lcol[j];
+            if (wide) {
+              __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(uintptr_t)a);
+            } else {
+              float v;
+              asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
+              __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)v), (gushort_ptr)(uintptr_t)a);
+            }
+          }
+      }
+    }
 }
 
 }  // namespace dmm

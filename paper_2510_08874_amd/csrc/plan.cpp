@@ -418,6 +418,41 @@ void tile_region(int64_t group, int64_t m0, int64_t m1, int64_t n0, int64_t n1, 
         }
 }
 
+// Launch slot i goes to XCD i % 8.  Two ways of dealing a sequence of macro-tiles (whose every run
+// of 32 is a compact block) to the 8 XCDs:
+//  - round-robin in blocks of 32 (the CUs of one XCD): at any time the 8 XCDs work on 8
+//    consecutive blocks, i.e. on neighbouring bands of the same column strip of one output
+//    region, which read the same B column panels (and the same replica of A) at about the same
+//    time, so that what one XCD pulled into the last-level cache serves the other seven;
+//  - 8 contiguous runs: each XCD on a region of its own.
+// The first wins where strips hold several bands (against the second: cfg3 +6 %, cfg5 +10 %,
+// column-block MLP-2 +24 %, cfg4 the same); where every strip is a single band, consecutive
+// blocks share no B panel and streaming separate regions is the better of the two (inner-
+// product MLP-1: +5 %).
+template <typename Item>
+void deal_to_xcds(const std::vector<Item> &seq, bool round_robin, std::vector<Item> *out) {
+  const int64_t n = (int64_t)seq.size(), X = 8, BLK = 32;
+  out->clear();
+  out->reserve((size_t)n);
+  if (round_robin) {
+    const int64_t nblk = (n + BLK - 1) / BLK;
+    for (int64_t b0 = 0; b0 < nblk; b0 += X)
+      for (int64_t j = 0; j < BLK; ++j)
+        for (int64_t x = 0; x < X; ++x) {
+          const int64_t idx = (b0 + x) * BLK + j;
+          if (idx < n) out->push_back(seq[(size_t)idx]);
+        }
+  } else {
+    int64_t longest = 0;
+    for (int64_t x = 0; x < X; ++x) longest = std::max(longest, (x + 1) * n / X - x * n / X);
+    for (int64_t j = 0; j < longest; ++j)
+      for (int64_t x = 0; x < X; ++x) {
+        const int64_t b0 = x * n / X, e = (x + 1) * n / X;
+        if (b0 + j < e) out->push_back(seq[(size_t)(b0 + j)]);
+      }
+  }
+}
+
 void build_items(dmm_plan_t *P) {
   std::vector<dmm_work_item> seq;
   for (size_t g = 0; g < P->groups.size(); ++g) {
@@ -469,18 +504,6 @@ void build_items(dmm_plan_t *P) {
             j = e;
           }
       }
-  // Launch slot i goes to XCD i % 8.  Two ways of dealing the sequence to the 8 XCDs:
-  //  - round-robin in blocks of 32 (the CUs of one XCD): at any time the 8 XCDs work on 8
-  //    consecutive blocks, i.e. on neighbouring bands of the same column strip of one output
-  //    region, which read the same B column panels (and the same replica of A) at about the same
-  //    time, so that what one XCD pulled into the last-level cache serves the other seven;
-  //  - 8 contiguous runs: each XCD on a region of its own.
-  // The first wins where strips hold several bands (against the second: cfg3 +6 %, cfg5 +10 %,
-  // column-block MLP-2 +24 %, cfg4 the same); where every strip is a single band, consecutive
-  // blocks share no B panel and streaming separate regions is the better of the two (inner-
-  // product MLP-1: +5 %).  So: round-robin if at least half of the blocks are followed by a
-  // block of the same strip.
-  const int64_t n = (int64_t)seq.size(), X = 8, BLK = 32;
   int64_t blocks = 0, followed = 0;
   for (const Group &G : P->groups) {
     const int64_t T = kMacroTile;
@@ -488,36 +511,147 @@ void build_items(dmm_plan_t *P) {
     blocks += bands * strips;
     followed += (bands - 1) * strips;
   }
-  P->items.clear();
-  P->items.reserve(n);
-  if (2 * followed >= blocks) {
-    const int64_t nblk = (n + BLK - 1) / BLK;
-    for (int64_t b0 = 0; b0 < nblk; b0 += X)
-      for (int64_t j = 0; j < BLK; ++j)
-        for (int64_t x = 0; x < X; ++x) {
-          const int64_t idx = (b0 + x) * BLK + j;
-          if (idx < n) P->items.push_back(seq[idx]);
-        }
-  } else {
-    int64_t longest = 0;
-    for (int64_t x = 0; x < X; ++x) longest = std::max(longest, (x + 1) * n / X - x * n / X);
-    for (int64_t j = 0; j < longest; ++j)
-      for (int64_t x = 0; x < X; ++x) {
-        const int64_t b0 = x * n / X, e = (x + 1) * n / X;
-        if (b0 + j < e) P->items.push_back(seq[b0 + j]);
+  deal_to_xcds(seq, 2 * followed >= blocks, &P->items);
+}
+
+// One axis of a C replica cut into macro-tile extents: 256 at a time, across the cuts; a tile
+// ends early where it would meet more than `cap` intervals, or at a cut that is not a multiple
+// of `align` away from the tile's start.
+struct Extent {
+  int64_t start;
+  int32_t ext, first, pieces;         // first interval met, number of intervals met
+};
+
+std::vector<Extent> tile_axis(const std::vector<int64_t> &cuts, int32_t cap, int64_t align) {
+  std::vector<Extent> out;
+  const int64_t L = cuts.back();
+  int64_t pos = 0;
+  size_t iv = 0;
+  while (pos < L) {
+    while (cuts[iv + 1] <= pos) ++iv;
+    int64_t end = std::min<int64_t>(pos + kMacroTile, L);
+    int32_t pieces = 1;
+    for (size_t j = iv; cuts[j + 1] < end; ++j) {
+      const int64_t c = cuts[j + 1];
+      if (pieces == cap || (c - pos) % align != 0) {
+        end = c;
+        break;
       }
+      ++pieces;
+    }
+    out.push_back({pos, (int32_t)(end - pos), (int32_t)iv, pieces});
+    pos = end;
   }
+  return out;
+}
+
+void build_merged(dmm_plan_t *P, uint32_t flags) {
+  Merged &G = P->merged;
+  G = Merged();
+  const Grid &A = P->A, &B = P->B, &C = P->C;
+  if (flags & (DMM_STATIONARY_B | DMM_STATIONARY_A)) return;
+  // every rank of a C replica has to read the same replica of A and of B
+  if (C.c % A.c != 0 || C.c % B.c != 0) return;
+  const int64_t M = A.rows, K = A.cols, N = B.cols, lim = (int64_t)1 << 31;
+  if (M <= 0 || K <= 0 || N <= 0 || M >= lim || K >= lim || N >= lim) return;
+  G.mc = merged_cuts({&A.rc, &C.rc});
+  G.nc = merged_cuts({&B.cc, &C.cc});
+  const std::vector<int64_t> kall = merged_cuts({&A.cc, &B.rc});
+  int64_t cap = kMaxPieces;
+  for (int32_t rep = 0; rep < C.c; ++rep) {
+    const int64_t lo = (int64_t)rep * K / C.c, hi = ((int64_t)rep + 1) * K / C.c;
+    if (lo >= hi) return;             // an empty share: that replica is zero-filled, not multiplied
+    MergedRep R;
+    R.kc.push_back(lo);
+    for (int64_t c : kall)
+      if (c > lo && c < hi) R.kc.push_back(c);
+    R.kc.push_back(hi);
+    R.a_rep = rep / (C.c / A.c);
+    R.b_rep = rep / (C.c / B.c);
+    const int64_t S = (int64_t)R.kc.size() - 1;
+    cap = std::min(cap, (kDescBytes - 4 * ((S + 3) & ~(int64_t)3)) / (48 * S));
+    G.reps.push_back(std::move(R));
+  }
+  if (cap < 1) return;
+  const std::vector<Extent> rows = tile_axis(G.mc, (int32_t)cap, 1), cols = tile_axis(G.nc, (int32_t)cap, kPieceAlign);
+  // worth it only if it saves a tenth of the macro-tiles
+  const int64_t merged_count = (int64_t)C.c * (int64_t)rows.size() * (int64_t)cols.size();
+  if (!(flags & DMM_MERGE_ALWAYS)) {
+    // (macro-tiles of the other list: every cell of the refinement grid tiled on its own)
+    int64_t tr = 0, tc = 0;
+    for (size_t i = 0; i + 1 < G.mc.size(); ++i) tr += (G.mc[i + 1] - G.mc[i] + kMacroTile - 1) / kMacroTile;
+    for (size_t j = 0; j + 1 < G.nc.size(); ++j) tc += (G.nc[j + 1] - G.nc[j] + kMacroTile - 1) / kMacroTile;
+    if (merged_count * 10 > (int64_t)C.c * tr * tc * 9) return;
+  }
+  std::vector<MergedItem> seq;
+  seq.reserve((size_t)merged_count);
+  const int64_t tm = (int64_t)rows.size(), tn = (int64_t)cols.size(), strip = 8, band = 4;
+  for (int32_t rep = 0; rep < C.c; ++rep)
+    for (int64_t s = 0; s < tn; s += strip)
+      for (int64_t r0 = 0; r0 < tm; r0 += band)
+        for (int64_t r = r0; r < std::min(tm, r0 + band); ++r)
+          for (int64_t c = s; c < std::min(tn, s + strip); ++c) {
+            const Extent &er = rows[(size_t)r], &ec = cols[(size_t)c];
+            seq.push_back({er.start, ec.start, er.ext, ec.ext, rep, er.first, er.pieces, ec.first, ec.pieces});
+          }
+  deal_to_xcds(seq, tm > band, &G.items);
+  G.view.reserve(G.items.size());
+  for (const MergedItem &w : G.items) G.view.push_back({w.m0, w.n0, w.m_ext, w.n_ext, w.rep, w.R, w.Q, 0});
+  G.valid = true;
 }
 
 }  // namespace
+
+int materialize(dmm_plan_t *P) {
+  if (P->listed) return DMM_OK;
+  const uint32_t flags = P->flags;
+  try {
+    P->tasks.clear();
+    {
+      // room for the op list up front: the boxes are cells of the merged cut grids (at most one
+      // more k interval per replica share), so their number is known to within that
+      const size_t mi = merged_cuts({&P->A.rc, &P->C.rc}).size(), ni = merged_cuts({&P->B.cc, &P->C.cc}).size();
+      const size_t ki = merged_cuts({&P->A.cc, &P->B.rc}).size() + (size_t)P->C.c;
+      const double est = (double)mi * (double)ni * (double)ki;
+      if (est < 5.0e7) P->tasks.reserve((size_t)est);
+    }
+    for (int32_t rank = 0; rank < P->nranks; ++rank) {
+      const size_t first = P->tasks.size();
+      if (flags & DMM_STATIONARY_B) generate_rank_b(*P, rank, &P->tasks);
+      else if (flags & DMM_STATIONARY_A) generate_rank_a(*P, rank, &P->tasks);
+      else generate_rank(*P, rank, &P->tasks);
+      if (flags & DMM_ITERATION_OFFSET) apply_iteration_offset(&P->tasks, first, flags);
+    }
+    group_tasks(P, flags);
+    build_items(P);
+  } catch (const std::bad_alloc &) {
+    P->tasks.clear();
+    P->order.clear();
+    P->group_offsets.clear();
+    P->groups.clear();
+    P->items.clear();
+    return DMM_ENOMEM;
+  }
+  P->listed = true;
+  return DMM_OK;
+}
+
 }  // namespace dmm
+
+namespace {
+// the plan with its op list written out, or null
+const dmm_plan_t *listed(const dmm_plan_t *p) {
+  if (!p) return nullptr;
+  return dmm::materialize(const_cast<dmm_plan_t *>(p)) == DMM_OK ? p : nullptr;
+}
+}  // namespace
 
 extern "C" {
 
 int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matrix_desc *C, int32_t nranks,
              uint32_t flags, dmm_plan_t **out) {
   if (!A || !B || !C || !out || nranks < 1) return DMM_EINVAL;
-  if (flags & ~(DMM_STATIONARY_B | DMM_STATIONARY_A | DMM_ITERATION_OFFSET)) return DMM_EINVAL;
+  if (flags & ~(DMM_STATIONARY_B | DMM_STATIONARY_A | DMM_ITERATION_OFFSET | DMM_MERGE_ALWAYS)) return DMM_EINVAL;
   if ((flags & DMM_STATIONARY_B) && (flags & DMM_STATIONARY_A)) return DMM_EINVAL;
   dmm_plan_t *P = new (std::nothrow) dmm_plan_t;
   if (!P) return DMM_ENOMEM;
@@ -533,23 +667,14 @@ int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matri
       delete P;
       return DMM_ESHAPE;
     }
-    {
-      // room for the op list up front: the boxes are cells of the merged cut grids (at most one
-      // more k interval per replica share), so their number is known to within that
-      const size_t mi = dmm::merged_cuts({&P->A.rc, &P->C.rc}).size(), ni = dmm::merged_cuts({&P->B.cc, &P->C.cc}).size();
-      const size_t ki = dmm::merged_cuts({&P->A.cc, &P->B.rc}).size() + (size_t)P->C.c;
-      const double est = (double)mi * (double)ni * (double)ki;
-      if (est < 5.0e7) P->tasks.reserve((size_t)est);
+    P->flags = flags;
+    dmm::build_merged(P, flags);
+    // With a merged work list the op list is not needed to run the plan: it is written out when
+    // somebody asks for it (an accessor, or dmm_execute when it has to run the other list).
+    if (!P->merged.valid && (rc = dmm::materialize(P))) {
+      delete P;
+      return rc;
     }
-    for (int32_t rank = 0; rank < nranks; ++rank) {
-      const size_t first = P->tasks.size();
-      if (flags & DMM_STATIONARY_B) dmm::generate_rank_b(*P, rank, &P->tasks);
-      else if (flags & DMM_STATIONARY_A) dmm::generate_rank_a(*P, rank, &P->tasks);
-      else dmm::generate_rank(*P, rank, &P->tasks);
-      if (flags & DMM_ITERATION_OFFSET) dmm::apply_iteration_offset(&P->tasks, first, flags);
-    }
-    dmm::group_tasks(P, flags);
-    dmm::build_items(P);
   } catch (const std::bad_alloc &) {
     delete P;
     return DMM_ENOMEM;
@@ -558,14 +683,18 @@ int dmm_plan(const dmm_matrix_desc *A, const dmm_matrix_desc *B, const dmm_matri
   return DMM_OK;
 }
 
-int64_t dmm_plan_num_tasks(const dmm_plan_t *p) { return p ? (int64_t)p->tasks.size() : 0; }
-const dmm_task *dmm_plan_tasks(const dmm_plan_t *p) { return p ? p->tasks.data() : nullptr; }
-const int64_t *dmm_plan_order(const dmm_plan_t *p) { return p ? p->order.data() : nullptr; }
-int64_t dmm_plan_num_groups(const dmm_plan_t *p) { return p ? (int64_t)p->groups.size() : 0; }
-const int64_t *dmm_plan_group_offsets(const dmm_plan_t *p) { return p ? p->group_offsets.data() : nullptr; }
-int64_t dmm_plan_num_items(const dmm_plan_t *p) { return p ? (int64_t)p->items.size() : 0; }
-const dmm_work_item *dmm_plan_items(const dmm_plan_t *p) { return p ? p->items.data() : nullptr; }
+int64_t dmm_plan_num_tasks(const dmm_plan_t *p) { return (p = listed(p)) ? (int64_t)p->tasks.size() : 0; }
+const dmm_task *dmm_plan_tasks(const dmm_plan_t *p) { return (p = listed(p)) ? p->tasks.data() : nullptr; }
+const int64_t *dmm_plan_order(const dmm_plan_t *p) { return (p = listed(p)) ? p->order.data() : nullptr; }
+int64_t dmm_plan_num_groups(const dmm_plan_t *p) { return (p = listed(p)) ? (int64_t)p->groups.size() : 0; }
+const int64_t *dmm_plan_group_offsets(const dmm_plan_t *p) { return (p = listed(p)) ? p->group_offsets.data() : nullptr; }
+int64_t dmm_plan_num_items(const dmm_plan_t *p) { return (p = listed(p)) ? (int64_t)p->items.size() : 0; }
+const dmm_work_item *dmm_plan_items(const dmm_plan_t *p) { return (p = listed(p)) ? p->items.data() : nullptr; }
 int32_t dmm_plan_macro_tile(const dmm_plan_t *) { return dmm::kMacroTile; }
+int64_t dmm_plan_num_merged_items(const dmm_plan_t *p) { return p && p->merged.valid ? (int64_t)p->merged.view.size() : 0; }
+const dmm_merged_item *dmm_plan_merged_items(const dmm_plan_t *p) {
+  return p && p->merged.valid ? p->merged.view.data() : nullptr;
+}
 
 void dmm_plan_destroy(dmm_plan_t *p) {
   if (!p) return;

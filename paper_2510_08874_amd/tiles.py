@@ -107,7 +107,8 @@ class DeviceProblem:
         tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
         self.plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"],
                                  binding.STATIONARY_FLAGS[cfg.get("stationary", "C")] |
-                                 (binding.DMM_ITERATION_OFFSET if cfg.get("iteration_offset") else 0))
+                                 (binding.DMM_ITERATION_OFFSET if cfg.get("iteration_offset") else 0) |
+                                 (binding.DMM_MERGE_ALWAYS if cfg.get("merge_always") else 0))
         self.A = TileSet(cfg["A"], tdt, device, ld_multiple)
         self.B = TileSet(cfg["B"], tdt, device, ld_multiple)
         # C tiles are fp32, or bf16 when asked for (DMM_C_BF16 then goes with every execute)

@@ -542,6 +542,74 @@ def test_bf16_c_tiles_need_an_unreplicated_c():
     prob.close()
 
 
+# ---- merged macro-tiles: tile grids much finer than 256 x 256 ---------------------------------
+
+def _bc(dims, nb, dtype, reps=(1, 1, 1), p=8):
+    M, K, N = dims
+    pr, pc = 2, 4
+    return dict(name=f"bc{nb}/{dtype}/{reps}@{M}x{K}x{N}", M=M, K=K, N=N, dtype=dtype, nranks=p,
+                A=workloads.block_cyclic_desc(M, K, nb, nb, pr, pc, reps[0]),
+                B=workloads.block_cyclic_desc(K, N, nb, nb, pr, pc, reps[1]),
+                C=workloads.block_cyclic_desc(M, N, nb, nb, pr, pc, reps[2]),
+                dist=("normal", 1.0), seeds=(71, 72))
+
+
+@pytest.mark.parametrize("dims,nb,dtype,ldm,reps,p", [
+    ((1536, 1024, 1280), 128, "bf16", 1, (1, 1, 1), 8),    # 2 x 2 tiles per macro-tile, everything aligned
+    ((700, 333, 517), 96, "bf16", 1, (1, 1, 1), 8),        # macro-tiles start inside tiles; odd leading dimensions; K tails
+    ((700, 333, 517), 96, "f32", 1, (1, 1, 1), 8),
+    ((520, 200, 530), 40, "bf16", 8, (1, 1, 1), 8),        # seven pieces per axis
+    ((300, 4100, 300), 24, "bf16", 1, (1, 1, 1), 8),       # 171 segments: the descriptor area caps a macro-tile at 3 x 3 pieces
+    ((640, 900, 512), 64, "bf16", 1, (2, 2, 2), 16),       # replicated: every replica its share of k, then the replica sum
+    ((640, 900, 512), 64, "f32", 4, (1, 2, 4), 32),        # C replicas read different replicas of B, all the one A
+    ((515, 130, 260), 100, "bf16", 1, (1, 1, 1), 8),       # cuts at 100, 200: column pieces not at multiples of 8: tiles end there
+])
+def test_merged_macro_tiles(dims, nb, dtype, ldm, reps, p):
+    """Where the tiles are small against the macro-tile the library runs macro-tiles that span
+    several tiles of A, B and C.  Parity with the oracle as everywhere, and bitwise the same C as
+    the one-macro-tile-per-output-sub-tile path (same K-segments, same order of summation)."""
+    from paper_2510_08874_amd import binding
+    cfg = _bc(dims, nb, dtype, reps, p)
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
+    assert prob.plan.num_merged_items() > 0
+    prob.execute()
+    assert prob.plan.ran_merged()
+    got = prob.c_global(0)
+    A64, B64 = _to_f64(A, cfg), _to_f64(B, cfg)
+    C_ref = omatmul.matmul(A, B, bf16=(dtype == "bf16"))
+    _check(got, C_ref, A64, B64, cfg, cfg["name"])
+    parts = [prob.c_global(r) for r in range(1, reps[2])]
+    for t, ld, (ti, tj) in zip(prob.C.tensors, prob.C.ld, [(i, j) for i in range(prob.C.gr) for j in range(prob.C.gc)]):
+        r0, r1, c0, c1 = prob.C.bounds(ti, tj)
+        if t is not None and ld > c1 - c0:
+            assert torch.isnan(t[:, c1 - c0:]).all(), "padding of a C tile was written"
+    prob.close()
+    plain = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
+    plain.execute(flags=binding.DMM_NO_MERGE)
+    assert not plain.plan.ran_merged()
+    assert np.array_equal(got, plain.c_global(0))
+    for r in range(1, reps[2]):
+        assert np.array_equal(parts[r - 1], plain.c_global(r))
+    plain.close()
+
+
+def test_merged_macro_tiles_bf16_c_and_rerun():
+    from paper_2510_08874_amd import binding
+    cfg = _bc((700, 333, 517), 96, "bf16")
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"), c_dtype="bf16")
+    assert prob.plan.num_merged_items() > 0
+    prob.execute()
+    got = prob.c_global(0)
+    _check_bf16_out(got, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg["name"])
+    prob.execute()
+    assert np.array_equal(got, prob.c_global(0))
+    prob.execute(flags=binding.DMM_NO_MERGE)
+    assert np.array_equal(got, prob.c_global(0))
+    prob.close()
+
+
 # ---- error paths that reach the device entry points ---------------------------------
 
 def test_execute_rejects_bad_arguments():

@@ -102,7 +102,7 @@ def test_iteration_offset_bit_exact(seed, mode):
 
 def test_stationary_flags_exclusive():
     ok = dict(rows=8, cols=8, row_cuts=(0, 8), col_cuts=(0, 8), proc_rows=1, proc_cols=1, replication=1)
-    for flags in (3, 7, 8, 16):
+    for flags in (3, 7, 11, 16, 32):
         with pytest.raises(binding.DmmError) as e:
             binding.Plan(ok, ok, ok, 1, flags)
         assert e.value.kind == "EINVAL"
@@ -241,4 +241,60 @@ def test_grouping_falls_back_when_output_sub_tiles_outnumber_ops():
     assert plan.tasks() == [tuple(t) for t in want]
     order, offsets = oplanner.reorder(want)
     assert plan.order() == order and plan.group_offsets() == offsets
+    plan.destroy()
+
+
+# ---- merged macro-tiles ----------------------------------------------------------------------
+
+def _check_merged(plan, prob):
+    """What has to hold for the alternative work list, from the descriptors alone."""
+    A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
+    items = plan.merged_items()
+    T = plan.macro_tile()
+    assert len(items) * 10 <= plan.num_items() * 9, "merged list kept although it saves less than a tenth"
+    mc = sorted(set(A.row_cuts) | set(C.row_cuts))
+    nc = sorted(set(B.col_cuts) | set(C.col_cuts))
+    hit = np.zeros((C.replication, A.rows, B.cols), dtype=np.int32)
+    for it in items:
+        assert 1 <= it["m_ext"] <= T and 1 <= it["n_ext"] <= T
+        m0, m1, n0, n1 = it["m0"], it["m0"] + it["m_ext"], it["n0"], it["n0"] + it["n_ext"]
+        hit[it["c_rep"], m0:m1, n0:n1] += 1
+        inner_m = [c for c in mc if m0 < c < m1]
+        inner_n = [c for c in nc if n0 < c < n1]
+        assert it["row_pieces"] == len(inner_m) + 1 <= 8 and it["col_pieces"] == len(inner_n) + 1 <= 8
+        assert all((c - n0) % 8 == 0 for c in inner_n), "a column piece starts inside a 16-byte chunk"
+    assert (hit == 1).all(), "merged macro-tiles do not tile every C replica exactly once"
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_merged_items_tile_every_replica_of_c_once(seed):
+    prob = helpers.random_problem(seed + 7000, max_dim=600, allow_empty=(seed % 4 == 0))
+    plan = binding.Plan(prob["A"], prob["B"], prob["C"], prob["nranks"])
+    cA, cB, cC = (prob[x]["replication"] for x in "ABC")
+    K = prob["K"]
+    eligible = cC % cA == 0 and cC % cB == 0 and all((r * K) // cC < ((r + 1) * K) // cC for r in range(cC))
+    if not eligible:
+        assert plan.num_merged_items() == 0
+    if plan.num_merged_items():
+        _check_merged(plan, prob)
+    plan.destroy()
+
+
+def test_merged_items_of_named_workloads():
+    want = dict(bc128=1024, bc256=0, bc512=0, cfg1=1, cfg2=0, cfg3=0, cfg4=0, cfg5=0)
+    for name, n in want.items():
+        cfg = workloads.config(name)
+        plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])
+        assert plan.num_merged_items() == n, name
+        if n and cfg["M"] <= 1024:
+            _check_merged(plan, cfg)
+        plan.destroy()
+    # 96 x 96 tiles: 256 = 2 x 96 + 64, so macro-tiles meet three or four tiles per axis and start inside tiles
+    cfg = workloads._block_cyclic(96, 700, 333, 517)
+    plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])
+    assert plan.num_merged_items() == 3 * 3 and plan.num_items() == 8 * 6
+    _check_merged(plan, cfg)
+    # Stationary B / A plans have no merged list
+    for mode in ("B", "A"):
+        assert binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], binding.STATIONARY_FLAGS[mode]).num_merged_items() == 0
     plan.destroy()

@@ -156,8 +156,9 @@ def block_cyclic_desc(rows: int, cols: int, nb_rows: int, nb_cols: int, proc_row
                       replication: int = 1) -> Dict:
     """Tiles of nb_rows x nb_cols (the last row / column of tiles may be ragged) on a
     proc_rows x proc_cols process grid."""
-    return desc(rows, cols, uniform_cuts(rows, -(-rows // nb_rows)), uniform_cuts(cols, -(-cols // nb_cols)),
-                proc_rows, proc_cols, replication)
+    rc = [min(i * nb_rows, rows) for i in range(-(-rows // nb_rows) + 1)]
+    cc = [min(j * nb_cols, cols) for j in range(-(-cols // nb_cols) + 1)]
+    return desc(rows, cols, rc, cc, proc_rows, proc_cols, replication)
 
 
 def _block_cyclic(nb: int, M: int = 8192, K: int = 8192, N: int = 8192) -> Dict:
