@@ -170,7 +170,9 @@ int32_t dmm_plan_macro_tile(const dmm_plan_t *p);           /* edge of the squar
  * the same replica of A and of B (the replication factor of C is a multiple of those of A and
  * B), so that the ops of a replica are the cells of one grid, (b) no replica has an empty share
  * of k, and (c) merging saves at least a tenth of the macro-tiles (tile grids much finer than the
- * macro-tile: block-cyclic layouts).  dmm_execute then runs this list instead of dmm_plan_items. */
+ * macro-tile: block-cyclic layouts), or the op list is long against the work list (at least 4096
+ * ops and 16 per macro-tile), so that running from the factored form saves the host the time to
+ * write the list out.  dmm_execute then runs this list instead of dmm_plan_items. */
 int64_t dmm_plan_num_merged_items(const dmm_plan_t *p);
 const dmm_merged_item *dmm_plan_merged_items(const dmm_plan_t *p);
 

@@ -22,7 +22,7 @@ namespace dmm {
 namespace {
 
 static_assert(kMaxPieces == PMAX && kDescBytes == DESC_LDS - DESC_GEO && sizeof(PieceDev) == 24 &&
-                  kPieceAlign * 2 >= 16 && 2 * (PMAX + 1) * 4 <= DESC_GEO && kMacroTile == BM && kMacroTile == BN,
+                  kPieceAlign * 2 >= 16 && 2 * (PMAX + 1) * 4 <= 128 && 128 + PMAX * PMAX * 24 <= DESC_GEO && kMacroTile == BM && kMacroTile == BN,
               "the planner's limits for merged macro-tiles describe the kernel's descriptor area");
 
 // Whether the current device lets one workgroup have the stages plus the descriptor area (the

@@ -126,7 +126,7 @@ constexpr int STAGE = A_STAGE + B_STAGE;      // 32 KB
 constexpr int NSTAGE = 4;
 constexpr int LDS_BYTES = NSTAGE * STAGE;     // 128 KB
 constexpr int DESC_LDS = 32 * 1024;           // behind the stages: a merged macro-tile's descriptors
-constexpr int DESC_GEO = 128;                 // ... of which the piece boundaries take the first bytes
+constexpr int DESC_GEO = 2048;                // ... of which the piece boundaries and the C slices take the first bytes
 constexpr int NW = 4;                         // waves per workgroup, 2 x 2
 constexpr int NT = 64 * NW;
 constexpr int WAVES_N = 2;
@@ -241,6 +241,12 @@ __device__ __forceinline__ void load_to_lds_16_masked_v(gptr addr, unsigned lds_
                : "memory", "scc");
 }
 
+// p + d where the caller knows that the low half of the address does not carry.
+__device__ __forceinline__ gptr add_low(gptr p, unsigned d) {
+  const uint64_t a = (uint64_t)(uintptr_t)p;
+  return (gptr)(uintptr_t)((a & 0xFFFFFFFF00000000ull) | (uint32_t)((uint32_t)a + d));
+}
+
 // The first `n` (< 16 / ES) elements at p, the rest zero; n <= 0 reads nothing.
 template <int ES>
 __device__ __forceinline__ u32x4 load_partial(gptr p, int n) {
@@ -322,11 +328,14 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // Merged macro-tiles: the piece that holds each of this lane's four A rows and four B chunks, the
   // row inside that piece and the byte column inside that piece; then, per segment, a full address
   // per load (ca, cbv), advanced by the load slot itself after every load, and the bytes one K
-  // step advances in B (the pitch of the lane's own B tile).
+  // step advances in B (the pitch of the lane's own B tile).  The slot adds to the low half of the
+  // address only (a 64-bit add costs the wave three times as long); a segment in which some
+  // lane's address would carry into the high half is loaded step by step from freshly computed
+  // addresses instead, like a segment that touches the end of a tile buffer.
   int ap[LOADS], bp[LOADS];
   unsigned a_lrow[LOADS], b_lcol[LOADS];
   gptr ca[LOADS], cbv[LOADS];
-  uint64_t bstep[LOADS];
+  unsigned bstep[LOADS];
   if constexpr (COMP) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
@@ -392,6 +401,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   int lead_left = 0;                                     // steps left in its segment, the current one included
   bool lead_tail = false;                                // the segment's last step is a K tail
   bool lead_seg_safe = true;                             // no step of the segment can overrun a tile buffer
+  bool lead_seg_carry = false;                           // (merged items) some lane's address crosses a 4 GB line in it
   unsigned ld_a_pitch = 0, ld_b_pitch = 0;               // row pitch in bytes of the lead segment's A and B tiles
   unsigned ld_a_off[LOADS], ld_b_off[LOADS];             // this lane's byte offsets at those pitches (per segment)
   gptr ld_a = nullptr, ld_b = nullptr;                   // base addresses of the lead step
@@ -422,20 +432,24 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       lead_left = (klen - kpos0 + BK - 1) / BK;
       lead_tail = klen % BK != 0;
       const int64_t more = lead_left - 1;                // the segment's last step reads furthest
-      bool overrun = false;
+      bool overrun = false, carry = false;
 #pragma unroll
       for (int i = 0; i < LOADS; ++i) {
         int64_t room;
         a_chunk(lead_seg, kpos0, i, ca[i], room);
         overrun |= room - more * (BK * ES) < 16;
+        carry |= (uint64_t)(uint32_t)(uintptr_t)ca[i] + (uint64_t)more * (BK * ES) > 0xFFFFFFFFull;
       }
 #pragma unroll
       for (int i = 0; i < LOADS; ++i) {
         int64_t room;
         b_chunk(lead_seg, kpos0, i, cbv[i], room);
-        bstep[i] = (uint64_t)BK * cx.bd[lead_seg * cx.Q + bp[i]].pitch;
+        bstep[i] = (unsigned)BK * cx.bd[lead_seg * cx.Q + bp[i]].pitch;
         overrun |= room - more * (int64_t)bstep[i] < 16;
+        carry |= (uint64_t)(uint32_t)(uintptr_t)cbv[i] + (uint64_t)more * bstep[i] > 0xFFFFFFFFull;
       }
+      lead_seg_carry = __builtin_amdgcn_ballot_w64(carry) != 0;
+      overrun |= lead_seg_carry;
       lead_seg_safe = __builtin_amdgcn_ballot_w64(overrun) == 0;
       return;
     }
@@ -482,14 +496,15 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       all = ~0u;
       if (__builtin_expect(!lead_seg_safe, 0)) {
         if constexpr (COMP) {
-          bool a_ok[LOADS], b_ok[LOADS], bad = false;
+          // (addresses computed afresh: in a segment with a carry the slots' own may have wrapped)
+          bool a_ok[LOADS], b_ok[LOADS], bad = lead_seg_carry;
+          gptr pa[LOADS], pb[LOADS];
 #pragma unroll
           for (int i = 0; i < LOADS; ++i) {
-            gptr p;
             int64_t room;
-            a_chunk(lead_seg, lead_kpos, i, p, room);
+            a_chunk(lead_seg, lead_kpos, i, pa[i], room);
             a_ok[i] = room >= 16;
-            b_chunk(lead_seg, lead_kpos, i, p, room);
+            b_chunk(lead_seg, lead_kpos, i, pb[i], room);
             b_ok[i] = room >= 16;
             bad |= !a_ok[i] || !b_ok[i];
           }
@@ -499,10 +514,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
             const unsigned sa = lds_base + stage * STAGE + wave * 1024;
 #pragma unroll
             for (int i = 0; i < LOADS; ++i)
-              if (a_ok[i]) load_to_lds_16_v(ca[i], sa + i * (NW * 1024));
+              if (a_ok[i]) load_to_lds_16_v(pa[i], sa + i * (NW * 1024));
 #pragma unroll
             for (int i = 0; i < LOADS; ++i)
-              if (b_ok[i]) load_to_lds_16_v(cbv[i], sa + A_STAGE + i * (NW * 1024));
+              if (b_ok[i]) load_to_lds_16_v(pb[i], sa + A_STAGE + i * (NW * 1024));
           }
         } else {
         const SegDev sd = segs[it.seg_begin + lead_seg];
@@ -538,10 +553,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     if constexpr (COMP) {
       if constexpr (j < LOADS) {
         load_to_lds_16_masked_v<j * (NW * 1024)>(ca[j], stage_base, ld_lo, ld_hi);
-        ca[j] += BK * ES;
+        ca[j] = add_low(ca[j], BK * ES);
       } else {
         load_to_lds_16_masked_v<A_STAGE + (j - LOADS) * (NW * 1024)>(cbv[j - LOADS], stage_base, ld_lo, ld_hi);
-        cbv[j - LOADS] += bstep[j - LOADS];
+        cbv[j - LOADS] = add_low(cbv[j - LOADS], bstep[j - LOADS]);
       }
     } else {
       if constexpr (j < LOADS)
@@ -896,9 +911,11 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   int32_t *geo = (int32_t *)(lds + LDS_BYTES);            // piece boundaries, where lanes can index them
+  PieceDev *cd = (PieceDev *)(geo + 32);                  // [R][Q] C slices
   int32_t *klen_s = geo + DESC_GEO / 4;
   PieceDev *ad = (PieceDev *)(klen_s + ((S + 3) & ~3));
   PieceDev *bd = ad + S * R;
+  for (int x = threadIdx.x; x < R * Q; x += NT) cd[x] = c_pieces[ci->c_first + (x / Q) * ci->c_stride + x % Q];
   for (int x = threadIdx.x; x < S; x += NT) klen_s[x] = klen[ci->k_first + x];
   for (int x = threadIdx.x; x < S * R; x += NT) ad[x] = a_pieces[ci->a_first + (x % R) * ci->a_stride + x / R];
   for (int x = threadIdx.x; x < S * Q; x += NT) bd[x] = b_pieces[ci->b_first + (x / Q) * ci->b_stride + x % Q];
@@ -951,7 +968,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
       for (int x = 1; x < R; ++x)
         if (geo[x] <= row) { p = x; base = geo[x]; }
       for (int q = 0; q < Q; ++q) {
-        const PieceDev d = c_pieces[ci->c_first + p * ci->c_stride + q];
+        const PieceDev d = cd[p * Q + q];
         rowbase[row * PMAX + q] = (uint64_t)(uintptr_t)d.ptr + (uint64_t)(row - base) * d.pitch;
       }
     }
@@ -972,26 +989,40 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
     qj[j] = q;
     lcol[j] = (unsigned)(col - base) * (unsigned)ces;
   }
+  // When the four columns of every lane of the wave lie in one column piece (pieces of 128 columns
+  // and more, at multiples of 128), a row takes one table read and its four stores differ by a
+  // constant; otherwise every store reads its own row address.
+  const bool one_piece = __builtin_amdgcn_ballot_w64(qj[0] != qj[FN - 1]) == 0;
+  auto store_all = [&](auto one_tag) {
+    constexpr bool ONE = decltype(one_tag)::value;
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
-      if (row < m_ext) {
+      for (int r = 0; r < 16; ++r) {
+        const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
+        if (row < m_ext) {
+          uint64_t a0 = 0;
+          if constexpr (ONE) a0 = rowbase[row * PMAX + qj[0]] + lcol[0];
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-          if (col0 + j * 32 < n_ext) {
-            const uint64_t a = rowbase[row * PMAX + qj[j]] + lcol[j];
-            if (wide) {
-              __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(uintptr_t)a);
-            } else {
-              float v;
-              asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
-              __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)v), (gushort_ptr)(uintptr_t)a);
+          for (int j = 0; j < FN; ++j)
+            if (col0 + j * 32 < n_ext) {
+              uint64_t a;
+              if constexpr (ONE) a = a0;
+              else a = rowbase[row * PMAX + qj[j]] + lcol[j];
+              if (wide) {
+                __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(uintptr_t)a + (ONE ? j * 32 : 0));
+              } else {
+                float v;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
+                __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)v),
+                                            (gushort_ptr)(uintptr_t)a + (ONE ? j * 32 : 0));
+              }
             }
-          }
+        }
       }
-    }
+  };
+  if (one_piece) store_all(std::true_type{});
+  else store_all(std::false_type{});
 }
 
 }  // namespace dmm

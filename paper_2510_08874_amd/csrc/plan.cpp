@@ -581,7 +581,16 @@ void build_merged(dmm_plan_t *P, uint32_t flags) {
     int64_t tr = 0, tc = 0;
     for (size_t i = 0; i + 1 < G.mc.size(); ++i) tr += (G.mc[i + 1] - G.mc[i] + kMacroTile - 1) / kMacroTile;
     for (size_t j = 0; j + 1 < G.nc.size(); ++j) tc += (G.nc[j + 1] - G.nc[j] + kMacroTile - 1) / kMacroTile;
-    if (merged_count * 10 > (int64_t)C.c * tr * tc * 9) return;
+    // ... or where the op list is so long against the work list (16 ops and more per macro-tile,
+    // thousands in all) that writing it out and turning it into device tables on every call costs
+    // the host as long as the multiplication takes the device (8192^3 in 256 x 256 tiles: 32768 ops,
+    // 1.4 ms of host time against 0.1 ms for the factored form and 0.95 ms of device time)
+    int64_t ops = 0;
+    for (const MergedRep &R : G.reps) ops += (int64_t)(G.mc.size() - 1) * (int64_t)(G.nc.size() - 1) * (int64_t)(R.kc.size() - 1);
+    const int64_t simple_count = (int64_t)C.c * tr * tc;
+    const bool saves_tiles = merged_count * 10 <= simple_count * 9;
+    const bool saves_host = ops >= 4096 && ops >= 16 * simple_count;
+    if (!saves_tiles && !saves_host) return;
   }
   std::vector<MergedItem> seq;
   seq.reserve((size_t)merged_count);

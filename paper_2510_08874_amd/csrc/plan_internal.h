@@ -35,7 +35,7 @@ struct Group {                        // one output sub-tile and its K-segments
 // tile boundaries, and is described by the row intervals and column intervals it meets.
 constexpr int32_t kMaxPieces = 8;     // row (column) intervals one merged macro-tile may meet
 constexpr int32_t kPieceAlign = 8;    // column pieces start at multiples of this many columns inside the macro-tile
-constexpr int64_t kDescBytes = 32 * 1024 - 128;   // room for one macro-tile's descriptors on the device:
+constexpr int64_t kDescBytes = 32 * 1024 - 2048;  // room for one macro-tile's descriptors on the device:
                                                    // 4 bytes per segment + 24 per (segment, piece)
 
 struct MergedRep {

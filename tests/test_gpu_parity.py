@@ -610,6 +610,44 @@ def test_merged_macro_tiles_bf16_c_and_rerun():
     prob.close()
 
 
+def test_merged_macro_tiles_across_a_4gb_line():
+    """The load slots of the merged kernel advance only the low half of a lane's address; a segment
+    in which an address would carry into the high half has to take the step-by-step path.  All
+    tiles of A and B are laid out back to back around a multiple of 2^32 inside one large buffer."""
+    from paper_2510_08874_amd import binding
+    cfg = _bc((300, 520, 300), 64, "bf16")
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"))
+    assert prob.plan.num_merged_items() > 0
+    prob.execute()
+    want = prob.c_global(0)
+    big = torch.empty((1 << 32) + (64 << 20), dtype=torch.uint8, device="cuda")
+    line = (big.data_ptr() + (1 << 32) - 1) // (1 << 32) * (1 << 32)       # the multiple of 2^32 inside it
+    for ts in (prob.A, prob.B):                                             # first A around the line, then B
+        kept = list(ts.tensors)
+        pos = line - 150_000 - big.data_ptr()
+        for i, t in enumerate(ts.tensors):
+            if t is None:
+                continue
+            nbytes = t.numel() * 2
+            view = big[pos:pos + nbytes].view(torch.bfloat16).view(t.shape)
+            view.copy_(t)
+            ts.tensors[i] = view
+            pos += nbytes + 6                                               # keeps the tiles 2-byte aligned only
+        assert big.data_ptr() + pos > line
+        prob.args = prob.plan.marshal(prob.A.tensors, prob.A.ld, prob.B.tensors, prob.B.ld, prob.C.tensors, prob.C.ld)
+        for t in prob.C.tensors:
+            if t is not None:
+                t.fill_(float("nan"))
+        prob.execute()
+        assert prob.plan.ran_merged()
+        assert np.array_equal(want, prob.c_global(0))
+        ts.tensors[:] = kept
+    C_ref = omatmul.matmul(A, B, bf16=True)
+    _check(want, C_ref, _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+    prob.close()
+
+
 # ---- error paths that reach the device entry points ---------------------------------
 
 def test_execute_rejects_bad_arguments():

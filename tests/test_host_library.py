@@ -251,7 +251,8 @@ def _check_merged(plan, prob):
     A, B, C = dist(prob["A"]), dist(prob["B"]), dist(prob["C"])
     items = plan.merged_items()
     T = plan.macro_tile()
-    assert len(items) * 10 <= plan.num_items() * 9, "merged list kept although it saves less than a tenth"
+    assert len(items) * 10 <= plan.num_items() * 9 or (plan.num_tasks() >= 4096 and plan.num_tasks() >= 16 * plan.num_items()), \
+        "merged list kept although it saves neither a tenth of the macro-tiles nor a long op list"
     mc = sorted(set(A.row_cuts) | set(C.row_cuts))
     nc = sorted(set(B.col_cuts) | set(C.col_cuts))
     hit = np.zeros((C.replication, A.rows, B.cols), dtype=np.int32)
@@ -281,7 +282,7 @@ def test_merged_items_tile_every_replica_of_c_once(seed):
 
 
 def test_merged_items_of_named_workloads():
-    want = dict(bc128=1024, bc256=0, bc512=0, cfg1=1, cfg2=0, cfg3=0, cfg4=0, cfg5=0)
+    want = dict(bc128=1024, bc256=1024, bc512=0, cfg1=1, cfg2=0, cfg3=0, cfg4=0, cfg5=0)
     for name, n in want.items():
         cfg = workloads.config(name)
         plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])
