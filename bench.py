@@ -203,7 +203,7 @@ def main() -> int:
         "device": {"name": dprop.name, "gcn_arch": getattr(dprop, "gcnArchName", ""), "compute_units": dprop.multi_processor_count,
                    "peak_used": f"{peak} TFLOP/s = published dense {cfg['dtype']} MFMA peak of MI355X "
                                 "(256 CUs x 4 SIMDs x 1024 flop/cycle x 2.4 GHz for bf16)"},
-        "roofline": {"kernel": "grouped_gemm_kernel", "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
+        "roofline": {"kernel": "grouped_gemm_comp_kernel" if ran_merged else "grouped_gemm_kernel", "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                      "avg_ms": round(g_avg, 4), "median_ms": round(float(np.median(gemm_ms)), 4),
                      "best_ms": round(g_best, 4),
