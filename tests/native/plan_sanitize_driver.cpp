@@ -1,6 +1,6 @@
 // Test driver (host only): runs the library's planner, built with AddressSanitizer and
 // UndefinedBehaviorSanitizer, over seeded random descriptors in all three data movement modes,
-// with and without the iteration offset, and reads every accessor to its end.  Prints one
+// with and without the iteration offset and the merged work list, and reads every accessor to its end.  Prints one
 // checksum line; any sanitizer report makes the process fail.
 #include <cstdint>
 #include <cstdio>
@@ -58,10 +58,14 @@ int main() {
     make(&A, M, K, p);
     make(&B, K, N, p);
     make(&C, M, N, p);
-    for (uint32_t flags : {0u, 1u, 2u, 4u, 5u, 6u}) {
+    for (uint32_t flags : {0u, 1u, 2u, 4u, 5u, 6u, 8u, 12u}) {
       dmm_plan_t *P = nullptr;
       const int rc = dmm_plan(&A.d, &B.d, &C.d, p, flags, &P);
       if (rc != DMM_OK) { std::printf("plan failed: %s\n", dmm_strerror(rc)); return 1; }
+      // the merged work list first: with it the plan has not written out its op list yet
+      const int64_t nm = dmm_plan_num_merged_items(P);
+      const dmm_merged_item *merged = dmm_plan_merged_items(P);
+      for (int64_t i = 0; i < nm; ++i) sum += (uint64_t)(merged[i].m0 + merged[i].n_ext + merged[i].row_pieces + merged[i].col_pieces);
       const int64_t n = dmm_plan_num_tasks(P), g = dmm_plan_num_groups(P), ni = dmm_plan_num_items(P);
       const dmm_task *t = dmm_plan_tasks(P);
       const int64_t *order = dmm_plan_order(P), *offs = dmm_plan_group_offsets(P);

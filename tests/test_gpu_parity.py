@@ -596,6 +596,29 @@ def test_merged_macro_tiles(dims, nb, dtype, ldm, reps, p):
     plain.close()
 
 
+@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_merged_macro_tiles_random_partitionings(seed, dtype):
+    """The merged kernel forced (DMM_MERGE_ALWAYS) onto random grids: uneven and empty tiles, odd
+    leading dimensions, K tails in every segment, column cuts at any position, replication.  Plans
+    that cannot have a merged list (C replicas reading several replicas of A or B, empty shares)
+    run the per-group path; either way parity, and bitwise the per-group result."""
+    from paper_2510_08874_amd import binding
+    prob = helpers.random_problem(seed + 300, max_dim=700, allow_empty=(seed % 2 == 1))
+    cfg = dict(prob, name=f"random-merged{seed}", dtype=dtype, dist=("normal", 1.0), seeds=(seed, seed + 900),
+               merge_always=True)
+    A, B = workloads.make_operands(cfg)
+    dev = _device_problem(cfg, A, B, c_fill=float("nan"))
+    dev.execute()
+    assert dev.plan.ran_merged() == (dev.plan.num_merged_items() > 0)
+    got = [dev.c_global(r) for r in range(cfg["C"]["replication"])]
+    _check(got[0], omatmul.matmul(A, B, bf16=(dtype == "bf16")), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+    dev.execute(flags=binding.DMM_NO_MERGE)
+    for r in range(cfg["C"]["replication"]):
+        assert np.array_equal(got[r], dev.c_global(r))
+    dev.close()
+
+
 def test_merged_macro_tiles_bf16_c_and_rerun():
     from paper_2510_08874_amd import binding
     cfg = _bc((700, 333, 517), 96, "bf16")

@@ -299,3 +299,21 @@ def test_merged_items_of_named_workloads():
     for mode in ("B", "A"):
         assert binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], binding.STATIONARY_FLAGS[mode]).num_merged_items() == 0
     plan.destroy()
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """include/dmm.h compiled as C99 with -pedantic -Werror; a C program plans configuration 1
+    through the library (host calls only) and reads the accessors."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    exe = tmp_path / "abi_from_c"
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "native", "abi_from_c.c"), "-o", str(exe),
+                    "-L", lib_dir, "-ldmm", "-Wl,-rpath," + lib_dir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert "tasks 16 groups 8 items 8 merged 1 first 0:[0,64)x[0,128)x[0,128) tile 256" in out
+    assert "both stationary flags: -1" in out

@@ -1,5 +1,5 @@
 """The host planner under AddressSanitizer + UndefinedBehaviorSanitizer: plan.cpp is pure host
-C++, so it is built here with g++ and a small driver (tests/native/) and run over 2400 random
+C++, so it is built here with g++ and a small driver (tests/native/) and run over 3200 random
 plans in every mode.  No GPU, no HIP."""
 import os
 import shutil
@@ -22,4 +22,4 @@ def test_planner_clean_under_asan_and_ubsan(tmp_path):
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
     run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert run.returncode == 0, run.stdout[-2000:] + run.stderr[-4000:]
-    assert run.stdout.startswith("ok plans=2400")
+    assert run.stdout.startswith("ok plans=3200")
