@@ -224,6 +224,24 @@ __device__ __forceinline__ void load_to_lds_16_masked(gptr base, unsigned lane_o
                : "memory", "scc");
 }
 
+// The form of the quiet iterations of the K loop, where every lane takes part for certain: no exec
+// mask to set and restore, two instructions fewer per load slot (s_nop is the wait state between
+// the M0 write and the LDS-DMA instruction).
+template <int IMM>
+__device__ __forceinline__ void load_to_lds_16_plain(gptr base, unsigned lane_off, unsigned lds_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_off), "s"(base), "s"(lds_base), "n"(IMM)
+               : "memory", "scc");
+}
+template <int IMM>
+__device__ __forceinline__ void load_to_lds_16_plain_v(gptr addr, unsigned lds_base) {
+  asm volatile("s_add_u32 m0, %1, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(addr), "s"(lds_base), "n"(IMM)
+               : "memory", "scc");
+}
+
 // The same two forms with a full 64-bit address per lane (merged macro-tiles: the lanes of one
 // instruction read from different tile buffers).
 __device__ __forceinline__ void load_to_lds_16_v(gptr addr, unsigned lds_base) {
@@ -548,22 +566,28 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   };
   // load number j of the lead step (0 .. LOADS - 1: A, LOADS .. 2 LOADS - 1: B) into the LDS stage
   // whose base address (plus this wave's KB offset) is `stage_base`
-  auto dma = [&](auto jc, unsigned stage_base) {
+  auto dma = [&](auto jc, unsigned stage_base, auto quiet_tag) {
     constexpr int j = decltype(jc)::value;
+    constexpr bool QUIET = decltype(quiet_tag)::value;   // every lane loads: no exec mask
+    constexpr int IMM = j < LOADS ? j * (NW * 1024) : A_STAGE + (j - LOADS) * (NW * 1024);
     if constexpr (COMP) {
       if constexpr (j < LOADS) {
-        load_to_lds_16_masked_v<j * (NW * 1024)>(ca[j], stage_base, ld_lo, ld_hi);
+        if constexpr (QUIET) load_to_lds_16_plain_v<IMM>(ca[j], stage_base);
+        else load_to_lds_16_masked_v<IMM>(ca[j], stage_base, ld_lo, ld_hi);
         ca[j] = add_low(ca[j], BK * ES);
       } else {
-        load_to_lds_16_masked_v<A_STAGE + (j - LOADS) * (NW * 1024)>(cbv[j - LOADS], stage_base, ld_lo, ld_hi);
+        if constexpr (QUIET) load_to_lds_16_plain_v<IMM>(cbv[j - LOADS], stage_base);
+        else load_to_lds_16_masked_v<IMM>(cbv[j - LOADS], stage_base, ld_lo, ld_hi);
         cbv[j - LOADS] = add_low(cbv[j - LOADS], bstep[j - LOADS]);
       }
     } else {
-      if constexpr (j < LOADS)
-        load_to_lds_16_masked<j * (NW * 1024)>(ld_a, ld_a_off[j], stage_base, ld_lo, ld_hi);
-      else
-        load_to_lds_16_masked<A_STAGE + (j - LOADS) * (NW * 1024)>(ld_b, ld_b_off[j - LOADS], stage_base,
-                                                                   ld_lo, ld_hi);
+      if constexpr (j < LOADS) {
+        if constexpr (QUIET) load_to_lds_16_plain<IMM>(ld_a, ld_a_off[j], stage_base);
+        else load_to_lds_16_masked<IMM>(ld_a, ld_a_off[j], stage_base, ld_lo, ld_hi);
+      } else {
+        if constexpr (QUIET) load_to_lds_16_plain<IMM>(ld_b, ld_b_off[j - LOADS], stage_base);
+        else load_to_lds_16_masked<IMM>(ld_b, ld_b_off[j - LOADS], stage_base, ld_lo, ld_hi);
+      }
     }
   };
 
@@ -685,7 +709,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // One sub-step: its FM FN MFMA slots; after slot n either one of this wave's loads (when
   // slot % 4 == ROT) or the next LDS read of the following sub-step.  `first` = index of the
   // sub-step's first slot within the K step (0 or 16).
-  auto sub_step = [&](auto first_tag, const Frags &cur, Frags &nxt, int rd_stage, int rd_q, int ld_stage) {
+  auto sub_step = [&](auto first_tag, auto quiet_tag, const Frags &cur, Frags &nxt, int rd_stage, int rd_q, int ld_stage) {
     constexpr int first = decltype(first_tag)::value;
     const unsigned ld_base = lds_base + ld_stage * STAGE + wave * 1024;
     // (unrolled by hand over the 16 slots so that slot numbers are compile-time constants)
@@ -699,7 +723,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
         ld_b_next = ld_b + ld_b_step;
       }
       if constexpr (g % NW == ROT) {
-        dma(std::integral_constant<int, g / NW>{}, ld_base);
+        dma(std::integral_constant<int, g / NW>{}, ld_base, quiet_tag);
       } else if (ES == 2) {
         read_op(rd_stage, rd_q, r, nxt);
       }
@@ -741,10 +765,10 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     if (t < n) {
       prepare_lead(true, t);
       const unsigned base = lds_base + t * STAGE + wave * 1024;
-      dma(std::integral_constant<int, 0>{}, base); dma(std::integral_constant<int, 1>{}, base);
-      dma(std::integral_constant<int, 2>{}, base); dma(std::integral_constant<int, 3>{}, base);
-      dma(std::integral_constant<int, 4>{}, base); dma(std::integral_constant<int, 5>{}, base);
-      dma(std::integral_constant<int, 6>{}, base); dma(std::integral_constant<int, 7>{}, base);
+      dma(std::integral_constant<int, 0>{}, base, std::false_type{}); dma(std::integral_constant<int, 1>{}, base, std::false_type{});
+      dma(std::integral_constant<int, 2>{}, base, std::false_type{}); dma(std::integral_constant<int, 3>{}, base, std::false_type{});
+      dma(std::integral_constant<int, 4>{}, base, std::false_type{}); dma(std::integral_constant<int, 5>{}, base, std::false_type{});
+      dma(std::integral_constant<int, 6>{}, base, std::false_type{}); dma(std::integral_constant<int, 7>{}, base, std::false_type{});
       ++issued;
       if (t + 1 < n) advance_lead();
     } else {
@@ -780,36 +804,41 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     lead_kpos += quiet * BK;
   };
   plan_quiet(NSTAGE - 1);
-  // Two nested loops around ONE copy of the iteration: the inner loop runs the quiet iterations
-  // and carries only s, the counter and the two addresses; the outer loop does the general
-  // bookkeeping between runs.  (As a single loop with a rare branch at its end, every scalar the
-  // rare branch may change is copied back and forth once per iteration.)
+  // The iteration exists in two copies.  The general one takes its loads' exec mask and its mid-
+  // iteration wait from what the bookkeeping prepared; the quiet one, which runs `quiet` times after
+  // it, knows that every lane loads and that nothing needs a repair, so its load slots are two
+  // instructions shorter and its wait is a constant.  The quiet loop carries only s, the counter
+  // and the two addresses; the general bookkeeping runs between such runs.
   int s = 0;
+  auto iteration = [&](auto quiet_tag) {
+    constexpr bool QUIET = decltype(quiet_tag)::value;
+    const int stage = s & (NSTAGE - 1);
+    const int ld_stage = (s + NSTAGE - 1) & (NSTAGE - 1);
+    sub_step(std::integral_constant<int, 0>{}, quiet_tag, fr[0], fr[1], stage, 1, ld_stage);
+    // publish step s + 1: this wave's loads of it must have landed; steps s + 2 and (half of)
+    // s + 3 may stay in flight (loads return in order)
+    if (QUIET || __builtin_expect(mid_plain != 0, 1)) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
+    } else {
+      if (loads_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
+      else if (s + 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (s + 1 < n) publish_fix(s + 1);
+    }
+    __syncthreads();                         // every wave has read stage s; step s + 1 is complete
+    sub_step(std::integral_constant<int, FM * FN>{}, quiet_tag, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
+    ++s;
+  };
   for (;;) {
+    iteration(std::false_type{});
 #pragma clang loop unroll(disable)
-    for (;;) {
-      const int stage = s & (NSTAGE - 1);
-      const int ld_stage = (s + NSTAGE - 1) & (NSTAGE - 1);
-      sub_step(std::integral_constant<int, 0>{}, fr[0], fr[1], stage, 1, ld_stage);
-      // publish step s + 1: this wave's loads of it must have landed; steps s + 2 and (half of)
-      // s + 3 may stay in flight (loads return in order)
-      if (__builtin_expect(mid_plain != 0, 1)) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
-      } else {
-        if (loads_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS + LOADS) : "memory");
-        else if (s + 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (s + 1 < n) publish_fix(s + 1);
-      }
-      __syncthreads();                       // every wave has read stage s; step s + 1 is complete
-      sub_step(std::integral_constant<int, FM * FN>{}, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
-      ++s;
-      if (quiet == 0) break;
+    while (quiet != 0) {
       --quiet;
       if constexpr (!COMP) {
         ld_a = ld_a_next;
         ld_b = ld_b_next;
       }
+      iteration(std::true_type{});
     }
     if (s >= n) break;
     loads_on = s - 1 + NSTAGE < n;           // step s + 3 exists (s is the coming iteration)
