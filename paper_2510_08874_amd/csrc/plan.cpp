@@ -573,6 +573,14 @@ void build_merged(dmm_plan_t *P, uint32_t flags) {
     G.reps.push_back(std::move(R));
   }
   if (cap < 1) return;
+  {
+    // the device tables hold one slice per (row interval, segment), (segment, column interval) and
+    // (row interval, column interval) of every replica, indexed with 32 bits: keep them moderate
+    const double mr = (double)G.mc.size(), nr = (double)G.nc.size();
+    double slices = 0;
+    for (const MergedRep &R : G.reps) slices += (mr + nr) * (double)R.kc.size() + mr * nr;
+    if (slices > 1.6e7) return;
+  }
   const std::vector<Extent> rows = tile_axis(G.mc, (int32_t)cap, 1), cols = tile_axis(G.nc, (int32_t)cap, kPieceAlign);
   // worth it only if it saves a tenth of the macro-tiles
   const int64_t merged_count = (int64_t)C.c * (int64_t)rows.size() * (int64_t)cols.size();
