@@ -168,7 +168,8 @@ int32_t dmm_plan_macro_tile(const dmm_plan_t *p);           /* edge of the squar
 /* The alternative work list of merged macro-tiles, in launch order; 0 / NULL when the plan has
  * none.  A plan has one when (a) it is a Stationary C plan in which all ranks of a C replica read
  * the same replica of A and of B (the replication factor of C is a multiple of those of A and
- * B), so that the ops of a replica are the cells of one grid, (b) no replica has an empty share
+ * B), or a Stationary B / A plan without any replication, so that the ops of a replica are the
+ * cells of one grid, (b) no replica has an empty share
  * of k, and (c) merging saves at least a tenth of the macro-tiles (tile grids much finer than the
  * macro-tile: block-cyclic layouts), or the op list is long against the work list (at least 4096
  * ops and 16 per macro-tile), so that running from the factored form saves the host the time to

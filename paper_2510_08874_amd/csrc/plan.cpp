@@ -549,7 +549,10 @@ void build_merged(dmm_plan_t *P, uint32_t flags) {
   Merged &G = P->merged;
   G = Merged();
   const Grid &A = P->A, &B = P->B, &C = P->C;
-  if (flags & (DMM_STATIONARY_B | DMM_STATIONARY_A)) return;
+  // With B or A in place the ops are the same boxes as with C in place as long as nothing is
+  // replicated (only the rank that performs a box differs), so the same work list serves; their
+  // replicas split M or N instead of K, which this list does not describe.
+  if ((flags & (DMM_STATIONARY_B | DMM_STATIONARY_A)) && (A.c != 1 || B.c != 1 || C.c != 1)) return;
   // every rank of a C replica has to read the same replica of A and of B
   if (C.c % A.c != 0 || C.c % B.c != 0) return;
   const int64_t M = A.rows, K = A.cols, N = B.cols, lim = (int64_t)1 << 31;

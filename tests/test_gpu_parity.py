@@ -619,6 +619,26 @@ def test_merged_macro_tiles_random_partitionings(seed, dtype):
     dev.close()
 
 
+@pytest.mark.parametrize("mode", ["B", "A"])
+def test_merged_macro_tiles_stationary_b_and_a(mode):
+    """Without replication the ops of a Stationary B (A) plan are the boxes of the Stationary C plan
+    on other ranks, so its merged macro-tiles are the same and so is C, bit for bit."""
+    cfg = _bc((700, 333, 517), 96, "bf16")
+    A, B = workloads.make_operands(cfg)
+    ref = _device_problem(cfg, A, B, c_fill=float("nan"))
+    ref.execute()
+    want = ref.c_global(0)
+    ref.close()
+    prob = _device_problem(dict(cfg, stationary=mode), A, B, c_fill=float("nan"))
+    assert prob.plan.num_merged_items() > 0
+    assert {t[0] for t in prob.plan.tasks()} == set(range(8))
+    prob.execute()
+    assert prob.plan.ran_merged()
+    assert np.array_equal(want, prob.c_global(0))
+    _check(want, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+    prob.close()
+
+
 def test_merged_macro_tiles_bf16_c_and_rerun():
     from paper_2510_08874_amd import binding
     cfg = _bc((700, 333, 517), 96, "bf16")

@@ -273,6 +273,13 @@ def test_merged_items_tile_every_replica_of_c_once(seed):
     plan = binding.Plan(prob["A"], prob["B"], prob["C"], prob["nranks"])
     cA, cB, cC = (prob[x]["replication"] for x in "ABC")
     K = prob["K"]
+    for mode in ("B", "A"):
+        other = binding.Plan(prob["A"], prob["B"], prob["C"], prob["nranks"], binding.STATIONARY_FLAGS[mode])
+        if cA == cB == cC == 1:
+            assert other.merged_items() == plan.merged_items()
+        else:
+            assert other.num_merged_items() == 0
+        other.destroy()
     eligible = cC % cA == 0 and cC % cB == 0 and all((r * K) // cC < ((r + 1) * K) // cC for r in range(cC))
     if not eligible:
         assert plan.num_merged_items() == 0
@@ -295,9 +302,12 @@ def test_merged_items_of_named_workloads():
     plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])
     assert plan.num_merged_items() == 3 * 3 and plan.num_items() == 8 * 6
     _check_merged(plan, cfg)
-    # Stationary B / A plans have no merged list
+    # Stationary B / A plans: the same list while nothing is replicated, none otherwise
     for mode in ("B", "A"):
-        assert binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], binding.STATIONARY_FLAGS[mode]).num_merged_items() == 0
+        other = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], binding.STATIONARY_FLAGS[mode])
+        assert other.merged_items() == plan.merged_items()
+        rep = dict(cfg["A"], replication=2)
+        assert binding.Plan(rep, cfg["B"], cfg["C"], 16, binding.STATIONARY_FLAGS[mode]).num_merged_items() == 0
     plan.destroy()
 
 
