@@ -61,6 +61,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
     ap.add_argument("--no-context", action="store_true", help="skip the vendor-library GEMM timing")
+    ap.add_argument("--no-fused", action="store_true", help="skip the extra timing of the DMM_FUSED_REDUCE variant")
     ap.add_argument("--no-reduce-large", action="store_true",
                     help="skip the stand-alone replica sum at c = 4 on 16384 x 16384 (5.4 GB moved)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -147,6 +148,43 @@ def main() -> int:
     while inflight:
         retire()
 
+    # the same steps with the replica sum fused into the GEMM (DMM_FUSED_REDUCE), for the record: no
+    # replica-sum kernel, replica 0's macro-tiles add the other replicas' partial sums before they store
+    fused = None
+    if c_rep > 1 and not args.no_fused and args.merge != "always" and not prob.plan.num_merged_items():
+        fms = []
+
+        def fstep(record):
+            plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], plan_flags)
+            plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING | binding.DMM_FUSED_REDUCE | exec_flags, stream)
+            inflight.append((plan, record))
+            if len(inflight) > DEPTH:
+                p0, rec = inflight.pop(0)
+                g, r = p0.elapsed_ms()
+                p0.destroy()
+                if rec:
+                    fms.append((g, r))
+        for _ in range(10):
+            fstep(False)
+        torch.cuda.synchronize()
+        tf0 = time.perf_counter()
+        for _ in range(args.steps):
+            fstep(True)
+        torch.cuda.synchronize()
+        tf1 = time.perf_counter()
+        while inflight:
+            p0, rec = inflight.pop(0)
+            g, r = p0.elapsed_ms()
+            p0.destroy()
+            if rec:
+                fms.append((g, r))
+        f_ms = (tf1 - tf0) * 1e3 / args.steps
+        fused = {"flag": "DMM_FUSED_REDUCE", "ms_per_step": round(f_ms, 4),
+                 "value": round(workloads.flops(cfg) / (f_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+                 "gemm_both_launches_avg_ms": round(float(np.mean([g for g, _ in fms])), 4),
+                 "replica_sum_kernel_ran": bool(any(r >= 0 for _, r in fms)),
+                 "note": "same final contents of every C replica, bit for bit; not the default, not `value`"}
+
     # the same step without re-planning (one plan, tables already resident), for the record
     torch.cuda.synchronize()
     te0 = time.perf_counter()
@@ -219,6 +257,9 @@ def main() -> int:
                                        "unit": "GB/s", "frac": round(red_bytes / (r_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                        "avg_ms": round(r_avg, 4), "best_ms": round(r_best, 4),
                                        "traffic": traffic.get("reduce_bytes")}
+
+    if fused:
+        out["fused_replica_sum"] = fused
 
     # parity spot check on the output of the timed run, and the CPU baseline
     from oracle import matmul as omatmul

@@ -65,6 +65,12 @@ typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
 #define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
 #define DMM_TIMING 2u    /* record events around the GEMM launch and around the replica-sum launch
                             on the given stream; read them with dmm_plan_elapsed_ms */
+#define DMM_FUSED_REDUCE 16u /* replicated C: no replica-sum kernel; the macro-tiles of replicas 1, 2, ...
+                            run first, those of replica 0 in a second launch behind them, where each adds
+                            the other replicas' partial sums of its region to its own, ((own + C_1) + C_2)
+                            ..., before it stores.  Same final contents of every replica, bit for bit, as
+                            without the flag.  Ignored where it does not apply: one replica of C,
+                            DMM_NO_REDUCE, merged macro-tiles, macro-tiles cut along K */
 #define DMM_NO_MERGE 8u  /* run the macro-tiles of dmm_plan_items even where the plan has merged ones */
 #define DMM_C_BF16 4u    /* the C tiles are bf16 buffers (c_ld in bf16 elements): every element receives
                             its fp32 sum rounded to nearest even, once.  Only for a C with one replica
@@ -182,7 +188,7 @@ const dmm_merged_item *dmm_plan_merged_items(const dmm_plan_t *p);
  *   a_tiles, b_tiles      host arrays of device pointers, one per (replica, tile) in table order
  *   c_tiles               host array of device pointers to fp32 tiles (bf16 tiles with DMM_C_BF16)
  *   a_ld, b_ld, c_ld      host arrays, leading dimension in elements, >= the tile's width
- *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING, DMM_C_BF16, DMM_NO_MERGE
+ *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING, DMM_C_BF16, DMM_NO_MERGE, DMM_FUSED_REDUCE
  *   hip_stream            hipStream_t, may be null (default stream)
  * Pointers of empty tiles may be null.  Tile buffers are caller-owned and must
  * stay valid until the stream work completes.  Asynchronous: returns after

@@ -20,6 +20,7 @@ DMM_NO_REDUCE = 1
 DMM_TIMING = 2
 DMM_C_BF16 = 4
 DMM_NO_MERGE = 8
+DMM_FUSED_REDUCE = 16
 DMM_STATIONARY_B = 1          # dmm_plan flags
 DMM_STATIONARY_A = 2
 DMM_ITERATION_OFFSET = 4

@@ -39,9 +39,13 @@ int ensure_state(dmm_plan_t *P) {
   {
     std::lock_guard<std::mutex> g(mu);
     if (!done[device]) {
-      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   LDS_BYTES));
-      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  LDS_BYTES));
+      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  LDS_BYTES));
+      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   LDS_BYTES));
       const bool ok =
              hipFuncSetAttribute((const void *)grouped_gemm_comp_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -399,7 +403,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   using namespace dmm;
   if (!P || !a_tiles || !a_ld || !b_tiles || !b_ld || !c_tiles || !c_ld) return DMM_EINVAL;
   if (dtype != DMM_BF16 && dtype != DMM_F32) return DMM_EINVAL;
-  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING | DMM_C_BF16 | DMM_NO_MERGE)) return DMM_EINVAL;
+  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING | DMM_C_BF16 | DMM_NO_MERGE | DMM_FUSED_REDUCE)) return DMM_EINVAL;
   const bool timed = (flags & DMM_TIMING) != 0;
   // bf16 C tiles only where a tile receives a final sum: partial sums of a replicated C stay fp32
   if ((flags & DMM_C_BF16) && P->C.c != 1) return DMM_EINVAL;
@@ -457,7 +461,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
     P->dev->ran_merged = false;
     if ((rc = materialize(P))) return rc;
     // The tables of all kernels go up in one copy in front of the GEMM launch, so that nothing
-    // but the launches separates them:  ItemDev[] | SegDev[] | FixItem[] | replica-sum tables.
+    // but the launches separates them:  ItemDev[] | SegDev[] | FixItem[] | RedSrc[] | replica-sum tables.
     RedLaunch red;
     const size_t n_plan_items = P->items.size();
     const size_t n_segs = P->tasks.size();
@@ -508,6 +512,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       d.n_ext = w.n_ext;
       d.first_step = 0;
       d.c_es = (int32_t)c_es;
+      d.red_first = d.red_count = 0;
       hi[i] = d;
     }
     // K-split of the last round (see sum_parts_kernel): with W working items on `cus` CUs the
@@ -576,10 +581,45 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         }
       for (FixItem &f : fixes) f.parts = (const float *)(P->dev->split_buf + (uintptr_t)f.parts);
     }
+    // Fused replica sum: the macro-tiles of replicas 1, 2, ... go first, in a launch of their own;
+    // those of replica 0 follow in a second launch (stream order: every partial sum is complete by
+    // then) and add the others' partial sums to their own before they store.  No replica-sum
+    // kernel runs.  (Not together with the K-split, whose runs store through a scratch buffer.)
+    const bool fuse = (flags & DMM_FUSED_REDUCE) && !(flags & DMM_NO_REDUCE) && P->C.c > 1 && n_runs == 0;
+    std::vector<RedSrc> reds;
+    size_t n_first = hi.size();               // items of the first launch
+    if (fuse) {
+      std::vector<ItemDev> others, origin;
+      others.reserve(hi.size());
+      origin.reserve(hi.size());
+      for (size_t i = 0; i < n_plan_items; ++i) {
+        const dmm_work_item &w = P->items[i];
+        if (w.c_rep != 0) {
+          others.push_back(hi[i]);
+          continue;
+        }
+        ItemDev d = hi[i];
+        d.red_first = (int32_t)reds.size();
+        d.red_count = P->C.c - 1;
+        for (int32_t r = 1; r < P->C.c; ++r) {
+          const int64_t idx = P->C.table_index(r, w.c_ti, w.c_tj);
+          if (!c_tiles[idx]) return DMM_EINVAL;
+          RedSrc src;
+          src.ld = c_ld[idx];
+          src.p = (const float *)c_tiles[idx] + (w.m0 - P->C.rc[w.c_ti]) * src.ld + (w.n0 - P->C.cc[w.c_tj]);
+          reds.push_back(src);
+        }
+        origin.push_back(d);
+      }
+      n_first = others.size();
+      hi = std::move(others);
+      hi.insert(hi.end(), origin.begin(), origin.end());
+    }
     const size_t n_items = hi.size();
     const size_t o_segs = n_items * sizeof(ItemDev);
     const size_t o_fix = o_segs + n_segs * sizeof(SegDev);
-    const size_t total = n_items > 0 ? o_fix + fixes.size() * sizeof(FixItem) : 0;
+    const size_t o_red = o_fix + fixes.size() * sizeof(FixItem);
+    const size_t total = n_items > 0 ? o_red + reds.size() * sizeof(RedSrc) : 0;
     std::vector<char> &h = P->dev->host;
     h.clear();
     h.resize(total);
@@ -587,8 +627,9 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       std::memcpy(h.data(), hi.data(), n_items * sizeof(ItemDev));
       std::memcpy(h.data() + o_segs, hs.data(), n_segs * sizeof(SegDev));
       if (!fixes.empty()) std::memcpy(h.data() + o_fix, fixes.data(), fixes.size() * sizeof(FixItem));
+      if (!reds.empty()) std::memcpy(h.data() + o_red, reds.data(), reds.size() * sizeof(RedSrc));
     }
-    if (!(flags & DMM_NO_REDUCE) && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, total, &red))) return rc;
+    if (!(flags & DMM_NO_REDUCE) && !fuse && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, total, &red))) return rc;
     if (!h.empty()) {
       if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
       red.dev_base = P->dev->gemm_table.dev();
@@ -600,11 +641,25 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         if ((rc = timing_events(P->dev->t_gemm))) return rc;
         DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
       }
-      if (dtype == DMM_BF16)
-        hipLaunchKernelGGL(grouped_gemm_kernel<2>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
-      else
-        hipLaunchKernelGGL(grouped_gemm_kernel<4>, dim3((unsigned)n_items), dim3(NT), LDS_BYTES, stream, di, ds);
-      DMM_HIP(hipGetLastError());
+      const RedSrc *dr = (const RedSrc *)(P->dev->gemm_table.dev() + o_red);
+      const size_t part[2][2] = {{0, n_first}, {n_first, n_items - n_first}};   // {first item, count} per launch
+      for (int l = 0; l < 2; ++l) {
+        if (part[l][1] == 0) continue;
+        const bool sums = fuse && l == 1;       // the launch whose macro-tiles add the other replicas' partial sums
+        if (dtype == DMM_BF16 && !sums)
+          hipLaunchKernelGGL((grouped_gemm_kernel<2, false>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
+                             di + part[l][0], ds, dr);
+        else if (dtype == DMM_BF16)
+          hipLaunchKernelGGL((grouped_gemm_kernel<2, true>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
+                             di + part[l][0], ds, dr);
+        else if (!sums)
+          hipLaunchKernelGGL((grouped_gemm_kernel<4, false>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
+                             di + part[l][0], ds, dr);
+        else
+          hipLaunchKernelGGL((grouped_gemm_kernel<4, true>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
+                             di + part[l][0], ds, dr);
+        DMM_HIP(hipGetLastError());
+      }
       if (!fixes.empty()) {
         hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(fixes.size() * (BM / FIX_ROWS))), dim3(256), 0, stream,
                            (const FixItem *)(P->dev->gemm_table.dev() + o_fix));

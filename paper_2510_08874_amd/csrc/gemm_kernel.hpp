@@ -79,6 +79,13 @@ struct ItemDev {         // one macro-tile, or a run of K steps of one
   int32_t first_step;    // where it starts in the group's step sequence (steps of a segment:
                          // ceil(klen / K step); the sequence runs over the segments in order)
   int32_t c_es;          // bytes per element of the destination: 4 = fp32, 2 = bf16 (rounded to nearest even)
+  int32_t red_first;     // fused replica sum: the other replicas' partial sums of this macro-tile are
+  int32_t red_count;     // added before the store, red[red_first .. + red_count) in that order (0: none)
+};
+
+struct RedSrc {          // one other replica's partial sum of a macro-tile: its top-left element, its pitch
+  const float *p;
+  int64_t ld;            // elements
 };
 
 // Merged macro-tiles.  Where the tiles of A, B and C are small against 256 x 256, a macro-tile may
@@ -851,9 +858,12 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 7" ::: "memory");
 }
 
-template <int ES>
+// FUSE: the instantiation whose epilogue can add other replicas' partial sums (fused replica sum);
+// a kernel of its own, so that the plain one keeps its size and its register allocation.
+template <int ES, bool FUSE = false>
 __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restrict__ items,
-                                                          const SegDev *__restrict__ segs) {
+                                                          const SegDev *__restrict__ segs,
+                                                          const RedSrc *__restrict__ red) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const ItemDev it = items[blockIdx.x];
   const int lane = threadIdx.x & 63;
@@ -915,7 +925,61 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
         }
       }
   };
-  if (it.m_ext == BM && it.n_ext == BN) store_all(std::true_type{});
+  // Fused replica sum (fp32 C only): the macro-tile of the origin replica, launched after the other
+  // replicas' macro-tiles have finished, adds their partial sums to its own, ((own + p_1) + p_2) ...,
+  // the order and precision of the replica-sum kernel, and stores the total.  32 rows at a time:
+  // 64 sums and 64 loaded values per lane, all loads of a partial in flight before the first add.
+  auto store_sum = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      float sum[16][FN];
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(sum[r][j]) : "a"(acc[i][j][r]));
+      for (int q = 0; q < it.red_count; ++q) {
+        const RedSrc src = red[it.red_first + q];
+        const __attribute__((address_space(1))) char *pbytes = (const __attribute__((address_space(1))) char *)src.p;
+        const unsigned ppitch = (unsigned)src.ld * 4u;
+        const unsigned poff = (unsigned)row0 * ppitch + (unsigned)col0 * 4u;
+        float v[16][FN];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int dr = i * 32 + 8 * (r >> 2) + (r & 3);
+          const unsigned o = poff + (unsigned)dr * ppitch;
+#pragma unroll
+          for (int j = 0; j < FN; ++j) {
+            v[r][j] = 0.f;
+            if (FULL || (row0 + dr < it.m_ext && col0 + j * 32 < it.n_ext))
+              v[r][j] = __builtin_nontemporal_load((const __attribute__((address_space(1))) float *)(pbytes + o + j * 128));
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+#pragma unroll
+          for (int j = 0; j < FN; ++j) sum[r][j] = sum[r][j] + v[r][j];
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int dr = i * 32 + 8 * (r >> 2) + (r & 3);
+        const unsigned o = voff + (unsigned)dr * pitch;
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          if (FULL || (row0 + dr < it.m_ext && col0 + j * 32 < it.n_ext))
+            __builtin_nontemporal_store(sum[r][j], (gfloat_ptr)(cbytes + o + j * 128));
+      }
+    }
+  };
+  const bool full = it.m_ext == BM && it.n_ext == BN;
+  if constexpr (FUSE) {
+    if (it.red_count > 0) {
+      if (full) store_sum(std::true_type{});
+      else store_sum(std::false_type{});
+      return;
+    }
+  }
+  if (full) store_all(std::true_type{});
   else store_all(std::false_type{});
 }
 
@@ -973,6 +1037,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
     it.n_ext = n_ext;
     it.first_step = 0;
     it.c_es = ci->c_es;
+    it.red_first = it.red_count = 0;
     CompCtx cx;
     cx.klen = klen_s;
     cx.ad = ad;

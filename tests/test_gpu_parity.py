@@ -693,6 +693,60 @@ def test_merged_macro_tiles_across_a_4gb_line():
     prob.close()
 
 
+# ---- fused replica sum (DMM_FUSED_REDUCE) -----------------------------------------------------
+
+def _fused_against_plain(cfg, A, B, ldm=1, must_fuse=True):
+    from paper_2510_08874_amd import binding
+    c = cfg["C"]["replication"]
+    plain = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
+    plain.execute(flags=binding.DMM_NO_MERGE)
+    want = [plain.c_global(r) for r in range(c)]
+    red_ms = None
+    plain.execute(flags=binding.DMM_NO_MERGE | binding.DMM_TIMING)
+    torch.cuda.synchronize()
+    assert plain.plan.elapsed_ms()[1] >= 0.0            # the replica-sum kernel ran
+    plain.close()
+    fused = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
+    fused.execute(flags=binding.DMM_NO_MERGE | binding.DMM_FUSED_REDUCE | binding.DMM_TIMING)
+    torch.cuda.synchronize()
+    red_ms = fused.plan.elapsed_ms()[1]
+    if must_fuse:
+        assert red_ms < 0.0, "the replica-sum kernel ran although the sum was to be fused"
+    for r in range(c):
+        assert np.array_equal(want[r], fused.c_global(r)), f"replica {r} differs"
+    fused.close()
+    return want[0]
+
+
+@pytest.mark.parametrize("name,dims,ldm", [("cfg4", (1024, 1024, 1024), 8), ("cfg4", (515, 771, 1030), 1),
+                                           ("mlp1-outer", (520, 1000, 300), 1)])
+def test_fused_replica_sum_families(name, dims, ldm):
+    """The replica sum folded into the epilogue of replica 0's macro-tiles: every replica ends up with
+    bitwise the contents the GEMM + replica-sum kernel pair leaves (partials in replicas 1.., the
+    sum in replica 0), and the sum is the product."""
+    cfg = workloads.scaled_config(name, *dims)
+    A, B = workloads.make_operands(cfg)
+    C0 = _fused_against_plain(cfg, A, B, ldm)
+    _check(C0, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+
+
+@pytest.mark.parametrize("seed", [2, 3, 4, 6, 8, 13, 15, 21, 22, 27])
+@pytest.mark.parametrize("mode", ["C", "B", "A"])
+def test_fused_replica_sum_random_partitionings(seed, mode):
+    """Random grids with a replicated C (2 to 8 replicas), in all three data movement modes (with B
+    or A in place some regions of a replica are zero fill): fused = unfused, bit for bit."""
+    prob = helpers.random_problem(seed + 300, max_dim=700, allow_empty=(seed % 2 == 1))
+    if prob["C"]["replication"] == 1:
+        prob["C"] = dict(prob["C"], replication=prob["nranks"], proc_rows=1, proc_cols=1)
+    cfg = dict(prob, name=f"random-fused{seed}/{mode}", dtype="bf16" if seed % 2 else "f32", dist=("normal", 1.0),
+               seeds=(seed, seed + 900), stationary=mode)
+    if cfg["C"]["replication"] == 1:
+        pytest.skip("one rank: nothing to sum")
+    A, B = workloads.make_operands(cfg)
+    C0 = _fused_against_plain(cfg, A, B, must_fuse=False)     # (tiny problems may be cut along K instead)
+    _check(C0, omatmul.matmul(A, B, bf16=(cfg["dtype"] == "bf16")), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+
+
 # ---- error paths that reach the device entry points ---------------------------------
 
 def test_execute_rejects_bad_arguments():
