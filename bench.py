@@ -2,6 +2,8 @@
 """Benchmark of the hot path on one MI355X: plan -> grouped GEMM -> replica sum.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
+                    (cfg1..cfg5, mlp{1,2}-{column,inner,outer,2d}, bc{512,256,128};
+                     --dtype f32, --c-dtype bf16, --merge auto|always|never, --ld-multiple N)
 
 One step = one pass of the whole path over one batch of synthetic input already
 resident in HBM: ``dmm_plan`` on the descriptors (host slicing + grouping), then
@@ -16,6 +18,9 @@ The line also carries
                 launch on the launch stream (DMM_TIMING);
   roofline_replica_sum   the replica-sum kernel against peak HBM bandwidth:
                 (c + 1) * 4 bytes per C element / its average duration;
+  fused_replica_sum   (replicated C) the same plan + execute steps with DMM_FUSED_REDUCE:
+                replica 0's macro-tiles add the other replicas' partial sums in their epilogue
+                and no replica-sum kernel runs; reported beside `value`, never as it;
   cpu_baseline  the CPU oracle (fp64 triple loop, as it stands) timed on the
                 host cores on a bounded sample of rows of the same product;
   context       (bf16 workloads) what the vendor library reaches on this very box
