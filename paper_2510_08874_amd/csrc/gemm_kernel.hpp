@@ -602,18 +602,21 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // `stage`: chunks it was masked out of are read element by element, and everything at
   // k >= remaining segment length is zeroed on both operands (so that stale or non-finite
   // bytes cannot reach a sum).  Rare: K tails and tile-buffer ends only.
+  int pub_seg = 0, pub_first = 0;                        // cursor of publish_fix: a segment and the number of its first step
   auto publish_fix = [&](int t) {                        // t = number of the step being published
     if (__builtin_expect((fix_bits & 4u) == 0u, 1)) return;
     const int stage = t & 3;
-    // find the step's segment and position (the item's steps lie inside the group's sequence)
-    int seg = 0, first = 0;
+    // find the step's segment and position (the item's steps lie inside the group's sequence).
+    // Repairs come in ascending step order, so the search goes on from where the last one ended:
+    // one look at a segment's length per segment instead of one per segment per repair.
     const int t_abs = it.first_step + t;
     for (;;) {
-      const int cnt = (seg_klen(seg) + BK - 1) / BK;
-      if (t_abs < first + cnt) break;
-      first += cnt;
-      ++seg;
+      const int cnt = (seg_klen(pub_seg) + BK - 1) / BK;
+      if (t_abs < pub_first + cnt) break;
+      pub_first += cnt;
+      ++pub_seg;
     }
+    const int seg = pub_seg, first = pub_first;
     const int kpos = (t_abs - first) * BK;
     const int krem = seg_klen(seg) - kpos;
     char *sa = lds + stage * STAGE + wave * 1024 + lane * 16;
