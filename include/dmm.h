@@ -251,7 +251,7 @@ void dmm_plan_destroy(dmm_plan_t *p);
 
 const char *dmm_strerror(int status);
 int dmm_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread, 0 if none */
-int dmm_version(void);
+int dmm_version(void);         /* 2: merged macro-tiles, bf16 C tiles, fused replica sum, lazily written op list */
 
 #ifdef __cplusplus
 }

@@ -735,6 +735,6 @@ const char *dmm_strerror(int status) {
   }
 }
 
-int dmm_version(void) { return 1; }
+int dmm_version(void) { return 2; }
 
 }  // extern "C"
