@@ -6,6 +6,7 @@
 
 #include <cstring>
 #include <mutex>
+#include <new>
 #include <vector>
 
 #include "dmm.h"
@@ -35,6 +36,10 @@ struct Slab {
   char *pinned[2] = {nullptr, nullptr};
   hipEvent_t ev[2] = {nullptr, nullptr};
   size_t cap = 0;
+  // Host copy of what the device buffer holds (empty: unknown).  It stays with the slab through
+  // the pool, so a new plan whose tables equal those of a destroyed one (plan + execute in a
+  // loop over the same buffers) finds them already on the device and uploads nothing.
+  std::vector<char> *mirror = nullptr;
 };
 
 class SlabPool {
@@ -70,6 +75,11 @@ class SlabPool {
     }
     s.cap = want;
     s.device = device;
+    s.mirror = new (std::nothrow) std::vector<char>;
+    if (!s.mirror) {
+      destroy(&s);
+      return DMM_ENOMEM;
+    }
     *out = s;
     return DMM_OK;
   }
@@ -84,6 +94,7 @@ class SlabPool {
 
  private:
   static void destroy(Slab *s) {
+    delete s->mirror;
     if (s->dev) (void)hipFree(s->dev);
     for (int i = 0; i < 2; ++i) {
       if (s->pinned[i]) (void)hipHostFree(s->pinned[i]);
@@ -123,17 +134,9 @@ struct Uploader {
   Slab slab;
   bool ev_used[2] = {false, false};
   int cur = 0;
-  std::vector<char> resident;
-  bool valid = false;
 
   char *dev() const { return slab.dev; }
   int upload(const void *src, size_t bytes, hipStream_t stream, hipEvent_t busy_until = nullptr) {
-    if (valid && resident.size() == bytes && (bytes == 0 || std::memcmp(resident.data(), src, bytes) == 0)) {
-      // already resident; the caller's stream (possibly another one than last time) still has to
-      // be ordered behind the copy that put it there
-      if (bytes != 0 && ev_used[cur]) DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
-      return DMM_OK;
-    }
     if (bytes == 0) return DMM_OK;
     if (bytes > slab.cap) {
       // growing: the old slab may still be read by enqueued work of this plan
@@ -144,8 +147,16 @@ struct Uploader {
       int rc = pool().acquire(bytes, &slab);
       if (rc) return rc;
       ev_used[0] = ev_used[1] = false;
-      valid = false;
     }
+    std::vector<char> &resident = *slab.mirror;
+    if (resident.size() == bytes && std::memcmp(resident.data(), src, bytes) == 0) {
+      // already resident; the caller's stream (possibly another one than last time) still has to
+      // be ordered behind the copy that put it there, if this uploader made that copy (a copy made
+      // for an earlier owner of the slab finished before the slab went back to the pool)
+      if (ev_used[cur]) DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
+      return DMM_OK;
+    }
+    resident.clear();                      // unknown contents until the copy below has been enqueued
     cur ^= 1;
     if (ev_used[cur]) DMM_HIP(hipEventSynchronize(slab.ev[cur]));  // slot last used two uploads ago
     std::memcpy(slab.pinned[cur], src, bytes);
@@ -158,12 +169,14 @@ struct Uploader {
     DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
     ev_used[cur] = true;
     resident.assign((const char *)src, (const char *)src + bytes);
-    valid = true;
     return DMM_OK;
   }
+  // The caller guarantees that no stream work still uses the slab: in particular its last copy has
+  // completed, so the mirror describes the buffer.
   void release() {
+    // (a call that failed between the upload and its launches may have left the copy in flight)
+    if (slab.dev && ev_used[cur]) (void)hipEventSynchronize(slab.ev[cur]);
     pool().release(&slab);
-    valid = false;
   }
 };
 
