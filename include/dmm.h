@@ -129,7 +129,8 @@ typedef struct {
  * cuts of A and C, its columns into col_pieces intervals of the merged column cuts of B and C;
  * inside the macro-tile a column piece starts at a multiple of 8 columns.  One workgroup
  * accumulates it over the K-segments of the replica's share of k in ascending k, exactly as the
- * macro-tiles of dmm_plan_items do for their group, so both lists give bitwise the same C. */
+ * macro-tiles of dmm_plan_items do for their group, so both lists give bitwise the same C (except
+ * where dmm_execute cuts the last round of one list along K and not of the other: see there). */
 typedef struct {
   int64_t m0, n0;
   int32_t m_ext, n_ext;

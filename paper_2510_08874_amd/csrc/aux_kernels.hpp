@@ -143,6 +143,8 @@ struct FixItem {
   int32_t m_ext, n_ext;
   int32_t nparts;
   int32_t c_es;          // bytes per element of dst: 4 = fp32, 2 = bf16 (the sum rounded to nearest even)
+  int32_t row0, col0;    // where the region that goes to dst begins inside the partial tiles (merged macro-tiles
+                         // are written piece by piece; col0 is a multiple of 4)
 };
 constexpr int FIX_ROWS = 4;           // rows of a macro-tile one workgroup sums: 4 rows x 64 float4 columns
 
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(256) void sum_parts_kernel(const FixItem *__restric
   const int r = (blockIdx.x % (BM / FIX_ROWS)) * FIX_ROWS + (threadIdx.x >> 6);
   const int c = (threadIdx.x & 63) << 2;
   if (r >= f.m_ext || c >= f.n_ext) return;
-  const float *p = f.parts + (int64_t)r * BN + c;
+  const float *p = f.parts + (int64_t)(f.row0 + r) * BN + f.col0 + c;
   floatx4 s = __builtin_nontemporal_load((const floatx4 *)p);
   // eight runs' loads in flight at a time; the adds follow in ascending k (the order is part of the result)
   constexpr int QB = 8;

@@ -226,12 +226,31 @@ int fire_reduce(dmm_plan_t *P, const RedLaunch &L, hipStream_t stream, bool time
 // A slices are numbered (replica, row interval, segment), B slices (replica, segment, column
 // interval), C slices (replica, row interval, column interval).
 struct MergedLaunch {
-  size_t n_items = 0, o_a = 0, o_b = 0, o_c = 0, o_k = 0, total = 0;
+  size_t n_items = 0, o_a = 0, o_b = 0, o_c = 0, o_k = 0, o_fix = 0, n_fix = 0, total = 0;
 };
 
-int build_merged_tables(const dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, const void *const *a_tiles,
+constexpr int32_t MIN_RUN = 64;   // K steps a run of a macro-tile cut along K has at least (see dmm_execute)
+
+// Scratch buffer of the plan for `n_runs` partial tiles; orders this call behind the plan's last one.
+int acquire_split_buffer(dmm_plan_t *P, size_t n_runs, hipStream_t stream) {
+  // the scratch buffer is shared by all calls on this plan: order this call behind the last one
+  // (a no-op when both are on the same stream)
+  if (P->dev->last_use_recorded) DMM_HIP(hipStreamWaitEvent(stream, P->dev->last_use, 0));
+  const size_t need = n_runs * sizeof(float) * BM * BN;
+  if (need > P->dev->split_cap) {
+    // growing: earlier calls on this plan may still use the old buffer
+    if (P->dev->split_buf) {
+      DMM_HIP(hipStreamSynchronize(stream));
+      scratch_pool().release(&P->dev->split_buf, &P->dev->split_cap);
+    }
+    return scratch_pool().acquire(need, &P->dev->split_buf, &P->dev->split_cap);
+  }
+  return DMM_OK;
+}
+
+int build_merged_tables(dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, const void *const *a_tiles,
                         const int64_t *a_ld, const void *const *b_tiles, const int64_t *b_ld, void *const *c_tiles,
-                        const int64_t *c_ld, std::vector<char> *hp, MergedLaunch *L) {
+                        const int64_t *c_ld, int cus, hipStream_t stream, std::vector<char> *hp, MergedLaunch *L) {
   const Merged &G = P->merged;
   const Grid &A = P->A, &B = P->B, &C = P->C;
   const size_t MR = G.mc.size() - 1, NR = G.nc.size() - 1;
@@ -319,12 +338,70 @@ int build_merged_tables(const dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_e
     for (int32_t q = 0; q <= w.Q; ++q) d.cb[q] = (int32_t)(G.nc[(size_t)(w.nr0 + q)] - w.n0);
     items[x] = d;
   }
+  // K-split of the last round, as for the per-group macro-tiles: the last W % cus macro-tiles, if
+  // they are at most half a round, are cut into runs of at least MIN_RUN K steps; every run writes
+  // a plain partial tile to the scratch buffer, and the partial tiles of a macro-tile are added up
+  // piece by piece (one FixItem per row piece and column piece, each with its own C slice).
+  std::vector<FixItem> fixes;
+  size_t n_runs = 0;
+  const size_t n_whole = items.size();
+  const size_t tail = n_whole % (size_t)cus;
+  if (tail > 0 && tail <= (size_t)cus / 2) {
+    const int32_t max_runs = (int32_t)((size_t)cus / tail);
+    for (size_t x = n_whole - tail; x < n_whole; ++x) {
+      int32_t runs = std::min(max_runs, items[x].nsteps / MIN_RUN);
+      if (runs < 2) continue;
+      const int32_t per = (items[x].nsteps + runs - 1) / runs;
+      runs = (items[x].nsteps + per - 1) / per;
+      const CompItemDev whole = items[x];
+      const size_t first_part = n_runs;
+      for (int32_t p = 0; p < whole.R; ++p)
+        for (int32_t q = 0; q < whole.Q; ++q) {
+          const int32_t r0 = std::max(whole.rb[p], 0), r1 = std::min(whole.rb[p + 1], whole.m_ext);
+          const int32_t q0 = std::max(whole.cb[q], 0), q1 = std::min(whole.cb[q + 1], whole.n_ext);
+          const PieceDev &cp = pc[(size_t)(whole.c_first + p * whole.c_stride + q)];
+          FixItem f;
+          f.dst = (void *)(cp.ptr + (int64_t)(r0 - whole.rb[p]) * cp.pitch + (int64_t)(q0 - whole.cb[q]) * c_es);
+          f.ldc = (int64_t)cp.pitch / c_es;
+          f.parts = (const float *)(uintptr_t)(first_part * sizeof(float) * BM * BN);   // offset for now
+          f.m_ext = r1 - r0;
+          f.n_ext = q1 - q0;
+          f.nparts = runs;
+          f.c_es = (int32_t)c_es;
+          f.row0 = r0;
+          f.col0 = q0;
+          fixes.push_back(f);
+        }
+      for (int32_t j = 0; j < runs; ++j) {
+        CompItemDev r = whole;
+        r.scratch = (float *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);   // offset for now
+        r.first_step = j * per;
+        r.nsteps = std::min(per, whole.nsteps - j * per);
+        r.pad = 1;                                                                            // marks the offset
+        if (j == 0) items[x] = r;
+        else items.push_back(r);
+      }
+      n_runs += (size_t)runs;
+    }
+  }
+  if (n_runs > 0) {
+    int rc = acquire_split_buffer(P, n_runs, stream);
+    if (rc) return rc;
+    for (CompItemDev &d : items)
+      if (d.pad == 1) {
+        d.scratch = (float *)(P->dev->split_buf + (uintptr_t)d.scratch);
+        d.pad = 0;
+      }
+    for (FixItem &f : fixes) f.parts = (const float *)(P->dev->split_buf + (uintptr_t)f.parts);
+  }
   L->n_items = items.size();
+  L->n_fix = fixes.size();
   L->o_a = items.size() * sizeof(CompItemDev);
   L->o_b = L->o_a + pa.size() * sizeof(PieceDev);
   L->o_c = L->o_b + pb.size() * sizeof(PieceDev);
   L->o_k = L->o_c + pc.size() * sizeof(PieceDev);
-  L->total = (L->o_k + klen.size() * sizeof(int32_t) + 7) & ~(size_t)7;
+  L->o_fix = (L->o_k + klen.size() * sizeof(int32_t) + 7) & ~(size_t)7;
+  L->total = L->o_fix + fixes.size() * sizeof(FixItem);
   std::vector<char> &h = *hp;
   h.assign(L->total, 0);
   std::memcpy(h.data(), items.data(), items.size() * sizeof(CompItemDev));
@@ -332,6 +409,7 @@ int build_merged_tables(const dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_e
   std::memcpy(h.data() + L->o_b, pb.data(), pb.size() * sizeof(PieceDev));
   std::memcpy(h.data() + L->o_c, pc.data(), pc.size() * sizeof(PieceDev));
   std::memcpy(h.data() + L->o_k, klen.data(), klen.size() * sizeof(int32_t));
+  if (!fixes.empty()) std::memcpy(h.data() + L->o_fix, fixes.data(), fixes.size() * sizeof(FixItem));
   return DMM_OK;
 }
 
@@ -432,7 +510,10 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       MergedLaunch ml;
       std::vector<char> &h = P->dev->host;
       h.clear();
-      if ((rc = build_merged_tables(P, es, bk, c_es, a_tiles, a_ld, b_tiles, b_ld, c_tiles, c_ld, &h, &ml))) return rc;
+      int cus = 0;
+      if ((rc = device_cus(&cus))) return rc;
+      if ((rc = build_merged_tables(P, es, bk, c_es, a_tiles, a_ld, b_tiles, b_ld, c_tiles, c_ld, cus, stream, &h, &ml)))
+        return rc;
       if (!(flags & DMM_NO_REDUCE) && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, ml.total, &red))) return rc;
       if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
       char *d = P->dev->gemm_table.dev();
@@ -450,6 +531,11 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
                            (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a), (const PieceDev *)(d + ml.o_b),
                            (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
       DMM_HIP(hipGetLastError());
+      if (ml.n_fix > 0) {
+        hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(ml.n_fix * (BM / FIX_ROWS))), dim3(256), 0, stream,
+                           (const FixItem *)(d + ml.o_fix));
+        DMM_HIP(hipGetLastError());
+      }
       if (timed) {
         DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
         P->dev->gemm_timed = true;
@@ -521,7 +607,6 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
     // go to the end; all of them write to the scratch buffer.  A run pays a prologue and an
     // epilogue of its own (about 13 K steps' worth) and the pass that adds the runs up is one more
     // launch: measured, runs of 32 steps lose (2048^3: 45 -> 66 us), so a run is 64 steps at least.
-    constexpr int32_t MIN_RUN = 64;
     int cus = 0;
     if ((rc = device_cus(&cus))) return rc;
     size_t working = 0;
@@ -547,6 +632,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         f.n_ext = whole.n_ext;
         f.nparts = runs;
         f.c_es = whole.c_es;
+        f.row0 = f.col0 = 0;
         fixes.push_back(f);
         for (int32_t j = 0; j < runs; ++j) {
           ItemDev r = whole;
@@ -562,18 +648,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       }
     }
     if (n_runs > 0) {
-      // the scratch buffer is shared by all calls on this plan: order this call behind the last one
-      // (a no-op when both are on the same stream)
-      if (P->dev->last_use_recorded) DMM_HIP(hipStreamWaitEvent(stream, P->dev->last_use, 0));
-      const size_t need = n_runs * sizeof(float) * BM * BN;
-      if (need > P->dev->split_cap) {
-        // growing: earlier calls on this plan may still use the old buffer
-        if (P->dev->split_buf) {
-          DMM_HIP(hipStreamSynchronize(stream));
-          scratch_pool().release(&P->dev->split_buf, &P->dev->split_cap);
-        }
-        if ((rc = scratch_pool().acquire(need, &P->dev->split_buf, &P->dev->split_cap))) return rc;
-      }
+      if ((rc = acquire_split_buffer(P, n_runs, stream))) return rc;
       for (ItemDev &d : hi)
         if (d.c_es < 0) {
           d.c = (void *)(P->dev->split_buf + (uintptr_t)d.c);

@@ -115,6 +115,10 @@ struct CompItemDev {     // one merged macro-tile
   int32_t rb[PMAX + 1];        // first row of every row piece relative to the macro-tile (rb[0] <= 0: the
                                // first piece may begin above it), rb[R] >= m_ext
   int32_t cb[PMAX + 1];        // likewise for the column pieces
+  float *scratch;              // a run of K steps of a macro-tile cut along K: its partial sums go here, as a
+                               // plain 256-wide fp32 tile, instead of to the C slices (null otherwise)
+  int32_t first_step;          // where the run starts in the macro-tile's step sequence
+  int32_t pad;
 };
 
 struct CompCtx {         // a merged macro-tile's descriptors, staged in LDS behind the stages
@@ -1038,7 +1042,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
     it.m_off = it.n_off = 0;
     it.m_ext = m_ext;
     it.n_ext = n_ext;
-    it.first_step = 0;
+    it.first_step = ci->first_step;
     it.c_es = ci->c_es;
     it.red_first = it.red_count = 0;
     CompCtx cx;
@@ -1056,6 +1060,24 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
   }
 
   // ---- epilogue ------------------------------------------------------------------------------
+  if (ci->scratch) {
+    // a run of a macro-tile cut along K: partial sums to the scratch tile, to be added up later
+    float *out = ci->scratch;
+    const int row0 = wm * WTM + 4 * (lane >> 5);
+    const int col0 = wn * WTN + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
+        if (row < m_ext) {
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+            if (col0 + j * 32 < n_ext) __builtin_nontemporal_store(acc[i][j][r], out + row * BN + col0 + j * 32);
+        }
+      }
+    return;
+  }
   __syncthreads();                                        // every wave is out of the K loop: the stages are free
   uint64_t *rowbase = (uint64_t *)lds;                    // [256][PMAX]: address of (row, first column of piece q)
   {
