@@ -264,6 +264,7 @@ int build_merged_tables(dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, con
   std::vector<PieceDev> pa, pb, pc;
   std::vector<int32_t> klen;
   std::vector<int32_t> a0(G.reps.size()), b0(G.reps.size()), c0(G.reps.size()), k0(G.reps.size()), steps(G.reps.size());
+  std::vector<std::vector<int32_t>> steps_before(G.reps.size());   // K steps in front of every segment, per replica
   auto piece = [](const void *base, int64_t ld, int64_t r, int64_t c, int64_t h, int64_t w, int64_t esz) {
     PieceDev d;
     const int64_t off = r * ld + c;
@@ -286,8 +287,10 @@ int build_merged_tables(dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, con
       a_tj[s] = holder(A.cc, R.kc[s]);
       b_ti[s] = holder(B.rc, R.kc[s]);
       klen.push_back((int32_t)(R.kc[s + 1] - R.kc[s]));
+      steps_before[rep].push_back(nsteps);
       nsteps += (int32_t)((R.kc[s + 1] - R.kc[s] + bk - 1) / bk);
     }
+    steps_before[rep].push_back(nsteps);
     steps[rep] = nsteps;
     for (size_t i = 0; i < MR; ++i)
       for (size_t s = 0; s < S; ++s) {
@@ -345,45 +348,96 @@ int build_merged_tables(dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, con
   std::vector<FixItem> fixes;
   size_t n_runs = 0;
   const size_t n_whole = items.size();
-  const size_t tail = n_whole % (size_t)cus;
-  if (tail > 0 && tail <= (size_t)cus / 2) {
-    const int32_t max_runs = (int32_t)((size_t)cus / tail);
-    for (size_t x = n_whole - tail; x < n_whole; ++x) {
-      int32_t runs = std::min(max_runs, items[x].nsteps / MIN_RUN);
-      if (runs < 2) continue;
-      const int32_t per = (items[x].nsteps + runs - 1) / runs;
-      runs = (items[x].nsteps + per - 1) / per;
-      const CompItemDev whole = items[x];
-      const size_t first_part = n_runs;
-      for (int32_t p = 0; p < whole.R; ++p)
-        for (int32_t q = 0; q < whole.Q; ++q) {
-          const int32_t r0 = std::max(whole.rb[p], 0), r1 = std::min(whole.rb[p + 1], whole.m_ext);
-          const int32_t q0 = std::max(whole.cb[q], 0), q1 = std::min(whole.cb[q + 1], whole.n_ext);
-          const PieceDev &cp = pc[(size_t)(whole.c_first + p * whole.c_stride + q)];
-          FixItem f;
-          f.dst = (void *)(cp.ptr + (int64_t)(r0 - whole.rb[p]) * cp.pitch + (int64_t)(q0 - whole.cb[q]) * c_es);
-          f.ldc = (int64_t)cp.pitch / c_es;
-          f.parts = (const float *)(uintptr_t)(first_part * sizeof(float) * BM * BN);   // offset for now
-          f.m_ext = r1 - r0;
-          f.n_ext = q1 - q0;
-          f.nparts = runs;
-          f.c_es = (int32_t)c_es;
-          f.row0 = r0;
-          f.col0 = q0;
-          fixes.push_back(f);
-        }
-      for (int32_t j = 0; j < runs; ++j) {
-        CompItemDev r = whole;
-        r.scratch = (float *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);   // offset for now
-        r.first_step = j * per;
-        r.nsteps = std::min(per, whole.nsteps - j * per);
-        r.pad = 1;                                                                            // marks the offset
-        if (j == 0) items[x] = r;
-        else items.push_back(r);
+  // one FixItem per (row piece, column piece) of a macro-tile whose `runs` partial tiles start at
+  // partial tile number `first_part`
+  auto fix_pieces = [&](const CompItemDev &whole, size_t first_part, int32_t runs) {
+    for (int32_t p = 0; p < whole.R; ++p)
+      for (int32_t q = 0; q < whole.Q; ++q) {
+        const int32_t r0 = std::max(whole.rb[p], 0), r1 = std::min(whole.rb[p + 1], whole.m_ext);
+        const int32_t q0 = std::max(whole.cb[q], 0), q1 = std::min(whole.cb[q + 1], whole.n_ext);
+        const PieceDev &cp = pc[(size_t)(whole.c_first + p * whole.c_stride + q)];
+        FixItem f;
+        f.dst = (void *)(cp.ptr + (int64_t)(r0 - whole.rb[p]) * cp.pitch + (int64_t)(q0 - whole.cb[q]) * c_es);
+        f.ldc = (int64_t)cp.pitch / c_es;
+        f.parts = (const float *)(uintptr_t)(first_part * sizeof(float) * BM * BN);   // offset for now
+        f.m_ext = r1 - r0;
+        f.n_ext = q1 - q0;
+        f.nparts = runs;
+        f.c_es = (int32_t)c_es;
+        f.row0 = r0;
+        f.col0 = q0;
+        fixes.push_back(f);
       }
-      n_runs += (size_t)runs;
-    }
+  };
+  // Cutting macro-tiles along K.  Two reasons, one mechanism: (a) the plan asks for it (G.window:
+  // the descriptors of all of a macro-tile's segments would not fit beside eight pieces per axis),
+  // (b) the macro-tiles fill the device badly: at most half a round of them in all, or a last round
+  // that is at most half full (then its macro-tiles only), as for the per-group macro-tiles.  A run
+  // is a range of at least MIN_RUN K steps; its workgroup stages the descriptors of the segments
+  // the range touches only, starts `first_step` steps into the first of them and writes a plain
+  // partial tile.  Launch order: the first run of every macro-tile in the macro-tiles' own order,
+  // then the second of every one, ...
+  auto desc_bytes = [](int64_t segs, int64_t pieces) { return 4 * ((segs + 3) & ~(int64_t)3) + 24 * segs * pieces; };
+  std::vector<int32_t> want(n_whole, 1);                 // runs wanted per macro-tile
+  size_t total = 0;
+  for (size_t x = 0; x < n_whole; ++x) {
+    if (G.window > 0 && items[x].S > G.window) want[x] = (items[x].S + G.window - 1) / G.window;
+    total += (size_t)want[x];
   }
+  if (total <= (size_t)cus / 2) {
+    const int32_t f = (int32_t)((size_t)cus / total);
+    for (size_t x = 0; x < n_whole; ++x) want[x] *= f;
+  } else if (G.window == 0) {
+    const size_t tail = n_whole % (size_t)cus;
+    if (tail > 0 && tail <= (size_t)cus / 2)
+      for (size_t x = n_whole - tail; x < n_whole; ++x) want[x] = (int32_t)((size_t)cus / tail);
+  }
+  std::vector<CompItemDev> later;
+  for (size_t x = 0; x < n_whole; ++x) {
+    const CompItemDev whole = items[x];
+    const std::vector<int32_t> &before = steps_before[(size_t)G.items[x].rep];
+    const int32_t least = G.window > 0 && whole.S > G.window ? (whole.S + G.window - 1) / G.window : 1;
+    int32_t runs = std::max(least, std::min(want[x], whole.nsteps / MIN_RUN));
+    if (runs < 2) continue;
+    // ranges of `per` steps; more runs if some range touches more segments than fit
+    int32_t per = 0;
+    for (;; ++runs) {
+      per = (whole.nsteps + runs - 1) / runs;
+      bool fits = true;
+      for (int32_t t0 = 0; t0 < whole.nsteps && fits; t0 += per) {
+        const int32_t t1 = std::min(t0 + per, whole.nsteps);
+        const int64_t lo = std::upper_bound(before.begin(), before.end(), t0) - before.begin() - 1;
+        const int64_t hi = std::upper_bound(before.begin(), before.end(), t1 - 1) - before.begin() - 1;
+        fits = desc_bytes(hi - lo + 1, whole.R + whole.Q) <= kDescBytes;
+      }
+      if (fits || per == 1) break;
+    }
+    runs = (whole.nsteps + per - 1) / per;
+    if (runs < 2) continue;
+    fix_pieces(whole, n_runs, runs);
+    for (int32_t j = 0; j < runs; ++j) {
+      const int32_t t0 = j * per, t1 = std::min(t0 + per, whole.nsteps);
+      const int32_t lo = (int32_t)(std::upper_bound(before.begin(), before.end(), t0) - before.begin()) - 1;
+      const int32_t hi = (int32_t)(std::upper_bound(before.begin(), before.end(), t1 - 1) - before.begin()) - 1;
+      CompItemDev r = whole;
+      r.S = hi - lo + 1;
+      r.a_first = whole.a_first + lo;
+      r.b_first = whole.b_first + lo * whole.b_stride;
+      r.k_first = whole.k_first + lo;
+      r.first_step = t0 - before[(size_t)lo];
+      r.nsteps = t1 - t0;
+      r.scratch = (float *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);   // offset for now
+      r.pad = 1 + j;                                                                        // marks the offset; run number + 1
+      if (j == 0) items[x] = r;
+      else later.push_back(r);
+    }
+    n_runs += (size_t)runs;
+  }
+  std::stable_sort(later.begin(), later.end(), [](const CompItemDev &a, const CompItemDev &b) { return a.pad < b.pad; });
+  for (CompItemDev &r : later) r.pad = 1;
+  for (CompItemDev &r : items)
+    if (r.pad > 0) r.pad = 1;
+  items.insert(items.end(), later.begin(), later.end());
   if (n_runs > 0) {
     int rc = acquire_split_buffer(P, n_runs, stream);
     if (rc) return rc;

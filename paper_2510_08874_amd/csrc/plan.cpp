@@ -560,7 +560,7 @@ void build_merged(dmm_plan_t *P, uint32_t flags) {
   G.mc = merged_cuts({&A.rc, &C.rc});
   G.nc = merged_cuts({&B.cc, &C.cc});
   const std::vector<int64_t> kall = merged_cuts({&A.cc, &B.rc});
-  int64_t cap = kMaxPieces;
+  int64_t cap = kMaxPieces, longest = 0;
   for (int32_t rep = 0; rep < C.c; ++rep) {
     const int64_t lo = (int64_t)rep * K / C.c, hi = ((int64_t)rep + 1) * K / C.c;
     if (lo >= hi) return;             // an empty share: that replica is zero-filled, not multiplied
@@ -573,7 +573,15 @@ void build_merged(dmm_plan_t *P, uint32_t flags) {
     R.b_rep = rep / (C.c / B.c);
     const int64_t S = (int64_t)R.kc.size() - 1;
     cap = std::min(cap, (kDescBytes - 4 * ((S + 3) & ~(int64_t)3)) / (48 * S));
+    longest = std::max(longest, S);
     G.reps.push_back(std::move(R));
+  }
+  if (cap < kMinPieces && longest > kSegWindow) {
+    // many short segments (K long against the tiles): rather than small macro-tiles, full ones that
+    // are run kSegWindow segments at a time
+    static_assert(4 * kSegWindow + 48 * kSegWindow * kMaxPieces <= kDescBytes, "a window of segments with all pieces fits");
+    G.window = kSegWindow;
+    cap = kMaxPieces;
   }
   if (cap < 1) return;
   {

@@ -50,8 +50,16 @@ struct MergedItem {
   int32_t mr0, R, nr0, Q;             // first row interval, row pieces, first column interval, column pieces
 };
 
+constexpr int32_t kSegWindow = 64;    // segments a macro-tile is run on at a time where all of them would crowd
+                                      // out the pieces (see Merged::window)
+constexpr int32_t kMinPieces = 6;     // ... which is when fewer than this many pieces per axis would fit
+
 struct Merged {
   bool valid = false;
+  // 0: a macro-tile's workgroup walks all K-segments of its replica.  Otherwise the descriptors of
+  // all segments would leave room for fewer than kMinPieces pieces per axis, and the executor runs
+  // every macro-tile in windows of at most this many segments, whose partial tiles it adds up.
+  int32_t window = 0;
   std::vector<int64_t> mc, nc;        // merged row cuts of A and C, merged column cuts of B and C
   std::vector<MergedRep> reps;
   std::vector<MergedItem> items;      // launch order

@@ -560,6 +560,11 @@ def _same_bits_expected(plan, cfg):
         lo, hi = r * cfg["K"] // c, (r + 1) * cfg["K"] // c
         pts = [lo] + [x for x in cuts if lo < x < hi] + [hi]
         steps = max(steps, sum(-(-(b - a) // bk) for a, b in zip(pts, pts[1:])))
+        # more than 64 segments whose descriptors would leave room for fewer than 6 pieces per axis:
+        # the merged macro-tiles are run 64 segments at a time and their partial tiles added up
+        S = len(pts) - 1
+        if plan.num_merged_items() and S > 64 and (30720 - 4 * ((S + 3) // 4 * 4)) // (48 * S) < 6:
+            return False
     if steps < 128:
         return True
     return all(n % cus == 0 or n % cus > cus // 2 for n in (plan.num_merged_items(), plan.num_items()))
@@ -580,7 +585,8 @@ def _bc(dims, nb, dtype, reps=(1, 1, 1), p=8):
     ((700, 333, 517), 96, "bf16", 1, (1, 1, 1), 8),        # macro-tiles start inside tiles; odd leading dimensions; K tails
     ((700, 333, 517), 96, "f32", 1, (1, 1, 1), 8),
     ((520, 200, 530), 40, "bf16", 8, (1, 1, 1), 8),        # seven pieces per axis
-    ((300, 4100, 300), 24, "bf16", 1, (1, 1, 1), 8),       # 171 segments: the descriptor area caps a macro-tile at 3 x 3 pieces
+    ((300, 4100, 300), 24, "bf16", 1, (1, 1, 1), 8),       # 171 segments: too many to stage at once, run in three windows of 64
+    ((200, 9000, 300), 40, "f32", 1, (1, 2, 2), 16),       # the same with two replicas (113 segments each) and the replica sum
     ((640, 900, 512), 64, "bf16", 1, (2, 2, 2), 16),       # replicated: every replica its share of k, then the replica sum
     ((640, 900, 512), 64, "f32", 4, (1, 2, 4), 32),        # C replicas read different replicas of B, all the one A
     ((515, 130, 260), 100, "bf16", 1, (1, 1, 1), 8),       # cuts at 100, 200: column pieces not at multiples of 8: tiles end there

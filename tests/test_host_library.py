@@ -302,6 +302,12 @@ def test_merged_items_of_named_workloads():
     plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"])
     assert plan.num_merged_items() == 3 * 3 and plan.num_items() == 8 * 6
     _check_merged(plan, cfg)
+    # many short segments: full macro-tiles (to be run in windows of segments), not small ones
+    long_k = workloads._block_cyclic(24, 300, 4100, 300)
+    lp = binding.Plan(long_k["A"], long_k["B"], long_k["C"], long_k["nranks"])
+    assert [(it["m_ext"], it["row_pieces"]) for it in lp.merged_items() if it["n0"] == 0 and it["m0"] in (0, 192)] == [(192, 8), (108, 5)]
+    _check_merged(lp, long_k)
+    lp.destroy()
     # Stationary B / A plans: the same list while nothing is replicated, none otherwise
     for mode in ("B", "A"):
         other = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], binding.STATIONARY_FLAGS[mode])

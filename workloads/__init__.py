@@ -173,6 +173,7 @@ def _block_cyclic(nb: int, M: int = 8192, K: int = 8192, N: int = 8192) -> Dict:
 _BUILDERS = dict(cfg1=_cfg1, cfg2=_cfg2, cfg3=_cfg3, cfg4=_cfg4, cfg5=_cfg5)
 CONFIG_NAMES = tuple(_BUILDERS)
 BLOCK_CYCLIC_NAMES = tuple(f"bc{nb}" for nb in BLOCK_CYCLIC_NB)
+BLOCK_CYCLIC_FINE_NAMES = ("bc64", "bc32")      # 2.1 M and 16.8 M ops: for the benchmark, not for the CPU tests
 MLP_NAMES = tuple(f"mlp{layer}-{part}" for layer in (1, 2) for part in MLP_PARTITIONINGS)
 
 
@@ -182,7 +183,7 @@ def config(name: str) -> Dict:
     if name in MLP_NAMES:
         layer, part = name.split("-")
         return _mlp(int(layer[3:]), part)
-    if name in BLOCK_CYCLIC_NAMES:
+    if name in BLOCK_CYCLIC_NAMES or name in BLOCK_CYCLIC_FINE_NAMES:
         return _block_cyclic(int(name[2:]))
     raise KeyError(name)
 
