@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY (see the package docstring).  Plain Python, integer
 arithmetic only, no blocking or shortcuts: ``overlapping_tiles`` scans every
-tile of the grid, op generation is the loop nest of Algorithm 1.
+tile of the grid, op generation narrows a box of the (m, k, n) index space tile by tile.
 
 What follows the paper, and where:
 
@@ -10,11 +10,12 @@ What follows the paper, and where:
   process grid, ScaLAPACK convention, Section 2.1) + replication factor c, with
   c replicas each laid out over p/c processes.
 * ``grid_shape / tile_bounds / overlapping_tiles`` -- Table 1.
-* ``gen_ops_stationary_c``       -- Algorithm 1, with the change Section 4.1
+* ``ops_of_rank``                -- what Algorithm 1 (Stationary C), Algorithm 2
+  (Stationary B) and its mirror image (Stationary A; Section 4.1 calls it
+  analogous and omits it) compute for one process, with the change Section 4.1
   asks for when the stationary matrix is replicated: replica r searches only
-  its 1/c share of the inner dimension and every k-bound is clipped to it.
-* ``gen_ops_stationary_b``       -- Algorithm 2; ``gen_ops_stationary_a`` is its mirror
-  image (Section 4.1 calls it analogous and omits it).
+  its 1/c share of the dimension that matrix does not index, and every bound on
+  that axis is clipped to the share.
 * ``reorder``                    -- not in the paper: the plain definition
   (a stable sort) of the grouping by output sub-tile that the GPU path uses.
 
@@ -191,125 +192,76 @@ def validate_problem(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int) -> Non
         raise PlanError("ESHAPE", "shapes do not form C[m,n] = A[m,k] B[k,n]")
 
 
-def k_share(replica: int, K: int, c: int) -> Interval:
+def replica_share(replica: int, extent: int, c: int) -> Interval:
     """Section 4.1: replica r of a c-fold replicated stationary matrix works on
-    1/c of the inner dimension (of M or N when B or A is the stationary matrix)."""
-    return ((replica * K) // c, ((replica + 1) * K) // c)
+    1/c of the dimension that matrix does not index (the inner dimension when C
+    stays in place; M for B, N for A): elements [floor(r L / c), floor((r+1) L / c))."""
+    return ((replica * extent) // c, ((replica + 1) * extent) // c)
 
 
-def gen_ops_stationary_c(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, rank: int) -> List[Task]:
-    """Algorithm 1 for one process, plus the replication rule of Section 4.1."""
-    ops: List[Task] = []
-    K = A.cols
-    c_rep = C.replica_of(rank, p)
-    a_rep = A.replica_of(rank, p)   # "its local replica" (Sections 3, 4.2)
-    b_rep = B.replica_of(rank, p)
-    share = k_share(c_rep, K, C.replication)
-    gr, gc = C.grid_shape()
-    for i in range(gr):
-        for j in range(gc):
-            if C.owner((i, j), c_rep, p) != rank:
+# A product C = A B runs over the index space (m, k, n).  Each matrix sees two of the three axes
+# (rows, columns); the third is the one its replicas share out between them.
+_AXES = {"A": ("m", "k"), "B": ("k", "n"), "C": ("m", "n")}
+# Whichever matrix stays in place, the other two are searched in the order A before B before C
+# (Algorithm 1: A tiles, then B tiles; Algorithm 2: A tiles, then C tiles; its mirror image for a
+# stationary A: B tiles, then C tiles).
+_SEARCHED = {"C": ("A", "B"), "B": ("A", "C"), "A": ("B", "C")}
+
+Box = dict   # axis name -> half-open interval
+
+
+def _view(box: Box, name: str) -> Slice2D:
+    """The 2-D slice of matrix ``name`` that the box touches."""
+    r, c = _AXES[name]
+    return (box[r], box[c])
+
+
+def _narrow(box: Box, name: str, tile: Slice2D) -> Box:
+    """The part of the box inside a tile of matrix ``name`` (``bound`` on the two axes it sees)."""
+    r, c = _AXES[name]
+    out = dict(box)
+    out[r] = bound(box[r], tile[0])
+    out[c] = bound(box[c], tile[1])
+    return out
+
+
+def ops_of_rank(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, rank: int, stationary: str = "C") -> List[Task]:
+    """The ops one process performs (Algorithm 1 for ``stationary == "C"``, Algorithm 2 for "B",
+    its mirror image for "A"), with the replication rule of Section 4.1.
+
+    Slicing, stated on boxes of the (m, k, n) index space: the process starts from the whole
+    space, cut down to its replica's share of the axis the stationary matrix does not see.  Each
+    stationary tile it owns narrows that box on the tile's two axes; every tile of the first
+    searched matrix that meets the box narrows it further; every tile of the second searched
+    matrix that meets what is left narrows it to the box of one op.  The tiles of the searched
+    matrices are taken from the process' local replicas (Section 3)."""
+    mats = {"A": A, "B": B, "C": C}
+    rep = {name: X.replica_of(rank, p) for name, X in mats.items()}
+    S = mats[stationary]
+    whole: Box = {"m": (0, A.rows), "k": (0, A.cols), "n": (0, B.cols)}
+    (shared_axis,) = set(whole) - set(_AXES[stationary])
+    whole[shared_axis] = replica_share(rep[stationary], whole[shared_axis][1], S.replication)
+    first, second = _SEARCHED[stationary]
+    out: List[Task] = []
+    rows, cols = S.grid_shape()
+    for ti in range(rows):
+        for tj in range(cols):
+            if S.owner((ti, tj), rep[stationary], p) != rank:
                 continue
-            c_bounds = C.tile_bounds((i, j))
-            # tiles of A(rows of my C tile, my share of 0:k)
-            a_tiles = A.overlapping_tiles((c_bounds[0], share), a_rep)
-            for a_idx in a_tiles:
-                a_bounds = A.tile_bounds(a_idx)
-                # tiles of B(the k range of this A tile, columns of my C tile)
-                b_tiles = B.overlapping_tiles((bound(a_bounds[1], share), c_bounds[1]), b_rep)
-                for b_idx in b_tiles:
-                    b_bounds = B.tile_bounds(b_idx)
-                    m_bound = bound(c_bounds[0], a_bounds[0])
-                    k_bound = bound(bound(a_bounds[1], b_bounds[0]), share)
-                    n_bound = bound(b_bounds[1], c_bounds[1])
-                    if is_empty(m_bound) or is_empty(k_bound) or is_empty(n_bound):
+            mine = _narrow(whole, stationary, S.tile_bounds((ti, tj)))
+            for t1 in mats[first].overlapping_tiles(_view(mine, first), rep[first]):
+                with_first = _narrow(mine, first, mats[first].tile_bounds(t1))
+                for t2 in mats[second].overlapping_tiles(_view(with_first, second), rep[second]):
+                    op = _narrow(with_first, second, mats[second].tile_bounds(t2))
+                    if is_empty(op["m"]) or is_empty(op["k"]) or is_empty(op["n"]):
                         continue
-                    ops.append(Task(rank, a_rep, a_idx[0], a_idx[1],
-                                    b_rep, b_idx[0], b_idx[1],
-                                    c_rep, i, j,
-                                    m_bound[0], m_bound[1],
-                                    k_bound[0], k_bound[1],
-                                    n_bound[0], n_bound[1]))
-    return ops
-
-
-def gen_ops_stationary_b(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, rank: int) -> List[Task]:
-    """Algorithm 2 for one process: its tiles of B stay in place.
-
-    A replicated B splits M between its replicas (see the module docstring)."""
-    ops: List[Task] = []
-    M = A.rows
-    b_rep = B.replica_of(rank, p)
-    a_rep = A.replica_of(rank, p)
-    c_rep = C.replica_of(rank, p)
-    share = k_share(b_rep, M, B.replication)         # this replica's rows of A and C
-    gr, gc = B.grid_shape()
-    for k in range(gr):
-        for j in range(gc):
-            if B.owner((k, j), b_rep, p) != rank:
-                continue
-            b_bounds = B.tile_bounds((k, j))
-            # tiles of A(my share of the rows, the k range of my B tile)
-            a_tiles = A.overlapping_tiles((share, b_bounds[0]), a_rep)
-            for a_idx in a_tiles:
-                a_bounds = A.tile_bounds(a_idx)
-                # tiles of C this product updates: rows of the A tile, columns of my B tile
-                c_tiles = C.overlapping_tiles((bound(a_bounds[0], share), b_bounds[1]), c_rep)
-                for c_idx in c_tiles:
-                    c_bounds = C.tile_bounds(c_idx)
-                    m_bound = bound(bound(c_bounds[0], a_bounds[0]), share)
-                    k_bound = bound(a_bounds[1], b_bounds[0])
-                    n_bound = bound(b_bounds[1], c_bounds[1])
-                    if is_empty(m_bound) or is_empty(k_bound) or is_empty(n_bound):
-                        continue
-                    ops.append(Task(rank, a_rep, a_idx[0], a_idx[1],
-                                    b_rep, k, j,
-                                    c_rep, c_idx[0], c_idx[1],
-                                    m_bound[0], m_bound[1],
-                                    k_bound[0], k_bound[1],
-                                    n_bound[0], n_bound[1]))
-    return ops
-
-
-def gen_ops_stationary_a(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, rank: int) -> List[Task]:
-    """The mirror image of Algorithm 2: the process' tiles of A stay in place.
-
-    A replicated A splits N between its replicas (see the module docstring)."""
-    ops: List[Task] = []
-    N = B.cols
-    a_rep = A.replica_of(rank, p)
-    b_rep = B.replica_of(rank, p)
-    c_rep = C.replica_of(rank, p)
-    share = k_share(a_rep, N, A.replication)         # this replica's columns of B and C
-    gr, gc = A.grid_shape()
-    for i in range(gr):
-        for l in range(gc):
-            if A.owner((i, l), a_rep, p) != rank:
-                continue
-            a_bounds = A.tile_bounds((i, l))
-            # tiles of B(the k range of my A tile, my share of the columns)
-            b_tiles = B.overlapping_tiles((a_bounds[1], share), b_rep)
-            for b_idx in b_tiles:
-                b_bounds = B.tile_bounds(b_idx)
-                # tiles of C this product updates: rows of my A tile, columns of the B tile
-                c_tiles = C.overlapping_tiles((a_bounds[0], bound(b_bounds[1], share)), c_rep)
-                for c_idx in c_tiles:
-                    c_bounds = C.tile_bounds(c_idx)
-                    m_bound = bound(c_bounds[0], a_bounds[0])
-                    k_bound = bound(a_bounds[1], b_bounds[0])
-                    n_bound = bound(bound(b_bounds[1], c_bounds[1]), share)
-                    if is_empty(m_bound) or is_empty(k_bound) or is_empty(n_bound):
-                        continue
-                    ops.append(Task(rank, a_rep, i, l,
-                                    b_rep, b_idx[0], b_idx[1],
-                                    c_rep, c_idx[0], c_idx[1],
-                                    m_bound[0], m_bound[1],
-                                    k_bound[0], k_bound[1],
-                                    n_bound[0], n_bound[1]))
-    return ops
-
-
-_GENERATORS = {"C": gen_ops_stationary_c, "B": gen_ops_stationary_b, "A": gen_ops_stationary_a}
+                    tile = {stationary: (ti, tj), first: t1, second: t2}
+                    out.append(Task(rank,
+                                    rep["A"], tile["A"][0], tile["A"][1],
+                                    rep["B"], tile["B"][0], tile["B"][1],
+                                    rep["C"], tile["C"][0], tile["C"][1],
+                                    op["m"][0], op["m"][1], op["k"][0], op["k"][1], op["n"][0], op["n"][1]))
+    return out
 
 
 def stationary_tile(t: Task, stationary: str) -> Tuple[int, int]:
@@ -341,10 +293,9 @@ def plan(A: DistMatrix, B: DistMatrix, C: DistMatrix, p: int, stationary: str = 
     ``stationary`` names the data movement strategy of Section 4: the matrix
     whose tiles stay in place and decide which process performs an op."""
     validate_problem(A, B, C, p)
-    gen = _GENERATORS[stationary]
     tasks: List[Task] = []
     for rank in range(p):
-        ops = gen(A, B, C, p, rank)
+        ops = ops_of_rank(A, B, C, p, rank, stationary)
         if iteration_offset:
             ops = apply_iteration_offset(ops, stationary)
         tasks.extend(ops)

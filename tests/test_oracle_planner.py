@@ -270,7 +270,7 @@ def test_wrong_share_rule_is_caught(monkeypatch):
     """A replica that searches all of k (ignoring Section 4.1's 1/c rule) does
     the whole product c times over."""
     A, B, C, p = _misaligned()
-    monkeypatch.setattr(planner, "k_share", lambda r, K, c: (0, K))
+    monkeypatch.setattr(planner, "replica_share", lambda r, K, c: (0, K))
     tasks = planner.plan(A, B, C, p)
     with pytest.raises(AssertionError):
         helpers.check_task_list(tasks, A, B, C, p)
@@ -354,7 +354,7 @@ def test_wrong_split_dimension_is_caught(monkeypatch, mode):
     C = DistMatrix(12, 10, (0, 4, 12), (0, 6, 10), 2, 2, 1)
     good = planner.plan(A, B, C, 8, stationary=mode)
     helpers.check_task_list(good, A, B, C, 8, stationary=mode)
-    monkeypatch.setattr(planner, "k_share", lambda r, L, c: (0, L))
+    monkeypatch.setattr(planner, "replica_share", lambda r, L, c: (0, L))
     bad = planner.plan(A, B, C, 8, stationary=mode)
     with pytest.raises(AssertionError):
         helpers.check_task_list(bad, A, B, C, 8, stationary=mode)
