@@ -775,18 +775,17 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       for (int l = 0; l < 2; ++l) {
         if (part[l][1] == 0) continue;
         const bool sums = fuse && l == 1;       // the launch whose macro-tiles add the other replicas' partial sums
+        // one workgroup per CU at most: workgroup w walks items w, w + grid, w + 2 grid, ... of its launch
+        const int count = (int)part[l][1];
+        const dim3 grid((unsigned)std::min(count, cus));
         if (dtype == DMM_BF16 && !sums)
-          hipLaunchKernelGGL((grouped_gemm_kernel<2, false>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
-                             di + part[l][0], ds, dr);
+          hipLaunchKernelGGL((grouped_gemm_kernel<2, false>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
         else if (dtype == DMM_BF16)
-          hipLaunchKernelGGL((grouped_gemm_kernel<2, true>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
-                             di + part[l][0], ds, dr);
+          hipLaunchKernelGGL((grouped_gemm_kernel<2, true>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
         else if (!sums)
-          hipLaunchKernelGGL((grouped_gemm_kernel<4, false>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
-                             di + part[l][0], ds, dr);
+          hipLaunchKernelGGL((grouped_gemm_kernel<4, false>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
         else
-          hipLaunchKernelGGL((grouped_gemm_kernel<4, true>), dim3((unsigned)part[l][1]), dim3(NT), LDS_BYTES, stream,
-                             di + part[l][0], ds, dr);
+          hipLaunchKernelGGL((grouped_gemm_kernel<4, true>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
         DMM_HIP(hipGetLastError());
       }
       if (!fixes.empty()) {

@@ -152,8 +152,10 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4_t *lds_short4_ptr;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(3))) char *lds_cptr;
 // Pointers read from the work table would otherwise be treated as generic (flat) addresses.
 typedef const __attribute__((address_space(1))) char *gptr;
 typedef __attribute__((address_space(1))) float *gfloat_ptr;
@@ -183,7 +185,7 @@ struct FragSet<2> {                // bf16: A rows x 8 k and B columns x 8 k per
 };
 template <>
 struct FragSet<4> {                // fp32: A rows x 4 k per lane; B value per MFMA e and column block
-  float4 a[FM];
+  f32x4 a[FM];
   float b[4][FN];
 };
 
@@ -217,8 +219,11 @@ __device__ __forceinline__ void load_to_lds_16(gptr base, unsigned lane_off, uns
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base)
-               : "memory");
+               : "memory", "m0");
 }
+// (All forms name M0, and the masked ones EXEC, as clobbered.  The masked ones leave EXEC at all
+// ones: they are only ever reached in wave-uniform control flow with every lane active, which is
+// how the whole of run_item runs; the divergent repairs of publish_fix use none of them.)
 // The form used in the K loop: the LDS address is a wave-uniform base plus a compile-time
 // constant, and the lanes that take part are given as an exec mask (all ones for an ordinary
 // step, fewer when some lanes would overrun a tile buffer, zero when there is nothing to load),
@@ -232,7 +237,7 @@ __device__ __forceinline__ void load_to_lds_16_masked(gptr base, unsigned lane_o
                "global_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base), "n"(IMM), "s"(lo), "s"(hi)
-               : "memory", "scc");
+               : "memory", "scc", "m0", "exec");
 }
 
 // The form of the quiet iterations of the K loop, where every lane takes part for certain: no exec
@@ -243,14 +248,14 @@ __device__ __forceinline__ void load_to_lds_16_plain(gptr base, unsigned lane_of
   asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base), "n"(IMM)
-               : "memory", "scc");
+               : "memory", "scc", "m0");
 }
 template <int IMM>
 __device__ __forceinline__ void load_to_lds_16_plain_v(gptr addr, unsigned lds_base) {
   asm volatile("s_add_u32 m0, %1, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(addr), "s"(lds_base), "n"(IMM)
-               : "memory", "scc");
+               : "memory", "scc", "m0");
 }
 
 // The same two forms with a full 64-bit address per lane (merged macro-tiles: the lanes of one
@@ -259,7 +264,7 @@ __device__ __forceinline__ void load_to_lds_16_v(gptr addr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(addr), "s"(lds_base)
-               : "memory");
+               : "memory", "m0");
 }
 template <int IMM>
 __device__ __forceinline__ void load_to_lds_16_masked_v(gptr addr, unsigned lds_base, unsigned lo, unsigned hi) {
@@ -267,7 +272,7 @@ __device__ __forceinline__ void load_to_lds_16_masked_v(gptr addr, unsigned lds_
                "global_load_lds_dwordx4 %0, off\n\ts_mov_b64 exec, -1"
                :
                : "v"(addr), "s"(lds_base), "n"(IMM), "s"(lo), "s"(hi)
-               : "memory", "scc");
+               : "memory", "scc", "m0", "exec");
 }
 
 // p + d where the caller knows that the low half of the address does not carry.
@@ -313,11 +318,74 @@ __device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
   return v;
 }
 
-// The work of one wave on one item.  ROT = this wave's index: it selects the MFMA slots
-// in which the wave issues its global->LDS loads (slot % 4 == ROT).
-template <int ES, int ROT, bool COMP = false>
-__device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__restrict__ segs, char *lds,
-                                         floatx16 (&acc)[FM][FN], const CompCtx &cx = CompCtx{}) {
+// ---- the accumulators ----------------------------------------------------------------------
+// The 256 partial sums of a lane live in the accumulator registers a0 .. a255 by name: tile (i, j)
+// of the wave's 4 x 4 tiles of 32 x 32 owns a[16 t .. 16 t + 15], t = 4 i + j.  Every instruction
+// that touches them is written out below with those names, so the register allocator has no say
+// in where they are.  (Held in C++ variables tied to the MFMAs' operands, the item loop's joins
+// made it shuffle all 256 of them, or spill them around single MFMAs.)  Each of these statements
+// names the whole file as clobbered: the compiler must never keep a value of its own in it.
+#define DMM_ACC_REGS "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47", "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95", "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143", "a144", "a145", "a146", "a147", "a148", "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", "a157", "a158", "a159", "a160", "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", "a169", "a170", "a171", "a172", "a173", "a174", "a175", "a176", "a177", "a178", "a179", "a180", "a181", "a182", "a183", "a184", "a185", "a186", "a187", "a188", "a189", "a190", "a191", "a192", "a193", "a194", "a195", "a196", "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", "a205", "a206", "a207", "a208", "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", "a217", "a218", "a219", "a220", "a221", "a222", "a223", "a224", "a225", "a226", "a227", "a228", "a229", "a230", "a231", "a232", "a233", "a234", "a235", "a236", "a237", "a238", "a239", "a240", "a241", "a242", "a243", "a244", "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", "a253", "a254", "a255"
+
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>): a loop whose index is a constant
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F &&>(f));
+}
+
+// all partial sums = 0: 0 * 0 + 0 through the matrix pipe, one instruction per tile
+template <int ES, int T>
+__device__ __forceinline__ void acc_clear_tile(u32x4 z) {
+  if constexpr (ES == 2)
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%1:%2], %0, %0, 0" : : "v"(z), "n"(16 * T), "n"(16 * T + 15) : DMM_ACC_REGS);
+  else
+    asm volatile("v_mfma_f32_32x32x2_f32 a[%1:%2], %0, %0, 0" : : "v"(z[0]), "n"(16 * T), "n"(16 * T + 15) : DMM_ACC_REGS);
+}
+template <int ES, int... T>
+__device__ __forceinline__ void acc_clear_tiles(u32x4 z, std::integer_sequence<int, T...>) {
+  (acc_clear_tile<ES, T>(z), ...);
+}
+template <int ES>
+__device__ __forceinline__ void acc_clear() {
+  u32x4 z = {0u, 0u, 0u, 0u};
+  // (the zeros have just been written by vector moves: the matrix pipe must not read them in the
+  // very next cycles, and the compiler, which inserts such wait states, does not look into assembly)
+  asm volatile("s_nop 7" : "+v"(z));
+  acc_clear_tiles<ES>(z, std::make_integer_sequence<int, FM * FN>{});
+}
+// partial sum number REG to base + off + IMM (a non-temporal store straight from the accumulator file)
+template <int REG, int IMM>
+__device__ __forceinline__ void acc_store(unsigned off, const __attribute__((address_space(1))) char *base) {
+  asm volatile("global_store_dword %0, a[%2], %1 offset:%3 nt" : : "v"(off), "s"(base), "n"(REG), "n"(IMM) : "memory");
+}
+// partial sum number REG (= 16 t + r) as a value
+template <int REG>
+__device__ __forceinline__ float acc_read() {
+  float v;
+  asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(REG));
+  return v;
+}
+
+template <bool FUSE>
+__device__ __forceinline__ void store_macro_tile(const ItemDev &it, const RedSrc *__restrict__ red, int wm, int wn, int lane);
+
+// The work of one wave on one item, or (LOOP) on every `stride`-th item of the list from number
+// `idx` on.  ROT = this wave's index: it selects the MFMA slots in which the wave issues its
+// global->LDS loads (slot % 4 == ROT).
+// LOOP: the workgroup stays on its CU and walks its share of the work list.  When an item's K
+// loop is done, the loads of the next item's first three K steps are issued first and the item's
+// C stores second, so that those loads travel while the stores drain; the accumulators are
+// cleared behind the stores.  (Without LOOP the caller stores, and `first_item` is the one item.)
+template <int ES, int ROT, bool COMP = false, bool LOOP = false, bool FUSE = false>
+__device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev *__restrict__ segs, char *lds,
+                                         const CompCtx &cx = CompCtx{},
+                                         const ItemDev *__restrict__ items = nullptr, int idx = 0, int stride = 0,
+                                         int n_items = 0, const RedSrc *__restrict__ red = nullptr) {
+  ItemDev it = first_item;
   using S = Shape<ES>;
   constexpr int BK = S::BK;
   constexpr int PER = 16 / ES;                          // elements per 16-byte chunk
@@ -327,6 +395,13 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
 
   const int lane = threadIdx.x & 63;
   const unsigned lds_base = (unsigned)(uintptr_t)(lds_void_ptr)lds;   // LDS byte address of stage 0
+  const lds_cptr lds3 = (lds_cptr)(lds_void_ptr)lds;
+  // Stage 2's address in a register of its own that the optimiser cannot see through: an LDS
+  // instruction's immediate offset reaches 64 KB, so with this second base every read address of
+  // the iterations that know their stage is one of a few per-lane registers plus an immediate.
+  // (Seen through, base + 64 KB + ... is folded into a separate address register per read.)
+  lds_cptr lds3_hi = lds3 + 2 * STAGE;
+  asm volatile("" : "+v"(lds3_hi));
 
   // ---- global -> LDS ------------------------------------------------------------------
   // Wave w, load i fills KB number NW i + w of the A stage (rows 16 (NW i + w) .. + 15) and KB
@@ -346,12 +421,19 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) {
     const int row = (i * NW + wave) * 16 + a_slot_row;
-    a_srow[i] = (unsigned)(row < it.m_ext ? row : it.m_ext - 1);
     a_c16[i] = (unsigned)((a_slot_pos ^ a_swizzle(row)) << 4);
     const int k = (i * NW + wave) * B_ROWS_PER_KB + b_slot_k;
     b_srow[i] = (unsigned)k;
     b_c16[i] = (unsigned)(b_swizzle_chunk<ES>(k, b_slot_pos) << 4);
   }
+  auto set_rows = [&]() {                                // the source rows depend on the item's height
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int row = (i * NW + wave) * 16 + a_slot_row;
+      a_srow[i] = (unsigned)(row < it.m_ext ? row : it.m_ext - 1);
+    }
+  };
+  set_rows();
   auto a_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(a_srow[i], pitch) + a_c16[i]; };
   auto b_offset = [&](unsigned pitch, int i) -> unsigned { return __umul24(b_srow[i], pitch) + b_c16[i]; };
   // Merged macro-tiles: the piece that holds each of this lane's four A rows and four B chunks, the
@@ -454,6 +536,26 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     a_need = ((int64_t)(rows - 1) * sd.lda + 3 * PER) * ES + 16;
     b_need = ((int64_t)(BK - 1) * sd.ldb + (S::B_CHUNKS - 1) * PER) * ES + 16;
   };
+  // the lead enters, at kpos0 (a multiple of BK), the segment whose record is sd
+  auto open_lead_at = [&](const SegDev &sd, int kpos0) {
+    lead_kpos = kpos0;
+    lead_left = (sd.klen - kpos0 + BK - 1) / BK;
+    lead_tail = sd.klen % BK != 0;
+    ld_a_pitch = (unsigned)(sd.lda * ES);
+    ld_b_pitch = (unsigned)(sd.ldb * ES);
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      ld_a_off[i] = a_offset(ld_a_pitch, i);
+      ld_b_off[i] = b_offset(ld_b_pitch, i);
+    }
+    ld_b_step = (int64_t)BK * sd.ldb * ES;
+    int64_t a_left, b_left, a_need, b_need;
+    step_geometry(sd, kpos0, ld_a, ld_b, a_left, b_left);
+    step_need(sd, a_need, b_need);
+    // the last step of the segment reads furthest: if it is safe, all are
+    lead_seg_safe = a_left - (int64_t)(lead_left - 1) * (BK * ES) >= a_need &&
+                    b_left - (int64_t)(lead_left - 1) * ld_b_step >= b_need;
+  };
   auto open_lead = [&](int kpos0) {                      // lead enters segment lead_seg at kpos0 (a multiple of BK)
     if constexpr (COMP) {
       const int klen = seg_klen(lead_seg);
@@ -482,24 +584,7 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       lead_seg_safe = __builtin_amdgcn_ballot_w64(overrun) == 0;
       return;
     }
-    const SegDev sd = segs[it.seg_begin + lead_seg];
-    lead_kpos = kpos0;
-    lead_left = (sd.klen - kpos0 + BK - 1) / BK;
-    lead_tail = sd.klen % BK != 0;
-    ld_a_pitch = (unsigned)(sd.lda * ES);
-    ld_b_pitch = (unsigned)(sd.ldb * ES);
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      ld_a_off[i] = a_offset(ld_a_pitch, i);
-      ld_b_off[i] = b_offset(ld_b_pitch, i);
-    }
-    ld_b_step = (int64_t)BK * sd.ldb * ES;
-    int64_t a_left, b_left, a_need, b_need;
-    step_geometry(sd, kpos0, ld_a, ld_b, a_left, b_left);
-    step_need(sd, a_need, b_need);
-    // the last step of the segment reads furthest: if it is safe, all are
-    lead_seg_safe = a_left - (int64_t)(lead_left - 1) * (BK * ES) >= a_need &&
-                    b_left - (int64_t)(lead_left - 1) * ld_b_step >= b_need;
+    open_lead_at(segs[it.seg_begin + lead_seg], kpos0);
   };
   auto advance_lead = [&]() {                            // to the next K step (the caller knows one exists)
     if (__builtin_expect(--lead_left == 0, 0)) {
@@ -656,6 +741,9 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
         *slot = load_partial<ES>(pc, (int)(room > 0 ? room / ES : 0));
       }
     }
+    // the repairs must have reached LDS before the barrier that publishes the stage (the K loop's
+    // barrier is the bare instruction, without the fence of __syncthreads)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   };
 
   // ---- LDS -> registers ----------------------------------------------------------------
@@ -665,16 +753,15 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
 
   // read number r of sub-step q of `stage` into f.  bf16 order: B0 (2 reads), A0, B1, B2, B3, A1..A3,
   // so that the operands of the next sub-step's first MFMAs arrive first.
-  auto read_op = [&](int stage, int q, int r, Frags &f) {
-    const char *sa = lds + stage * STAGE;
-    const char *sb = sa + A_STAGE;
+  auto read_op = [&](lds_cptr sa, int q, int r, Frags &f) {   // sa: the stage
+    const lds_cptr sb = sa + A_STAGE;
     if constexpr (ES == 2) {
       constexpr int kind[12] = {4, 4, 0, 5, 5, 6, 6, 7, 7, 1, 2, 3};   // 0..3: A frag i; 4..7: B frag j
       constexpr int half[12] = {0, 1, 0, 0, 1, 0, 1, 0, 1, 0, 0, 0};
       const int what = kind[r];
       if (what < 4) {
         const int row = wm * WTM + what * 32 + (lane & 31);
-        f.a[what] = *(const bf16x8 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
+        f.a[what] = *(const __attribute__((address_space(3))) bf16x8 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
       } else {
         // ds_read_b64_tr_b16: in every group of 16 lanes, lane i supplies the address of 4
         // consecutive columns of k row i / 4 and receives column i of those 4 k rows.
@@ -690,12 +777,12 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       // consumes element e, i.e. k = 8 q + 4 h + e, and the B side reads that same k row.
       if (r < FM) {
         const int row = wm * WTM + r * 32 + (lane & 31);
-        f.a[r] = *(const float4 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
+        f.a[r] = *(const __attribute__((address_space(3))) f32x4 *)(sa + a_lds_off(row, q * 2 + (lane >> 5)));
       } else {
         const int e = (r - FM) / FN, j = (r - FM) % FN;
         const int k = q * 8 + (lane >> 5) * 4 + e;
         const int ncol = wn * WTN + j * 32 + (lane & 31);
-        f.b[e][j] = *(const float *)(sb + b_lds_off<4>(k, ncol >> 2) + (ncol & 3) * 4);
+        f.b[e][j] = *(const __attribute__((address_space(3))) float *)(sb + b_lds_off<4>(k, ncol >> 2) + (ncol & 3) * 4);
       }
     }
   };
@@ -705,38 +792,83 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // reads and loads of the sub-step, which then execute with nothing to hide them.)  The compiler
   // still sees the register operands and waits for the LDS reads that produce them; what it can
   // no longer see is the result hazard of the matrix pipe, covered after the loop.
-  auto mfma_op = [&](const Frags &f, int n) {            // MFMA slot n of a sub-step: tile (n / FN, n % FN)
-    const int i = n / FN, j = n % FN;
+  auto mfma_op = [&](const Frags &f, auto nc) {          // MFMA slot n of a sub-step: tile (n / FN, n % FN)
+    constexpr int n = decltype(nc)::value;
+    constexpr int i = n / FN, j = n % FN;
     if constexpr (ES == 2) {
       union { short4_t h[2]; bf16x8 v; } u;
       u.h[0] = f.b[j][0];
       u.h[1] = f.b[j][1];
-      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(f.a[i]), "v"(u.v) : "memory");
+      asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]"
+                   :
+                   : "v"(f.a[i]), "v"(u.v), "n"(16 * n), "n"(16 * n + 15)
+                   : "memory", DMM_ACC_REGS);
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float av = e == 0 ? f.a[i].x : e == 1 ? f.a[i].y : e == 2 ? f.a[i].z : f.a[i].w;
-        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(av), "v"(f.b[e][j]) : "memory");
+        asm volatile("v_mfma_f32_32x32x2_f32 a[%2:%3], %0, %1, a[%2:%3]"
+                     :
+                     : "v"(av), "v"(f.b[e][j]), "n"(16 * n), "n"(16 * n + 15)
+                     : "memory", DMM_ACC_REGS);
+      }
+    }
+  };
+  // MFMA slot n of a sub-step and, in its shadow, load number j of the lead step, every lane taking
+  // part (bf16, quiet iterations only): see the slots of sub_step
+  auto mfma_dma = [&](const Frags &f, auto nc, auto jc, unsigned stage_base) {
+    constexpr int n = decltype(nc)::value;
+    constexpr int i = n / FN, jj = n % FN;
+    constexpr int j = decltype(jc)::value;
+    constexpr int IMM = j < LOADS ? j * (NW * 1024) : A_STAGE + (j - LOADS) * (NW * 1024);
+    if constexpr (ES == 2) {
+      union { short4_t h[2]; bf16x8 v; } u;
+      u.h[0] = f.b[jj][0];
+      u.h[1] = f.b[jj][1];
+      if constexpr (COMP) {
+        gptr &addr = j < LOADS ? ca[j < LOADS ? j : 0] : cbv[j < LOADS ? 0 : j - LOADS];
+        asm volatile("s_add_u32 m0, %1, %2\n\tv_mfma_f32_32x32x16_bf16 a[%5:%6], %3, %4, a[%5:%6]\n\t"
+                     "global_load_lds_dwordx4 %0, off"
+                     :
+                     : "v"(addr), "s"(stage_base), "n"(IMM), "v"(f.a[i]), "v"(u.v), "n"(16 * n), "n"(16 * n + 15)
+                     : "memory", "scc", "m0", DMM_ACC_REGS);
+        addr = add_low(addr, j < LOADS ? (unsigned)(BK * ES) : bstep[j < LOADS ? 0 : j - LOADS]);
+      } else {
+        const unsigned off = j < LOADS ? ld_a_off[j < LOADS ? j : 0] : ld_b_off[j < LOADS ? 0 : j - LOADS];
+        const gptr base = j < LOADS ? ld_a : ld_b;
+        asm volatile("s_add_u32 m0, %2, %3\n\tv_mfma_f32_32x32x16_bf16 a[%6:%7], %4, %5, a[%6:%7]\n\t"
+                     "global_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(off), "s"(base), "s"(stage_base), "n"(IMM), "v"(f.a[i]), "v"(u.v), "n"(16 * n), "n"(16 * n + 15)
+                     : "memory", "scc", "m0", DMM_ACC_REGS);
       }
     }
   };
   // One sub-step: its FM FN MFMA slots; after slot n either one of this wave's loads (when
   // slot % 4 == ROT) or the next LDS read of the following sub-step.  `first` = index of the
   // sub-step's first slot within the K step (0 or 16).
-  auto sub_step = [&](auto first_tag, auto quiet_tag, const Frags &cur, Frags &nxt, int rd_stage, int rd_q, int ld_stage) {
+  auto sub_step = [&](auto first_tag, auto quiet_tag, const Frags &cur, Frags &nxt, lds_cptr rd_stage, int rd_q, int ld_stage) {
     constexpr int first = decltype(first_tag)::value;
     const unsigned ld_base = lds_base + ld_stage * STAGE + wave * 1024;
     // (unrolled by hand over the 16 slots so that slot numbers are compile-time constants)
     auto slot = [&](auto nc) {
       constexpr int n = decltype(nc)::value;
       constexpr int r = n - (n + NW - 1 - ROT) / NW;    // LDS reads issued in earlier slots of this sub-step
-      mfma_op(cur, n);
       constexpr int g = first + n;
+      constexpr bool QUIET_SLOT = decltype(quiet_tag)::value;
+      // A bf16 load slot of a quiet iteration is one statement: M0 write, MFMA, load.  The MFMA
+      // is the wait state the M0 write needs before the LDS-DMA instruction reads it, so the slot
+      // is three instructions, which fit the 32 cycles of the MFMA; with a separate wait state
+      // they do not quite.
+      constexpr bool FUSED = ES == 2 && QUIET_SLOT && g % NW == ROT;
+      if constexpr (FUSED) mfma_dma(cur, nc, std::integral_constant<int, g / NW>{}, ld_base);
+      else mfma_op(cur, nc);
       if constexpr (!COMP && g == NW + ((ROT + 1) % NW)) {   // a slot without a load: addresses of the next step
         ld_a_next = ld_a + BK * ES;
         ld_b_next = ld_b + ld_b_step;
       }
-      if constexpr (g % NW == ROT) {
+      if constexpr (FUSED) {
+      } else if constexpr (g % NW == ROT) {
         dma(std::integral_constant<int, g / NW>{}, ld_base, quiet_tag);
       } else if (ES == 2) {
         read_op(rd_stage, rd_q, r, nxt);
@@ -760,45 +892,45 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
   // ---- the K loop ------------------------------------------------------------------------
   // Iteration s multiplies stage s % 4 while the loads of step s + 3 are issued into stage
   // (s + 3) % 4, which every wave finished reading before the barrier of iteration s - 1.
-  const int n = it.nsteps;
-  {
-    // the item's first step: segment and position (first_step lies inside the group's sequence)
-    int first = 0;
-    for (;;) {
-      const int cnt = (seg_klen(lead_seg) + BK - 1) / BK;
-      if (it.first_step < first + cnt) break;
-      first += cnt;
-      ++lead_seg;
-    }
-    open_lead((it.first_step - first) * BK);
-  }
-  // prologue: steps 0, 1, 2 in flight; publish step 0
-  int issued = 0;
-#pragma unroll
-  for (int t = 0; t < NSTAGE - 1; ++t) {
-    if (t < n) {
-      prepare_lead(true, t);
-      const unsigned base = lds_base + t * STAGE + wave * 1024;
-      dma(std::integral_constant<int, 0>{}, base, std::false_type{}); dma(std::integral_constant<int, 1>{}, base, std::false_type{});
-      dma(std::integral_constant<int, 2>{}, base, std::false_type{}); dma(std::integral_constant<int, 3>{}, base, std::false_type{});
-      dma(std::integral_constant<int, 4>{}, base, std::false_type{}); dma(std::integral_constant<int, 5>{}, base, std::false_type{});
-      dma(std::integral_constant<int, 6>{}, base, std::false_type{}); dma(std::integral_constant<int, 7>{}, base, std::false_type{});
-      ++issued;
-      if (t + 1 < n) advance_lead();
+  int n = 0;                                             // K steps of the current item
+  int issued = 0;                                        // steps whose loads the prologue has issued
+  // Cursors to the item's first step, then its prologue: steps 0, 1, 2 in flight.
+  auto begin_item = [&](const SegDev *first_seg) {        // first_seg: the record of the item's first segment, if at hand
+    n = it.nsteps;
+    lead_seg = 0;
+    fix_bits = 0;
+    pub_seg = pub_first = 0;
+    if (!COMP && first_seg != nullptr) {
+      open_lead_at(*first_seg, 0);
     } else {
-      fix_bits <<= 1;                                    // keep the register in step: no such step, no repair
+      // the item's first step: segment and position (first_step lies inside the group's sequence)
+      int first = 0;
+      for (;;) {
+        const int cnt = (seg_klen(lead_seg) + BK - 1) / BK;
+        if (it.first_step < first + cnt) break;
+        first += cnt;
+        ++lead_seg;
+      }
+      open_lead((it.first_step - first) * BK);
     }
-  }
-  if (issued >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LOADS) : "memory");
-  else if (issued == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  publish_fix(0);
-  __syncthreads();
+    issued = 0;
 #pragma unroll
-  for (int r = 0; r < READS; ++r) read_op(0, 0, r, fr[0]);
-  // here the lead cursor is at step min(3, n - 1), which has been issued iff n <= 3
-  bool loads_on = n > NSTAGE - 1;                        // a step s + 3 exists for s = 0
-  prepare_lead(loads_on, NSTAGE - 1);
+    for (int t = 0; t < NSTAGE - 1; ++t) {
+      if (t < n) {
+        prepare_lead(true, t);
+        const unsigned base = lds_base + t * STAGE + wave * 1024;
+        dma(std::integral_constant<int, 0>{}, base, std::false_type{}); dma(std::integral_constant<int, 1>{}, base, std::false_type{});
+        dma(std::integral_constant<int, 2>{}, base, std::false_type{}); dma(std::integral_constant<int, 3>{}, base, std::false_type{});
+        dma(std::integral_constant<int, 4>{}, base, std::false_type{}); dma(std::integral_constant<int, 5>{}, base, std::false_type{});
+        dma(std::integral_constant<int, 6>{}, base, std::false_type{}); dma(std::integral_constant<int, 7>{}, base, std::false_type{});
+        ++issued;
+        if (t + 1 < n) advance_lead();
+      } else {
+        fix_bits <<= 1;                                  // keep the register in step: no such step, no repair
+      }
+    }
+  };
+  bool loads_on = false;
   int quiet = 0;                                         // iterations whose end is a plain advance of the lead
   int mid_plain = 0;                                     // the coming publication needs no repair and loads go on
   // After the lead step number `lead_idx` has been prepared by the general path: how many plain
@@ -817,18 +949,26 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
     lead_left -= quiet;
     lead_kpos += quiet * BK;
   };
-  plan_quiet(NSTAGE - 1);
   // The iteration exists in two copies.  The general one takes its loads' exec mask and its mid-
   // iteration wait from what the bookkeeping prepared; the quiet one, which runs `quiet` times after
   // it, knows that every lane loads and that nothing needs a repair, so its load slots are two
   // instructions shorter and its wait is a constant.  The quiet loop carries only s, the counter
   // and the two addresses; the general bookkeeping runs between such runs.
+  // A quiet iteration can also be told its stage at compile time (`stage_tag` 0 .. 3 instead of -1):
+  // every LDS address is then a register fixed per lane plus an immediate, and the vector adds
+  // that otherwise rebuild the read addresses from the stage's base (each right in front of the
+  // read that needs it, which waits for it) are gone, with the scalar arithmetic behind them.
   int s = 0;
-  auto iteration = [&](auto quiet_tag) {
+  auto iteration = [&](auto quiet_tag, auto stage_tag) {
     constexpr bool QUIET = decltype(quiet_tag)::value;
-    const int stage = s & (NSTAGE - 1);
-    const int ld_stage = (s + NSTAGE - 1) & (NSTAGE - 1);
-    sub_step(std::integral_constant<int, 0>{}, quiet_tag, fr[0], fr[1], stage, 1, ld_stage);
+    constexpr int FIXED = decltype(stage_tag)::value;
+    const int stage = FIXED >= 0 ? FIXED : (s & (NSTAGE - 1));
+    const int ld_stage = FIXED >= 0 ? ((FIXED + NSTAGE - 1) & (NSTAGE - 1)) : ((s + NSTAGE - 1) & (NSTAGE - 1));
+    auto stage_ptr = [&](int st) -> lds_cptr {
+      if constexpr (FIXED >= 0) return (st >= 2 ? lds3_hi : lds3) + (st & 1) * STAGE;
+      else return lds3 + st * STAGE;
+    };
+    sub_step(std::integral_constant<int, 0>{}, quiet_tag, fr[0], fr[1], stage_ptr(stage), 1, ld_stage);
     // publish step s + 1: this wave's loads of it must have landed; steps s + 2 and (half of)
     // s + 3 may stay in flight (loads return in order)
     if (QUIET || __builtin_expect(mid_plain != 0, 1)) {
@@ -839,121 +979,182 @@ __device__ __forceinline__ void run_item(const ItemDev &it, const SegDev *__rest
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       if (s + 1 < n) publish_fix(s + 1);
     }
-    __syncthreads();                         // every wave has read stage s; step s + 1 is complete
-    sub_step(std::integral_constant<int, FM * FN>{}, quiet_tag, fr[1], fr[0], (s + 1) & (NSTAGE - 1), 0, ld_stage);
+    // Every wave has issued its reads of stage s; step s + 1 is complete.  The bare barrier
+    // instruction, not __syncthreads: its fence would make every wave wait here for the LDS reads
+    // it issued in the last slots (the operands of the coming sub-step's later MFMAs), with the
+    // matrix pipe idle meanwhile.  The reads in flight at this point are reads of stage s, whose
+    // next writer is a load of step s + 4, issued an iteration from now behind another barrier and
+    // landing a memory latency later still; the compiler waits for each operand before its MFMA.
+    __builtin_amdgcn_s_barrier();
+    sub_step(std::integral_constant<int, FM * FN>{}, quiet_tag, fr[1], fr[0], stage_ptr((stage + 1) & (NSTAGE - 1)), 0, ld_stage);
     ++s;
   };
+
+  // LOOP: the next item's record and that of its first segment are read while the current item
+  // waits for its first loads, not when they are needed: a scalar load that misses the caches
+  // takes a microsecond, and three of them in a row stood between two items.
+  ItemDev ahead = it;
+  SegDev ahead_seg = {};
+  bool ahead_seg_valid = false;
+  if (!LOOP || it.nsteps > 0) begin_item(nullptr);
   for (;;) {
-    iteration(std::false_type{});
-#pragma clang loop unroll(disable)
-    while (quiet != 0) {
-      --quiet;
-      if constexpr (!COMP) {
-        ld_a = ld_a_next;
-        ld_b = ld_b_next;
+    if constexpr (LOOP) {
+      const int nxt = idx + stride;
+      if (nxt < n_items) {
+        ahead = items[nxt];
+        ahead_seg_valid = ahead.nsteps > 0 && ahead.first_step == 0;
+        if (ahead_seg_valid) ahead_seg = segs[ahead.seg_begin];
       }
-      iteration(std::true_type{});
     }
-    if (s >= n) break;
-    loads_on = s - 1 + NSTAGE < n;           // step s + 3 exists (s is the coming iteration)
-    if (loads_on) advance_lead();
-    prepare_lead(loads_on, (s - 1) & (NSTAGE - 1));   // it goes to the stage the last iteration consumed
-    plan_quiet(s - 1 + NSTAGE);
+    if (!LOOP || it.nsteps > 0) {
+      // publish step 0
+      if constexpr (LOOP) {
+        // (also the previous item's stores: the counter is shared and too narrow to tell them apart)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      } else {
+        if (issued >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LOADS) : "memory");
+        else if (issued == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+      publish_fix(0);
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < READS; ++r) read_op(lds3, 0, r, fr[0]);
+      // here the lead cursor is at step min(3, n - 1), which has been issued iff n <= 3
+      loads_on = n > NSTAGE - 1;                         // a step s + 3 exists for s = 0
+      prepare_lead(loads_on, NSTAGE - 1);
+      plan_quiet(NSTAGE - 1);
+      s = 0;
+      auto quiet_iteration = [&](auto stage_tag) {
+        if constexpr (!COMP) {
+          ld_a = ld_a_next;
+          ld_b = ld_b_next;
+        }
+        iteration(std::true_type{}, stage_tag);
+      };
+      for (;;) {
+        iteration(std::false_type{}, std::integral_constant<int, -1>{});
+#pragma clang loop unroll(disable)
+        while (quiet != 0) {
+          if ((s & (NSTAGE - 1)) == 0 && quiet >= NSTAGE) {
+            // a run of four from stage 0 on: the copies with their stages built in
+#pragma clang loop unroll(disable)
+            do {
+              quiet -= NSTAGE;
+              quiet_iteration(std::integral_constant<int, 0>{});
+              quiet_iteration(std::integral_constant<int, 1>{});
+              quiet_iteration(std::integral_constant<int, 2>{});
+              quiet_iteration(std::integral_constant<int, 3>{});
+            } while (quiet >= NSTAGE);
+            continue;
+          }
+          --quiet;
+          quiet_iteration(std::integral_constant<int, -1>{});
+        }
+        if (s >= n) break;
+        loads_on = s - 1 + NSTAGE < n;           // step s + 3 exists (s is the coming iteration)
+        if (loads_on) advance_lead();
+        prepare_lead(loads_on, (s - 1) & (NSTAGE - 1));   // it goes to the stage the last iteration consumed
+        plan_quiet(s - 1 + NSTAGE);
+      }
+      // nothing may land in LDS after the workgroup has gone; and the last MFMA results must have left
+      // the matrix pipe before other instructions read the accumulators (18 wait states and more)
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+    }
+    if constexpr (!LOOP) {
+      return;
+    } else {
+      const ItemDev done = it;
+      const int nxt = idx + stride;
+      // every wave is out of the K loop (all its LDS reads have been issued long since): the stages
+      // may be filled again
+      __builtin_amdgcn_s_barrier();
+      if (nxt < n_items) {
+        it = ahead;
+        idx = nxt;
+        set_rows();
+        if (it.nsteps > 0) begin_item(ahead_seg_valid ? &ahead_seg : nullptr);
+      }
+      store_macro_tile<FUSE>(done, red, wm, wn, lane);
+      if (nxt >= n_items) return;
+      // (the stores above read the accumulators as they issue; a few idle cycles for good measure)
+      asm volatile("s_nop 7" ::: "memory");
+      acc_clear<ES>();
+    }
   }
-  // nothing may land in LDS after the workgroup has gone; and the last MFMA results must have left
-  // the matrix pipe before other instructions read the accumulators (18 wait states and more)
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 7" ::: "memory");
 }
 
-// FUSE: the instantiation whose epilogue can add other replicas' partial sums (fused replica sum);
-// a kernel of its own, so that the plain one keeps its size and its register allocation.
-template <int ES, bool FUSE = false>
-__global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restrict__ items,
-                                                          const SegDev *__restrict__ segs,
-                                                          const RedSrc *__restrict__ red) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const ItemDev it = items[blockIdx.x];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  floatx16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  if (it.nsteps > 0) {
-    // one instantiation per wave: the four waves of the CU issue their loads in different slots
-    if (wave == 0) run_item<ES, 0>(it, segs, lds, acc);
-    else if (wave == 1) run_item<ES, 1>(it, segs, lds, acc);
-    else if (wave == 2) run_item<ES, 2>(it, segs, lds, acc);
-    else run_item<ES, 3>(it, segs, lds, acc);
-  }
-  // epilogue: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 tile.
-  // Addresses are the item's base plus a 32-bit byte offset (the host rejects C pitches of 2^24
-  // bytes and more): one add per row, the four column blocks of a row through the immediate offset.
-  // A full 256 x 256 item stores without predicates.  A bf16 destination receives the fp32 sum
-  // rounded to nearest even, one 2-byte store per element.
+// The C stores of one macro-tile: lane holds column (lane & 31), rows 8 (r / 4) + 4 (lane / 32) + r % 4 of
+// each 32 x 32 tile.  Addresses are the item's base plus a 32-bit byte offset (the host rejects C
+// pitches of 2^24 bytes and more): one add per row, the four column blocks of a row through the
+// immediate offset.  A full 256 x 256 item stores without predicates.  A bf16 destination receives
+// the fp32 sum rounded to nearest even, one 2-byte store per element.
+// FUSE: the instantiation that can add other replicas' partial sums (fused replica sum).
+template <bool FUSE>
+__device__ __forceinline__ void store_macro_tile(const ItemDev &it, const RedSrc *__restrict__ red, int wm, int wn, int lane) {
+  // (the lane number is hidden from the optimiser here: inside the item loop it would otherwise
+  // move everything below that depends on the lane alone, the 64 row numbers of the predicates
+  // among it, in front of the loop and keep it in registers all the way through the K loops)
+  asm volatile("" : "+v"(lane));
   const __attribute__((address_space(1))) char *cbytes = (const __attribute__((address_space(1))) char *)it.c;
   const int row0 = wm * WTM + 4 * (lane >> 5);
   const int col0 = wn * WTN + (lane & 31);
   const bool wide = it.c_es == 4;
   const unsigned pitch = (unsigned)it.ldc * (unsigned)it.c_es;
   const unsigned voff = (unsigned)row0 * pitch + (unsigned)col0 * (unsigned)it.c_es;
-  auto store_all = [&](auto full_tag) {
+  auto store_all = [&](auto full_tag, auto wide_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int dr = i * 32 + 8 * (r >> 2) + (r & 3);
-        const unsigned o = voff + (unsigned)dr * pitch;
-        if (FULL || row0 + dr < it.m_ext) {
-          if (wide) {
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-              if (FULL || col0 + j * 32 < it.n_ext)
-                __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(cbytes + o + j * 128));
-          } else {
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-              if (FULL || col0 + j * 32 < it.n_ext)
-              {
-                // the copy out of the accumulator file is written out, next to its use: left to the
-                // compiler, all 256 sums are moved to ordinary registers ahead of the first store
-                float v;
-                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
-                __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)v),
-                                            (gushort_ptr)(cbytes + o + j * 64));
-              }
+    constexpr bool wide = decltype(wide_tag)::value;       // fp32 destination (else bf16)
+    // the row offset is carried from row to row (rows go +1, +1, +1, +5) and hidden from the
+    // optimiser after every step: it would otherwise work out all 64 offsets ahead of the stores
+    unsigned o = voff;
+    const unsigned pitch5 = 5u * pitch;
+    static_for<FM * 16>([&](auto xc) {
+      constexpr int i = decltype(xc)::value / 16, r = decltype(xc)::value % 16;
+      constexpr int dr = i * 32 + 8 * (r >> 2) + (r & 3);
+      asm volatile("" : "+v"(o));
+      if (FULL || row0 + dr < it.m_ext) {
+        static_for<FN>([&](auto jc) {
+          constexpr int j = decltype(jc)::value;
+          constexpr int REG = 16 * (i * FN + j) + r;
+          if (FULL || col0 + j * 32 < it.n_ext) {
+            if constexpr (wide) {
+              // data straight from the accumulator file, one offset register
+              acc_store<REG, j * 128>(o, cbytes);
+            } else {
+              __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)acc_read<REG>()),
+                                          (gushort_ptr)(cbytes + o + j * 64));
+            }
           }
-        }
+        });
       }
+      o += (r & 3) == 3 ? pitch5 : pitch;
+    });
   };
   // Fused replica sum (fp32 C only): the macro-tile of the origin replica, launched after the other
   // replicas' macro-tiles have finished, adds their partial sums to its own, ((own + p_1) + p_2) ...,
-  // the order and precision of the replica-sum kernel, and stores the total.  32 rows at a time:
-  // 64 sums and 64 loaded values per lane, all loads of a partial in flight before the first add.
+  // the order and precision of the replica-sum kernel, and stores the total.  Eight rows of a 32 x 32
+  // tile at a time: 32 sums and 32 loaded values per lane, all loads of a batch in flight before the
+  // first add (the registers of the next item's first loads are live here as well).
   auto store_sum = [&](auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-      float sum[16][FN];
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(sum[r][j]) : "a"(acc[i][j][r]));
+    constexpr int RB = 8;                                  // accumulator registers (rows) per batch
+    static_for<FM * (16 / RB)>([&](auto xc) {
+      constexpr int i = decltype(xc)::value / (16 / RB), rb = (decltype(xc)::value % (16 / RB)) * RB;
+      float sum[RB][FN];
+      static_for<RB * FN>([&](auto yc) {
+        constexpr int r = decltype(yc)::value / FN, j = decltype(yc)::value % FN;
+        sum[r][j] = acc_read<16 * (i * FN + j) + rb + r>();
+      });
       for (int q = 0; q < it.red_count; ++q) {
         const RedSrc src = red[it.red_first + q];
         const __attribute__((address_space(1))) char *pbytes = (const __attribute__((address_space(1))) char *)src.p;
         const unsigned ppitch = (unsigned)src.ld * 4u;
         const unsigned poff = (unsigned)row0 * ppitch + (unsigned)col0 * 4u;
-        float v[16][FN];
+        float v[RB][FN];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int dr = i * 32 + 8 * (r >> 2) + (r & 3);
+        for (int r = 0; r < RB; ++r) {
+          const int dr = i * 32 + 8 * ((rb + r) >> 2) + ((rb + r) & 3);
           const unsigned o = poff + (unsigned)dr * ppitch;
 #pragma unroll
           for (int j = 0; j < FN; ++j) {
@@ -963,20 +1164,20 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
           }
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
+        for (int r = 0; r < RB; ++r)
 #pragma unroll
           for (int j = 0; j < FN; ++j) sum[r][j] = sum[r][j] + v[r][j];
       }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int dr = i * 32 + 8 * (r >> 2) + (r & 3);
+      for (int r = 0; r < RB; ++r) {
+        const int dr = i * 32 + 8 * ((rb + r) >> 2) + ((rb + r) & 3);
         const unsigned o = voff + (unsigned)dr * pitch;
 #pragma unroll
         for (int j = 0; j < FN; ++j)
           if (FULL || (row0 + dr < it.m_ext && col0 + j * 32 < it.n_ext))
             __builtin_nontemporal_store(sum[r][j], (gfloat_ptr)(cbytes + o + j * 128));
       }
-    }
+    });
   };
   const bool full = it.m_ext == BM && it.n_ext == BN;
   if constexpr (FUSE) {
@@ -986,8 +1187,35 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restr
       return;
     }
   }
-  if (full) store_all(std::true_type{});
-  else store_all(std::false_type{});
+  if (wide) {
+    if (full) store_all(std::true_type{}, std::true_type{});
+    else store_all(std::false_type{}, std::true_type{});
+  } else {
+    if (full) store_all(std::true_type{}, std::false_type{});
+    else store_all(std::false_type{}, std::false_type{});
+  }
+}
+
+// The launch: one workgroup per CU (or fewer), workgroup w taking items w, w + gridDim.x, ... of the
+// `n_items` of the list, which the planner has ordered so that this keeps the macro-tiles of one
+// block on one XCD.  FUSE: a kernel of its own, so that the plain one keeps its size and its
+// register allocation.
+template <int ES, bool FUSE = false>
+__global__ __launch_bounds__(NT) void grouped_gemm_kernel(const ItemDev *__restrict__ items,
+                                                          const SegDev *__restrict__ segs,
+                                                          const RedSrc *__restrict__ red, int n_items) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int idx = blockIdx.x;
+  if (idx >= n_items) return;
+  const ItemDev it = items[idx];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  acc_clear<ES>();
+  // one instantiation per wave: the four waves of the CU issue their loads in different slots
+  const int stride = (int)gridDim.x;
+  if (wave == 0) run_item<ES, 0, false, true, FUSE>(it, segs, lds, CompCtx{}, items, idx, stride, n_items, red);
+  else if (wave == 1) run_item<ES, 1, false, true, FUSE>(it, segs, lds, CompCtx{}, items, idx, stride, n_items, red);
+  else if (wave == 2) run_item<ES, 2, false, true, FUSE>(it, segs, lds, CompCtx{}, items, idx, stride, n_items, red);
+  else run_item<ES, 3, false, true, FUSE>(it, segs, lds, CompCtx{}, items, idx, stride, n_items, red);
 }
 
 // The same multiplication for merged macro-tiles.  The item's descriptors (segment lengths, one A
@@ -1025,13 +1253,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
   }
   __syncthreads();
 
-  floatx16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  acc_clear<ES>();
 
   if (ci->nsteps > 0) {
     ItemDev it;
@@ -1053,10 +1275,10 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
     cx.cb = geo + PMAX + 1;
     cx.R = R;
     cx.Q = Q;
-    if (wave == 0) run_item<ES, 0, true>(it, nullptr, lds, acc, cx);
-    else if (wave == 1) run_item<ES, 1, true>(it, nullptr, lds, acc, cx);
-    else if (wave == 2) run_item<ES, 2, true>(it, nullptr, lds, acc, cx);
-    else run_item<ES, 3, true>(it, nullptr, lds, acc, cx);
+    if (wave == 0) run_item<ES, 0, true>(it, nullptr, lds, cx);
+    else if (wave == 1) run_item<ES, 1, true>(it, nullptr, lds, cx);
+    else if (wave == 2) run_item<ES, 2, true>(it, nullptr, lds, cx);
+    else run_item<ES, 3, true>(it, nullptr, lds, cx);
   }
 
   // ---- epilogue ------------------------------------------------------------------------------
@@ -1065,17 +1287,17 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
     float *out = ci->scratch;
     const int row0 = wm * WTM + 4 * (lane >> 5);
     const int col0 = wn * WTN + (lane & 31);
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (row < m_ext) {
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-            if (col0 + j * 32 < n_ext) __builtin_nontemporal_store(acc[i][j][r], out + row * BN + col0 + j * 32);
-        }
+    static_for<FM * 16>([&](auto xc) {
+      constexpr int i = decltype(xc)::value / 16, r = decltype(xc)::value % 16;
+      const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
+      if (row < m_ext) {
+        static_for<FN>([&](auto jc) {
+          constexpr int j = decltype(jc)::value;
+          if (col0 + j * 32 < n_ext)
+            __builtin_nontemporal_store(acc_read<16 * (i * FN + j) + r>(), out + row * BN + col0 + j * 32);
+        });
       }
+    });
     return;
   }
   __syncthreads();                                        // every wave is out of the K loop: the stages are free
@@ -1114,31 +1336,28 @@ __global__ __launch_bounds__(NT) void grouped_gemm_comp_kernel(const CompItemDev
   const bool one_piece = __builtin_amdgcn_ballot_w64(qj[0] != qj[FN - 1]) == 0;
   auto store_all = [&](auto one_tag) {
     constexpr bool ONE = decltype(one_tag)::value;
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (row < m_ext) {
-          uint64_t a0 = 0;
-          if constexpr (ONE) a0 = rowbase[row * PMAX + qj[0]] + lcol[0];
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-            if (col0 + j * 32 < n_ext) {
-              uint64_t a;
-              if constexpr (ONE) a = a0;
-              else a = rowbase[row * PMAX + qj[j]] + lcol[j];
-              if (wide) {
-                __builtin_nontemporal_store(acc[i][j][r], (gfloat_ptr)(uintptr_t)a + (ONE ? j * 32 : 0));
-              } else {
-                float v;
-                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
-                __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)v),
-                                            (gushort_ptr)(uintptr_t)a + (ONE ? j * 32 : 0));
-              }
-            }
-        }
+    static_for<FM * 16>([&](auto xc) {
+      constexpr int i = decltype(xc)::value / 16, r = decltype(xc)::value % 16;
+      const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
+      if (row < m_ext) {
+        uint64_t a0 = 0;
+        if constexpr (ONE) a0 = rowbase[row * PMAX + qj[0]] + lcol[0];
+        static_for<FN>([&](auto jc) {
+          constexpr int j = decltype(jc)::value;
+          if (col0 + j * 32 < n_ext) {
+            uint64_t a;
+            if constexpr (ONE) a = a0;
+            else a = rowbase[row * PMAX + qj[j]] + lcol[j];
+            const float v = acc_read<16 * (i * FN + j) + r>();
+            if (wide)
+              __builtin_nontemporal_store(v, (gfloat_ptr)(uintptr_t)a + (ONE ? j * 32 : 0));
+            else
+              __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, (__bf16)v),
+                                          (gushort_ptr)(uintptr_t)a + (ONE ? j * 32 : 0));
+          }
+        });
       }
+    });
   };
   if (one_piece) store_all(std::true_type{});
   else store_all(std::false_type{});
