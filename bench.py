@@ -15,7 +15,11 @@ The line also carries
   roofline      the grouped-GEMM kernel against the dense bf16 (or fp32) MFMA
                 peak: algorithmic FLOPs (2 M N K per launch) / its average
                 duration, taken from HIP events the library records around the
-                launch on the launch stream (DMM_TIMING), on every fourth timed step;
+                launch on the launch stream (DMM_TIMING) on every one of 24 more
+                steps run right after the timed region (which carries no events);
+  per_config    (default workload only) the other configurations, a short run each:
+                plan + execute rate, kernel rate and fraction of the MFMA peak of the
+                configuration's element type, parity of a sample of rows;
   roofline_replica_sum   the replica-sum kernel against peak HBM bandwidth:
                 (c + 1) * 4 bytes per C element / its average duration;
   fused_replica_sum   (replicated C) the same plan + execute steps with DMM_FUSED_REDUCE:
@@ -49,6 +53,106 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 
 
+def parity_sample(prob, cfg, A, B, np, omatmul):
+    """Rows of C from the last run against the oracle: the first and last row, one row out of
+    every 256-row band (every macro-tile band) and a few random ones, all columns."""
+    rng = np.random.default_rng(3)
+    M = cfg["M"]
+    rows = {0, M - 1} | {int(b + rng.integers(0, min(256, M - b))) for b in range(0, M, 256)}
+    rows |= {int(r) for r in rng.integers(0, M, 6)}
+    rows = np.array(sorted(rows))
+    got = prob.C.gather_rows(rows, 0).astype(np.float64)
+    ref = omatmul.matmul(A[rows], B, bf16=(cfg["dtype"] == "bf16"))
+    return {"rows_checked": int(len(rows)), "rel_frobenius": float(np.linalg.norm(got - ref) / np.linalg.norm(ref)),
+            "tolerance": 2e-3 if cfg["dtype"] == "bf16" else 1e-5}
+
+
+def short_run(name, ld_multiple, np, torch, workloads, binding, DeviceProblem, omatmul, steps=12, kernel_steps=12):
+    """One of the other configurations: `steps` plan + execute steps between two synchronisations,
+    then `kernel_steps` more with events around the kernels, then the parity sample."""
+    cfg = workloads.config(name)
+    A, B = workloads.make_operands(cfg)
+    prob = DeviceProblem(cfg, A, B, ld_multiple=ld_multiple)
+    stream = torch.cuda.current_stream().cuda_stream
+    fl = workloads.flops(cfg)
+    peak = PEAK_TFLOPS[cfg["dtype"]]
+
+    def one(flags):
+        plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], 0)
+        plan.execute_marshalled(prob.dtype_code, prob.args, flags | prob.c_flags, stream)
+        return plan
+    inflight = []
+
+    def run(n):                               # n steps, three in flight (destroy waits for the plan's own work)
+        for _ in range(n):
+            inflight.append(one(0))
+            if len(inflight) > 3:
+                inflight.pop(0).destroy()
+    run(5)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    while inflight:
+        inflight.pop(0).destroy()
+    g, r = [], []
+    for _ in range(kernel_steps):
+        p = one(binding.DMM_TIMING)
+        gm, rm = p.elapsed_ms()
+        p.destroy()
+        g.append(gm)
+        r.append(rm)
+    res = {"workload": f"{cfg['name']}: M={cfg['M']} K={cfg['K']} N={cfg['N']} {cfg['dtype']}, {cfg['what']}",
+           "ld_multiple": ld_multiple, "tasks": prob.plan.num_tasks(), "work_items": prob.plan.num_items(),
+           "ran_merged": prob.plan.ran_merged(), "steps": steps,
+           "ms_per_step": round(ms, 4), "value": round(fl / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+           "pct_of_mfma_peak": round(100.0 * fl / (ms * 1e-3) / 1e12 / peak, 2),
+           "gemm_kernel": {"avg_ms": round(float(np.mean(g)), 4), "median_ms": round(float(np.median(g)), 4),
+                           "best_ms": round(float(np.min(g)), 4), "launches_timed": len(g),
+                           "achieved": round(fl / (float(np.mean(g)) * 1e-3) / 1e12, 2), "peak": peak, "unit": "TFLOP/s",
+                           "frac": round(fl / (float(np.mean(g)) * 1e-3) / 1e12 / peak, 4)},
+           "parity": parity_sample(prob, cfg, A, B, np, omatmul)}
+    if cfg["C"]["replication"] > 1:
+        res["replica_sum_kernel_avg_ms"] = round(float(np.mean(r)), 4)
+    prob.close()
+    del prob, A, B
+    gc.collect()
+    torch.cuda.empty_cache()
+    return res
+
+
+def reduce_large(np, torch, workloads, DeviceProblem, stream):
+    """The replica sum alone at a size where neither launch overhead nor the last-level cache
+    matter: 16 tiles of 4096 x 4096, four replicas: 4 x 1.07 GB read, 1.07 GB written."""
+    Mr = Nr = 16384
+    rcfg = dict(name="reduce-large", M=Mr, K=64, N=Nr, dtype="bf16", nranks=64,
+                A=workloads.block_desc(Mr, 64, 4, 4, replication=4), B=workloads.block_desc(64, Nr, 4, 4, replication=4),
+                C=workloads.block_desc(Mr, Nr, 4, 4, replication=4))
+    rp = DeviceProblem(rcfg, c_fill=1.0)
+    for _ in range(2):
+        rp.reduce(0, stream)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+    ev[0].record()
+    for i in range(10):
+        rp.reduce(0, stream)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ts = [ev[i].elapsed_time(ev[i + 1]) for i in range(10)]
+    rbytes = 5 * 4.0 * Mr * Nr
+    res = {"kernel": "reduce_replicas_kernel", "bound": "hbm",
+           "workload": "c = 4, C 16384 x 16384 fp32 in 4x4 tiles, dmm_reduce_replicas alone",
+           "achieved": round(rbytes / (float(np.mean(ts)) * 1e-3) / 1e9, 1),
+           "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "frac": round(rbytes / (float(np.mean(ts)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+           "avg_ms": round(float(np.mean(ts)), 4), "best_ms": round(min(ts), 4)}
+    rp.close()
+    del rp
+    torch.cuda.empty_cache()
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +173,10 @@ def main() -> int:
     ap.add_argument("--no-fused", action="store_true", help="skip the extra timing of the DMM_FUSED_REDUCE variant")
     ap.add_argument("--no-reduce-large", action="store_true",
                     help="skip the stand-alone replica sum at c = 4 on 16384 x 16384 (5.4 GB moved)")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the short runs of the other configurations (cfg1, cfg2, cfg3, cfg5 packed and padded)")
+    ap.add_argument("--only-reduce-large", action="store_true",
+                    help="run nothing but the stand-alone replica sum at c = 4 on 16384 x 16384 (for a kernel trace)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -91,6 +199,11 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     dprop = torch.cuda.get_device_properties(0)
+
+    if args.only_reduce_large:
+        print(json.dumps({"roofline_replica_sum_large":
+                          reduce_large(np, torch, workloads, DeviceProblem, torch.cuda.current_stream().cuda_stream)}), flush=True)
+        return 0
 
     cfg = workloads.config(args.workload)
     if args.dtype and args.dtype != cfg["dtype"]:
@@ -116,8 +229,8 @@ def main() -> int:
     inflight = []
     gemm_ms, red_ms = [], []
 
-    TIMED_EVERY = 4           # the kernels of every fourth step are bracketed by HIP events (the events
-                              # themselves cost a few microseconds of device time per step)
+    KERNEL_STEPS = 24         # steps after the timed region whose kernels are bracketed by HIP events (the
+                              # events cost the stream about 20 us per step, so the timed steps carry none)
 
     def step(record, timed=True):
         h0 = time.perf_counter()
@@ -151,11 +264,17 @@ def main() -> int:
     host_s[0] = host_s[1] = 0.0
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(True, timed=(i % TIMED_EVERY == 0))
+        step(False, timed=False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     while inflight:
         retire()
+    # the same steps once more, each with events around its kernels: the roofline figures
+    for i in range(KERNEL_STEPS):
+        step(True, timed=True)
+    while inflight:
+        retire()
+    torch.cuda.synchronize()
 
     # the same steps with the replica sum fused into the GEMM (DMM_FUSED_REDUCE), for the record: no
     # replica-sum kernel, replica 0's macro-tiles add the other replicas' partial sums before they store
@@ -240,7 +359,7 @@ def main() -> int:
                    "virtual_ranks": cfg["nranks"], "tasks": prob.plan.num_tasks(), "groups": prob.plan.num_groups(),
                    "work_items": prob.plan.num_items(), "merged_work_items": prob.plan.num_merged_items(),
                    "ran_merged": ran_merged, "merge": args.merge, "ld_multiple": args.ld_multiple, "c_dtype": args.c_dtype,
-                   "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "kernel_events_on_every_nth_step": TIMED_EVERY, "plan_host_us": round(plan_us, 1),
+                   "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "kernel_event_steps_after_the_timed_region": KERNEL_STEPS, "plan_host_us": round(plan_us, 1),
                    "plan_with_op_list_host_us": round(list_us, 1),
                    "execute_only_ms_per_step": round(exec_only_ms, 4),
                    "execute_only_tflops": round(workloads.flops(cfg) / (exec_only_ms * 1e-3) / 1e12, 2),
@@ -253,7 +372,7 @@ def main() -> int:
         "roofline": {"kernel": "grouped_gemm_comp_kernel" if ran_merged else "grouped_gemm_kernel", "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                      "avg_ms": round(g_avg, 4), "median_ms": round(float(np.median(gemm_ms)), 4),
-                     "best_ms": round(g_best, 4),
+                     "best_ms": round(g_best, 4), "launches_timed": len(gemm_ms),
                      "best_frac": round(fl / (g_best * 1e-3) / 1e12 / peak, 4),
                      "traffic": traffic.get("gemm_bytes")},
     }
@@ -272,11 +391,7 @@ def main() -> int:
 
     # parity spot check on the output of the timed run, and the CPU baseline
     from oracle import matmul as omatmul
-    rows = np.array(sorted({0, cfg["M"] - 1} | {int(r) for r in np.random.default_rng(3).integers(0, cfg["M"], 6)}))
-    got = prob.C.gather_rows(rows, 0).astype(np.float64)
-    ref = omatmul.matmul(A[rows], B, bf16=(cfg["dtype"] == "bf16"))
-    out["parity"] = {"rows_checked": int(len(rows)),
-                     "rel_frobenius": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+    out["parity"] = parity_sample(prob, cfg, A, B, np, omatmul)
 
     if not args.no_cpu_baseline:
         n_rows = args.cpu_rows or max(1, min(cfg["M"], int(3.0e12 / (2.0 * cfg["K"] * cfg["N"]))))
@@ -290,35 +405,20 @@ def main() -> int:
                                          f"(all {cfg['N']} columns, K={cfg['K']}), {tc:.1f} s",
                                "seconds": round(tc, 2)}
     prob.close()
+    del prob
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    if args.workload == "cfg4" and not args.dtype and not args.no_per_config and args.ld_multiple == 1 \
+            and args.c_dtype == "f32" and args.merge == "auto":
+        per = {}
+        for name, ldm in (("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg5", 1), ("cfg5", 8)):
+            per[name if ldm == 1 else f"{name}/ld{ldm}"] = short_run(name, ldm, np, torch, workloads, binding, DeviceProblem, omatmul)
+        per["cfg4"] = {"see": "the top level of this line (value, roofline, parity)"}
+        out["per_config"] = per
 
     if not args.no_reduce_large and c_rep > 1:
-        # The replica sum alone at a size where neither launch overhead nor the last-level cache
-        # matter: 16 tiles of 4096 x 4096, four replicas: 4 x 1.07 GB read, 1.07 GB written.
-        Mr = Nr = 16384
-        rcfg = dict(name="reduce-large", M=Mr, K=64, N=Nr, dtype="bf16", nranks=64,
-                    A=workloads.block_desc(Mr, 64, 4, 4, replication=4), B=workloads.block_desc(64, Nr, 4, 4, replication=4),
-                    C=workloads.block_desc(Mr, Nr, 4, 4, replication=4))
-        rp = DeviceProblem(rcfg, c_fill=1.0)
-        for _ in range(2):
-            rp.reduce(0, stream)
-        torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
-        ev[0].record()
-        for i in range(10):
-            rp.reduce(0, stream)
-            ev[i + 1].record()
-        torch.cuda.synchronize()
-        ts = [ev[i].elapsed_time(ev[i + 1]) for i in range(10)]
-        rbytes = 5 * 4.0 * Mr * Nr
-        out["roofline_replica_sum_large"] = {"kernel": "reduce_replicas_kernel", "bound": "hbm",
-                                             "workload": "c = 4, C 16384 x 16384 fp32 in 4x4 tiles, dmm_reduce_replicas alone",
-                                             "achieved": round(rbytes / (float(np.mean(ts)) * 1e-3) / 1e9, 1),
-                                             "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                             "frac": round(rbytes / (float(np.mean(ts)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                                             "avg_ms": round(float(np.mean(ts)), 4), "best_ms": round(min(ts), 4)}
-        rp.close()
-        del rp
-        torch.cuda.empty_cache()
+        out["roofline_replica_sum_large"] = reduce_large(np, torch, workloads, DeviceProblem, stream)
 
     if not args.no_context and cfg["dtype"] == "bf16":
         def vendor(kind):

@@ -49,33 +49,34 @@ typedef enum {
  * dmm_execute is given DMM_C_BF16. */
 typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
 
-/* dmm_plan flags: the data movement strategy of Section 4, i.e. which matrix stays in place
- * and so decides which rank performs an op.  0 = Stationary C (Algorithm 1). */
-#define DMM_STATIONARY_B 1u /* Algorithm 2 */
-#define DMM_STATIONARY_A 2u /* its mirror image (Section 4.1: "analogous") */
+/* dmm_plan flags (bits 0 .. 7): the data movement strategy of Section 4, i.e. which matrix stays
+ * in place and so decides which rank performs an op.  0 = Stationary C (Algorithm 1). */
+#define DMM_STATIONARY_B 0x1u /* Algorithm 2 */
+#define DMM_STATIONARY_A 0x2u /* its mirror image (Section 4.1: "analogous") */
 /* Iteration offset of Section 4.2: each rank's ops of stationary tile (i, j) start i + j
  * positions later in their cyclic order.  It changes the order of the raw task list only
  * (what a rank would fetch when); the grouped order and the results do not depend on it. */
-#define DMM_ITERATION_OFFSET 4u
+#define DMM_ITERATION_OFFSET 0x4u
 /* Keep the merged work list (see dmm_plan_merged_items) whenever the plan can have one, also
  * where it saves no macro-tiles. */
-#define DMM_MERGE_ALWAYS 8u
+#define DMM_MERGE_ALWAYS 0x8u
 
-/* dmm_execute flags */
-#define DMM_NO_REDUCE 1u /* leave every C replica holding its partial sum */
-#define DMM_TIMING 2u    /* record events around the GEMM launch and around the replica-sum launch
-                            on the given stream; read them with dmm_plan_elapsed_ms */
-#define DMM_FUSED_REDUCE 16u /* replicated C: no replica-sum kernel; the macro-tiles of replicas 1, 2, ...
-                            run first, those of replica 0 in a second launch behind them, where each adds
-                            the other replicas' partial sums of its region to its own, ((own + C_1) + C_2)
-                            ..., before it stores.  Same final contents of every replica, bit for bit, as
-                            without the flag.  Ignored where it does not apply: one replica of C,
-                            DMM_NO_REDUCE, merged macro-tiles, macro-tiles cut along K */
-#define DMM_NO_MERGE 8u  /* run the macro-tiles of dmm_plan_items even where the plan has merged ones */
-#define DMM_C_BF16 4u    /* the C tiles are bf16 buffers (c_ld in bf16 elements): every element receives
-                            its fp32 sum rounded to nearest even, once.  Only for a C with one replica
-                            (DMM_EINVAL otherwise): the partial sums of a replicated C stay fp32, since one
-                            rounding to bf16 already costs a relative error of up to 2^-8 per element */
+/* dmm_execute flags (bits 8 .. 15; the two sets share no bit, so a flag handed to the wrong call
+ * is rejected with DMM_EINVAL) */
+#define DMM_NO_REDUCE 0x100u /* leave every C replica holding its partial sum */
+#define DMM_TIMING 0x200u    /* record events around the GEMM launch and around the replica-sum launch
+                                on the given stream; read them with dmm_plan_elapsed_ms */
+#define DMM_C_BF16 0x400u    /* the C tiles are bf16 buffers (c_ld in bf16 elements): every element receives
+                                its fp32 sum rounded to nearest even, once.  Only for a C with one replica
+                                (DMM_EINVAL otherwise): the partial sums of a replicated C stay fp32, since one
+                                rounding to bf16 already costs a relative error of up to 2^-8 per element */
+#define DMM_NO_MERGE 0x800u  /* run the macro-tiles of dmm_plan_items even where the plan has merged ones */
+#define DMM_FUSED_REDUCE 0x1000u /* replicated C: no replica-sum kernel; the macro-tiles of replicas 1, 2, ...
+                                run first, those of replica 0 in a second launch behind them, where each adds
+                                the other replicas' partial sums of its region to its own, ((own + C_1) + C_2)
+                                ..., before it stores.  Same final contents of every replica, bit for bit, as
+                                without the flag.  Ignored where it does not apply: one replica of C,
+                                DMM_NO_REDUCE, merged macro-tiles, macro-tiles cut along K */
 
 /* Distributed matrix descriptor (Section 3): shape, partition object, replication
  * factor.  The partition is a tile grid given by cut points (a uniform tile
@@ -223,10 +224,18 @@ int dmm_reduce_replicas(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld
 int dmm_broadcast_replica(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld, int32_t origin_replica,
                           void *hip_stream);
 
+/* ---- measurement and test aids (not steps of the method) ---------------------------------- */
+
 /* 1 if the last dmm_execute on this plan ran the merged macro-tiles (the plan has such a list,
  * DMM_NO_MERGE was not given and the device grants a workgroup the 160 KB of LDS their kernel
  * asks for), else 0. */
 int dmm_plan_ran_merged(const dmm_plan_t *p);
+
+/* 1 if the last dmm_execute on this plan cut macro-tiles along K (partial tiles through a scratch
+ * buffer, added up in ascending k by a second kernel: the last round of workgroups would have
+ * left most of the device idle, or a merged macro-tile had more K-segments than its workgroup
+ * can hold descriptors for), else 0.  Such a run sums in another order than an uncut one. */
+int dmm_plan_ran_k_split(const dmm_plan_t *p);
 
 /* Device time of the two kernels of the last dmm_execute(..., DMM_TIMING, ...) on this
  * plan, in milliseconds, excluding the work-table upload.  Blocks until those kernels
@@ -252,7 +261,7 @@ void dmm_plan_destroy(dmm_plan_t *p);
 
 const char *dmm_strerror(int status);
 int dmm_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread, 0 if none */
-int dmm_version(void);         /* 2: merged macro-tiles, bf16 C tiles, fused replica sum, lazily written op list */
+int dmm_version(void);         /* 3: flag values of dmm_plan and dmm_execute disjoint, dmm_plan_ran_k_split */
 
 #ifdef __cplusplus
 }

@@ -16,15 +16,15 @@ LIB_PATH = os.path.join(_HERE, "libdmm.so")
 
 DMM_OK, DMM_EINVAL, DMM_ESHAPE, DMM_EREPL, DMM_ENOMEM, DMM_EHIP, DMM_ELD = 0, -1, -2, -3, -4, -5, -6
 DMM_BF16, DMM_F32 = 1, 2
-DMM_NO_REDUCE = 1
-DMM_TIMING = 2
-DMM_C_BF16 = 4
-DMM_NO_MERGE = 8
-DMM_FUSED_REDUCE = 16
-DMM_STATIONARY_B = 1          # dmm_plan flags
-DMM_STATIONARY_A = 2
-DMM_ITERATION_OFFSET = 4
-DMM_MERGE_ALWAYS = 8
+DMM_STATIONARY_B = 0x1        # dmm_plan flags (bits 0 .. 7)
+DMM_STATIONARY_A = 0x2
+DMM_ITERATION_OFFSET = 0x4
+DMM_MERGE_ALWAYS = 0x8
+DMM_NO_REDUCE = 0x100         # dmm_execute flags (bits 8 .. 15)
+DMM_TIMING = 0x200
+DMM_C_BF16 = 0x400
+DMM_NO_MERGE = 0x800
+DMM_FUSED_REDUCE = 0x1000
 STATIONARY_FLAGS = {"C": 0, "B": DMM_STATIONARY_B, "A": DMM_STATIONARY_A}
 STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EREPL", -4: "ENOMEM", -5: "EHIP", -6: "ELD"}
 
@@ -106,6 +106,8 @@ def lib() -> C.CDLL:
         L.dmm_plan_merged_items.argtypes = [P]
         L.dmm_plan_ran_merged.restype = C.c_int
         L.dmm_plan_ran_merged.argtypes = [P]
+        L.dmm_plan_ran_k_split.restype = C.c_int
+        L.dmm_plan_ran_k_split.argtypes = [P]
         L.dmm_plan_macro_tile.restype = C.c_int32
         L.dmm_plan_macro_tile.argtypes = [P]
         L.dmm_execute.restype = C.c_int
@@ -130,7 +132,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
-           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged",
+           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged", "dmm_plan_ran_k_split",
            "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
 
@@ -213,6 +215,9 @@ class Plan:
 
     def ran_merged(self) -> bool:
         return bool(lib().dmm_plan_ran_merged(self._h))
+
+    def ran_k_split(self) -> bool:
+        return bool(lib().dmm_plan_ran_k_split(self._h))
 
     def macro_tile(self) -> int:
         return int(lib().dmm_plan_macro_tile(self._h))

@@ -139,8 +139,10 @@ struct Uploader {
   int upload(const void *src, size_t bytes, hipStream_t stream, hipEvent_t busy_until = nullptr) {
     if (bytes == 0) return DMM_OK;
     if (bytes > slab.cap) {
-      // growing: the old slab may still be read by enqueued work of this plan
+      // growing: the old slab may still be read by enqueued work of this plan, on this stream or,
+      // from an earlier call, on another one (busy_until is behind all of it)
       if (slab.dev) {
+        if (busy_until) DMM_HIP(hipEventSynchronize(busy_until));
         DMM_HIP(hipStreamSynchronize(stream));
         pool().release(&slab);
       }
@@ -250,6 +252,7 @@ struct DeviceState {
   hipEvent_t t_gemm[2] = {nullptr, nullptr}, t_red[2] = {nullptr, nullptr};  // DMM_TIMING
   bool gemm_timed = false, red_timed = false;
   bool ran_merged = false;            // the last dmm_execute ran the merged macro-tiles
+  bool ran_k_split = false;           // ... and cut macro-tiles along K
 };
 
 void destroy_device_state(DeviceState *d) {

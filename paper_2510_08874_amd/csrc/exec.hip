@@ -3,6 +3,7 @@
 // replica sum, the replica broadcast and the measurement aids (aux_kernels.hpp), on top of the
 // pools and the uploader of device_state.hpp.
 #include <hip/hip_runtime.h>
+#include <rocprofiler-sdk-roctx/roctx.h>
 
 #include <algorithm>
 #include <cstdio>
@@ -24,6 +25,23 @@ namespace {
 static_assert(kMaxPieces == PMAX && kDescBytes == DESC_LDS - DESC_GEO && sizeof(PieceDev) == 24 &&
                   kPieceAlign * 2 >= 16 && 2 * (PMAX + 1) * 4 <= 128 && 128 + PMAX * PMAX * 24 <= DESC_GEO && kMacroTile == BM && kMacroTile == BN,
               "the planner's limits for merged macro-tiles describe the kernel's descriptor area");
+
+// A named range on the calling thread for tracing tools (rocprofv3 --marker-trace), closed when
+// the object goes out of scope: "dmm_execute" with "tables" (host assembly of the work tables and
+// their upload), "gemm" and "replica_sum" (the launches) inside it, "dmm_reduce_replicas", ...
+struct TraceRange {
+  explicit TraceRange(const char *name) { roctxRangePushA(name); }
+  ~TraceRange() { end(); }
+  void end() {                        // (ranges nest: end them in reverse order of their construction)
+    if (open_) roctxRangePop();
+    open_ = false;
+  }
+  TraceRange(const TraceRange &) = delete;
+  TraceRange &operator=(const TraceRange &) = delete;
+
+ private:
+  bool open_ = true;
+};
 
 // Whether the current device lets one workgroup have the stages plus the descriptor area (the
 // merged macro-tile kernels); decided in ensure_state.
@@ -554,11 +572,13 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   for (int64_t i = 0; i < P->C.c * P->C.tiles_per_rep(); ++i)
     if (c_ld[i] * c_es >= MAX_PITCH) return DMM_ELD;
   hipStream_t stream = (hipStream_t)hip_stream;
+  TraceRange whole("dmm_execute");
   try {
     if ((rc = ensure_state(P))) return rc;
     int device = 0;
     DMM_HIP(hipGetDevice(&device));
     if (P->merged.valid && !(flags & DMM_NO_MERGE) && g_comp_ok[device]) {
+      TraceRange tables("tables");
       // merged macro-tiles:  merged tables | replica-sum tables, one copy, then the launches
       RedLaunch red;
       MergedLaunch ml;
@@ -572,6 +592,8 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
       char *d = P->dev->gemm_table.dev();
       red.dev_base = d;
+      tables.end();
+      TraceRange gemm("gemm");
       if (timed) {
         if ((rc = timing_events(P->dev->t_gemm))) return rc;
         DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
@@ -594,11 +616,18 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
         P->dev->gemm_timed = true;
       }
+      gemm.end();
       P->dev->ran_merged = true;
-      if ((rc = fire_reduce(P, red, stream, timed))) return rc;
+      P->dev->ran_k_split = ml.n_fix > 0;
+      {
+        TraceRange tr("replica_sum");
+        if ((rc = fire_reduce(P, red, stream, timed))) return rc;
+      }
       return mark_use(P, stream);
     }
     P->dev->ran_merged = false;
+    P->dev->ran_k_split = false;
+    TraceRange tables("tables");
     if ((rc = materialize(P))) return rc;
     // The tables of all kernels go up in one copy in front of the GEMM launch, so that nothing
     // but the launches separates them:  ItemDev[] | SegDev[] | FixItem[] | RedSrc[] | replica-sum tables.
@@ -763,7 +792,9 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
       red.dev_base = P->dev->gemm_table.dev();
     }
+    tables.end();
     if (n_items > 0) {
+      TraceRange gemm("gemm");
       const ItemDev *di = (const ItemDev *)P->dev->gemm_table.dev();
       const SegDev *ds = (const SegDev *)(P->dev->gemm_table.dev() + o_segs);
       if (timed) {
@@ -798,12 +829,18 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         P->dev->gemm_timed = true;
       }
     }
-    if ((rc = fire_reduce(P, red, stream, timed))) return rc;
+    P->dev->ran_k_split = n_runs > 0;
+    {
+      TraceRange tr("replica_sum");
+      if ((rc = fire_reduce(P, red, stream, timed))) return rc;
+    }
     return mark_use(P, stream);
   } catch (const std::bad_alloc &) {
     return DMM_ENOMEM;
   }
 }
+
+int dmm_plan_ran_k_split(const dmm_plan_t *P) { return P && P->dev && P->dev->ran_k_split ? 1 : 0; }
 
 int dmm_plan_ran_merged(const dmm_plan_t *P) { return P && P->dev && P->dev->ran_merged ? 1 : 0; }
 
@@ -831,6 +868,7 @@ int dmm_reduce_replicas(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld
   if (origin_replica < 0 || origin_replica >= P->C.c) return DMM_EINVAL;
   int rc;
   if ((rc = check_lds(P->C, c_ld))) return rc;
+  TraceRange whole("dmm_reduce_replicas");
   try {
     if ((rc = ensure_state(P))) return rc;
     RedLaunch red;
@@ -849,6 +887,7 @@ int dmm_broadcast_replica(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_
   if (origin_replica < 0 || origin_replica >= P->C.c) return DMM_EINVAL;
   int rc;
   if ((rc = check_lds(P->C, c_ld))) return rc;
+  TraceRange whole("dmm_broadcast_replica");
   try {
     if ((rc = ensure_state(P))) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;

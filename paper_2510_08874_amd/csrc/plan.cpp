@@ -743,6 +743,6 @@ const char *dmm_strerror(int status) {
   }
 }
 
-int dmm_version(void) { return 2; }
+int dmm_version(void) { return 3; }
 
 }  // extern "C"

@@ -194,6 +194,8 @@ def test_k_split_of_the_last_round(dtype, dims, kcuts):
     A, B = workloads.make_operands(cfg)
     prob = _device_problem(cfg, A, B, c_fill=float("nan"))
     prob.execute()
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:    # (the sizes above are cut for 256 CUs)
+        assert prob.plan.ran_k_split()
     first = prob.c_global(0)
     A64, B64 = _to_f64(A, cfg), _to_f64(B, cfg)
     C_ref = omatmul.matmul(A, B, bf16=(dtype == "bf16"))
@@ -224,6 +226,32 @@ def test_one_plan_alternating_streams_and_output_sets():
     second = other.gather(0)
     _check(first, C_ref, A64, B64, cfg, "stream 0")
     assert np.array_equal(first, second)
+    prob.close()
+
+
+def test_work_table_grows_between_two_streams():
+    """A plan whose work table outgrows its device buffer between two calls on different streams:
+    the first call (partial sums only, a small table) may still be running when the second (with
+    the replica sum's tables, past the buffer's 64 KB) makes the library take a larger buffer; the
+    old one must not go back to the pool before the first call has finished with it."""
+    from paper_2510_08874_amd import binding
+    from paper_2510_08874_amd.tiles import TileSet
+    cfg = workloads.scaled_config("cfg4", 4608, 2100, 4608)    # 5184 blocks of the replica sum: 83 KB of tables
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"))
+    other = TileSet(cfg["C"], torch.float32, "cuda", 1, fill=float("nan"))
+    args2 = prob.plan.marshal(prob.A.tensors, prob.A.ld, prob.B.tensors, prob.B.ld, other.tensors, other.ld)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    prob.plan.execute_marshalled(prob.dtype_code, prob.args, binding.DMM_NO_REDUCE, streams[0].cuda_stream)
+    prob.plan.execute_marshalled(prob.dtype_code, args2, 0, streams[1].cuda_stream)
+    torch.cuda.synchronize()
+    partial = [prob.C.gather(r) for r in range(cfg["C"]["replication"])]
+    total = other.gather(0)
+    assert np.isfinite(total).all() and all(np.isfinite(x).all() for x in partial)
+    assert np.array_equal(total, partial[0] + partial[1])       # fp32 a + b, as the replica sum computes it
+    _check(total, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, "grown table")
+    assert np.array_equal(other.gather(1), partial[1])
     prob.close()
 
 
@@ -586,30 +614,6 @@ def test_bf16_c_tiles_need_an_unreplicated_c():
 
 # ---- merged macro-tiles: tile grids much finer than 256 x 256 ---------------------------------
 
-def _same_bits_expected(plan, cfg):
-    """The merged and the per-group work lists sum every C element over the same K-segments in the
-    same order, so they agree bit for bit, unless the library cuts the macro-tiles of the last round
-    of one of the lists along K (few macro-tiles, at least 128 K steps): partial tiles are then added
-    up separately.  Says whether neither list can be cut."""
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    bk = 32 if cfg["dtype"] == "bf16" else 16
-    c = cfg["C"]["replication"]
-    cuts = sorted(set(cfg["A"]["col_cuts"]) | set(cfg["B"]["row_cuts"]))
-    steps = 0
-    for r in range(c):
-        lo, hi = r * cfg["K"] // c, (r + 1) * cfg["K"] // c
-        pts = [lo] + [x for x in cuts if lo < x < hi] + [hi]
-        steps = max(steps, sum(-(-(b - a) // bk) for a, b in zip(pts, pts[1:])))
-        # more than 64 segments whose descriptors would leave room for fewer than 6 pieces per axis:
-        # the merged macro-tiles are run 64 segments at a time and their partial tiles added up
-        S = len(pts) - 1
-        if plan.num_merged_items() and S > 64 and (30720 - 4 * ((S + 3) // 4 * 4)) // (48 * S) < 6:
-            return False
-    if steps < 128:
-        return True
-    return all(n % cus == 0 or n % cus > cus // 2 for n in (plan.num_merged_items(), plan.num_items()))
-
-
 def _bc(dims, nb, dtype, reps=(1, 1, 1), p=8):
     M, K, N = dims
     pr, pc = 2, 4
@@ -642,6 +646,7 @@ def test_merged_macro_tiles(dims, nb, dtype, ldm, reps, p):
     assert prob.plan.num_merged_items() > 0
     prob.execute()
     assert prob.plan.ran_merged()
+    merged_cut = prob.plan.ran_k_split()
     got = prob.c_global(0)
     A64, B64 = _to_f64(A, cfg), _to_f64(B, cfg)
     C_ref = omatmul.matmul(A, B, bf16=(dtype == "bf16"))
@@ -655,7 +660,10 @@ def test_merged_macro_tiles(dims, nb, dtype, ldm, reps, p):
     plain = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
     plain.execute(flags=binding.DMM_NO_MERGE)
     assert not plain.plan.ran_merged()
-    if _same_bits_expected(plain.plan, cfg):
+    # The merged and the per-group work lists sum every C element over the same K-segments in the
+    # same order, so they agree bit for bit, unless the library cut macro-tiles of one of the runs
+    # along K (partial tiles are then added up separately); the library says whether it did.
+    if not merged_cut and not plain.plan.ran_k_split():
         assert np.array_equal(got, plain.c_global(0))
         for r in range(1, reps[2]):
             assert np.array_equal(parts[r - 1], plain.c_global(r))
@@ -679,10 +687,11 @@ def test_merged_macro_tiles_random_partitionings(seed, dtype):
     dev = _device_problem(cfg, A, B, c_fill=float("nan"))
     dev.execute()
     assert dev.plan.ran_merged() == (dev.plan.num_merged_items() > 0)
+    merged_cut = dev.plan.ran_k_split()
     got = [dev.c_global(r) for r in range(cfg["C"]["replication"])]
     _check(got[0], omatmul.matmul(A, B, bf16=(dtype == "bf16")), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
     dev.execute(flags=binding.DMM_NO_MERGE)
-    if _same_bits_expected(dev.plan, cfg):
+    if not merged_cut and not dev.plan.ran_k_split():
         for r in range(cfg["C"]["replication"]):
             assert np.array_equal(got[r], dev.c_global(r))
     dev.close()
@@ -870,6 +879,12 @@ def test_execute_rejects_bad_arguments():
     assert e.value.kind == "EINVAL"
     with pytest.raises(binding.DmmError):
         prob.plan.reduce_replicas(prob.C.tensors, prob.C.ld, origin=5)
+    # a dmm_plan flag is not a dmm_execute flag (the two sets share no bit)
+    for plan_flag in (binding.DMM_STATIONARY_B, binding.DMM_ITERATION_OFFSET, binding.DMM_MERGE_ALWAYS):
+        with pytest.raises(binding.DmmError) as e:
+            prob.plan.execute(binding.DMM_F32, prob.A.tensors, prob.A.ld, prob.B.tensors, prob.B.ld,
+                              prob.C.tensors, prob.C.ld, flags=plan_flag)
+        assert e.value.kind == "EINVAL"
     prob.close()
 
 
