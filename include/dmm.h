@@ -41,8 +41,10 @@ typedef enum {
                       or the process grid needs more ranks than one replica has */
   DMM_ENOMEM = -4, /* host or device allocation failed */
   DMM_EHIP = -5,   /* a HIP call failed; dmm_last_hip_error() holds its code */
-  DMM_ELD = -6     /* a leading dimension is smaller than the tile's width, or a row pitch (leading
+  DMM_ELD = -6,    /* a leading dimension is smaller than the tile's width, or a row pitch (leading
                       dimension times element size) of an A, B or C tile is 2^24 bytes or more */
+  DMM_ELIMIT = -7  /* dmm_reduce_replicas_static: the work tables of this call do not fit the library's
+                      static device buffer (DMM_STATIC_SCRATCH_BYTES) */
 } dmm_status;
 
 /* Element type of the A and B tiles.  All partial sums are fp32, and so are the C tiles unless
@@ -224,6 +226,22 @@ int dmm_reduce_replicas(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld
 int dmm_broadcast_replica(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld, int32_t origin_replica,
                           void *hip_stream);
 
+/* reduce_replicas for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, result (bit for bit) and error
+ * behaviour as dmm_reduce_replicas, but the call allocates nothing, on the device or on the host:
+ * the kernel's work tables (one record per C tile and per block of rows, the replicas' tile
+ * pointers and leading dimensions) are assembled in a fixed host buffer inside the library and
+ * copied on `hip_stream` into a static device buffer of DMM_STATIC_SCRATCH_BYTES, of which every
+ * GPU the library runs on holds one copy for the life of the process.  A call whose tables need
+ * more (about 48 bytes per C tile plus 16 per replica of it, and 16 bytes per 4096 elements of C)
+ * fails with DMM_ELIMIT and launches nothing.  All calls on one GPU share that buffer: calls on
+ * one stream follow each other safely (stream order), calls that overlap on different streams
+ * of one GPU race and must be ordered by the caller.  The plan's device state is not touched, so
+ * dmm_plan_destroy does not wait for work enqueued here (that work reads nothing the plan owns). */
+#define DMM_STATIC_SCRATCH_BYTES (1u << 20)
+int dmm_reduce_replicas_static(dmm_plan_t *p, void *const *c_tiles, const int64_t *c_ld,
+                               int32_t origin_replica, void *hip_stream);
+
 /* ---- measurement and test aids (not steps of the method) ---------------------------------- */
 
 /* 1 if the last dmm_execute on this plan ran the merged macro-tiles (the plan has such a list,
@@ -261,7 +279,8 @@ void dmm_plan_destroy(dmm_plan_t *p);
 
 const char *dmm_strerror(int status);
 int dmm_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread, 0 if none */
-int dmm_version(void);         /* 3: flag values of dmm_plan and dmm_execute disjoint, dmm_plan_ran_k_split */
+int dmm_version(void);         /* 3: flag values of dmm_plan and dmm_execute disjoint, dmm_reduce_replicas_static,
+                                  dmm_plan_ran_k_split */
 
 #ifdef __cplusplus
 }

@@ -14,7 +14,7 @@ from typing import Dict, List, Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdmm.so")
 
-DMM_OK, DMM_EINVAL, DMM_ESHAPE, DMM_EREPL, DMM_ENOMEM, DMM_EHIP, DMM_ELD = 0, -1, -2, -3, -4, -5, -6
+DMM_OK, DMM_EINVAL, DMM_ESHAPE, DMM_EREPL, DMM_ENOMEM, DMM_EHIP, DMM_ELD, DMM_ELIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 DMM_BF16, DMM_F32 = 1, 2
 DMM_STATIONARY_B = 0x1        # dmm_plan flags (bits 0 .. 7)
 DMM_STATIONARY_A = 0x2
@@ -25,8 +25,9 @@ DMM_TIMING = 0x200
 DMM_C_BF16 = 0x400
 DMM_NO_MERGE = 0x800
 DMM_FUSED_REDUCE = 0x1000
+DMM_STATIC_SCRATCH_BYTES = 1 << 20
 STATIONARY_FLAGS = {"C": 0, "B": DMM_STATIONARY_B, "A": DMM_STATIONARY_A}
-STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EREPL", -4: "ENOMEM", -5: "EHIP", -6: "ELD"}
+STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EREPL", -4: "ENOMEM", -5: "EHIP", -6: "ELD", -7: "ELIMIT"}
 
 
 class dmm_matrix_desc(C.Structure):
@@ -116,6 +117,8 @@ def lib() -> C.CDLL:
         L.dmm_reduce_replicas.argtypes = [P, P, P, C.c_int32, P]
         L.dmm_broadcast_replica.restype = C.c_int
         L.dmm_broadcast_replica.argtypes = [P, P, P, C.c_int32, P]
+        L.dmm_reduce_replicas_static.restype = C.c_int
+        L.dmm_reduce_replicas_static.argtypes = [P, P, P, C.c_int32, P]
         L.dmm_plan_elapsed_ms.restype = C.c_int
         L.dmm_plan_elapsed_ms.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.dmm_plan_destroy.restype = None
@@ -133,6 +136,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
            "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged", "dmm_plan_ran_k_split",
+           "dmm_reduce_replicas_static",
            "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
 
@@ -250,6 +254,14 @@ class Plan:
         if rc != DMM_OK:
             raise DmmError(rc, "dmm_reduce_replicas")
 
+    def reduce_replicas_static(self, c_tiles: Sequence, c_ld: Sequence[int], origin: int = 0,
+                               stream: Optional[int] = None) -> None:
+        ct = _table([_ptr(t) for t in c_tiles], C.c_void_p)
+        cl = _table(list(c_ld), C.c_int64)
+        rc = lib().dmm_reduce_replicas_static(self._h, ct, cl, origin, C.c_void_p(stream or 0))
+        if rc != DMM_OK:
+            raise DmmError(rc, "dmm_reduce_replicas_static")
+
     def broadcast_replica(self, c_tiles: Sequence, c_ld: Sequence[int], origin: int = 0,
                           stream: Optional[int] = None) -> None:
         ct = _table([_ptr(t) for t in c_tiles], C.c_void_p)
@@ -289,6 +301,10 @@ def dmm_execute(plan: Plan, dtype: int, a_tiles, a_ld, b_tiles, b_ld, c_tiles, c
 
 def dmm_reduce_replicas(plan: Plan, c_tiles, c_ld, origin: int = 0, stream: Optional[int] = None) -> None:
     plan.reduce_replicas(c_tiles, c_ld, origin, stream)
+
+
+def dmm_reduce_replicas_static(plan: Plan, c_tiles, c_ld, origin: int = 0, stream: Optional[int] = None) -> None:
+    plan.reduce_replicas_static(c_tiles, c_ld, origin, stream)
 
 
 def dmm_plan_destroy(plan: Plan) -> None:

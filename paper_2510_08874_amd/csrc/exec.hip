@@ -906,3 +906,143 @@ int dmm_broadcast_replica(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------ no allocation: static tables
+
+// The replica sum's work tables for dmm_reduce_replicas_static.  In host code this name stands in
+// for the symbol only: the memory is reached through the address hipGetSymbolAddress returns on
+// each device (static_scratch below), never through the name.
+static __device__ __align__(256) unsigned char scratch[DMM_STATIC_SCRATCH_BYTES];
+
+namespace dmm {
+namespace {
+
+// Device address of `scratch` on the current device (every GPU holds its own copy), looked up
+// once per device.
+int static_scratch(char **out) {
+  static std::mutex mu;
+  static char *ptr[64] = {};
+  int dev = 0;
+  DMM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return DMM_EINVAL;
+  std::lock_guard<std::mutex> g(mu);
+  if (!ptr[dev]) {
+    void *p = nullptr;
+    DMM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return DMM_EHIP;
+    ptr[dev] = (char *)p;
+  }
+  *out = ptr[dev];
+  return DMM_OK;
+}
+
+// The tables of build_reduce, laid out the same way (items | tiles | part pointers | part lds),
+// written into `dst` (capacity `cap` bytes) without any allocation: sizes first, then the records.
+int build_reduce_in_place(const dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, char *dst,
+                          size_t cap, RedLaunch *L, size_t *bytes) {
+  const Grid &C = P->C;
+  L->n_items = 0;
+  *bytes = 0;
+  if (C.c <= 1) return DMM_OK;
+  const int nparts = C.c;
+  auto rows_per_item = [](int64_t cols) { int64_t per = (RED_ELEMS + cols - 1) / cols; return per < 1 ? (int64_t)1 : per; };
+  size_t n_tiles = 0, n_items = 0;
+  for (int32_t ti = 0; ti < C.gr; ++ti)
+    for (int32_t tj = 0; tj < C.gc; ++tj) {
+      const int64_t rows = C.rc[ti + 1] - C.rc[ti], cols = C.cc[tj + 1] - C.cc[tj];
+      if (rows <= 0 || cols <= 0) continue;
+      const int64_t per = rows_per_item(cols);
+      ++n_tiles;
+      n_items += (size_t)((rows + per - 1) / per);
+    }
+  if (n_items == 0) return DMM_OK;
+  const size_t o_items = 0;
+  const size_t o_tiles = o_items + n_items * sizeof(RedItem);
+  const size_t o_parts = o_tiles + n_tiles * sizeof(RedTile);
+  const size_t o_lds = o_parts + n_tiles * (size_t)nparts * sizeof(void *);
+  const size_t total = o_lds + n_tiles * (size_t)nparts * sizeof(int64_t);
+  if (total > cap) return DMM_ELIMIT;
+  RedItem *items = (RedItem *)(dst + o_items);
+  RedTile *tiles = (RedTile *)(dst + o_tiles);
+  const float **parts = (const float **)(dst + o_parts);
+  int64_t *part_ld = (int64_t *)(dst + o_lds);
+  bool vec_ok = true;
+  size_t t_idx = 0, i_idx = 0;
+  for (int32_t ti = 0; ti < C.gr; ++ti)
+    for (int32_t tj = 0; tj < C.gc; ++tj) {
+      const int64_t rows = C.rc[ti + 1] - C.rc[ti], cols = C.cc[tj + 1] - C.cc[tj];
+      if (rows <= 0 || cols <= 0) continue;
+      RedTile t;
+      const int64_t oi = C.table_index(origin, ti, tj);
+      t.out = (float *)c_tiles[oi];
+      t.ldo = c_ld[oi];
+      t.part_begin = (int64_t)(t_idx * (size_t)nparts);
+      t.rows = (int32_t)rows;
+      t.cols = (int32_t)cols;
+      if (!t.out) return DMM_EINVAL;
+      if (((uintptr_t)t.out & 15) || (t.ldo & 3) || (cols & 3)) vec_ok = false;
+      for (int32_t rep = 0; rep < nparts; ++rep) {
+        const int64_t pi = C.table_index(rep, ti, tj);
+        const float *pp = (const float *)c_tiles[pi];
+        if (!pp) return DMM_EINVAL;
+        if (((uintptr_t)pp & 15) || (c_ld[pi] & 3)) vec_ok = false;
+        parts[t_idx * (size_t)nparts + (size_t)rep] = pp;
+        part_ld[t_idx * (size_t)nparts + (size_t)rep] = c_ld[pi];
+      }
+      const int64_t per = rows_per_item(cols);
+      for (int64_t r = 0; r < rows; r += per) {
+        RedItem it;
+        it.tile = (int32_t)t_idx;
+        it.row0 = (int32_t)r;
+        it.nrows = (int32_t)(rows - r < per ? rows - r : per);
+        it.pad = 0;
+        items[i_idx++] = it;
+      }
+      tiles[t_idx++] = t;
+    }
+  L->n_items = n_items;
+  L->o_items = o_items;
+  L->o_tiles = o_tiles;
+  L->o_parts = o_parts;
+  L->o_lds = o_lds;
+  L->nparts = nparts;
+  L->vec_ok = vec_ok;
+  *bytes = total;
+  return DMM_OK;
+}
+
+}  // namespace
+}  // namespace dmm
+
+extern "C" int dmm_reduce_replicas_static(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld,
+                                          int32_t origin_replica, void *hip_stream) {
+  using namespace dmm;
+  if (!P || !c_tiles || !c_ld) return DMM_EINVAL;
+  if (origin_replica < 0 || origin_replica >= P->C.c) return DMM_EINVAL;
+  int rc;
+  if ((rc = check_lds(P->C, c_ld))) return rc;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char *dev = nullptr;
+  if ((rc = static_scratch(&dev))) return rc;
+  // Fixed host buffers for all callers, taken in turn, one for the length of a call.  The copy
+  // below reads pageable memory out (or stages it) before hipMemcpyAsync returns; taking four
+  // buffers in turn means that even a copy that lagged behind its call would have to lag by four
+  // calls to find its source overwritten.
+  static std::mutex mu;
+  constexpr int SLOTS = 4;
+  alignas(16) static char slots[SLOTS][DMM_STATIC_SCRATCH_BYTES];
+  static int next_slot = 0;
+  std::lock_guard<std::mutex> g(mu);
+  char *staging = slots[next_slot];
+  RedLaunch L;
+  size_t bytes = 0;
+  if ((rc = build_reduce_in_place(P, c_tiles, c_ld, origin_replica, staging, DMM_STATIC_SCRATCH_BYTES, &L, &bytes))) return rc;
+  if (L.n_items == 0) return DMM_OK;
+  next_slot = (next_slot + 1) % SLOTS;
+  DMM_HIP(hipMemcpyAsync(dev, staging, bytes, hipMemcpyHostToDevice, stream));
+  hipLaunchKernelGGL(reduce_replicas_kernel, dim3((unsigned)L.n_items), dim3(RED_NT), 0, stream,
+                     (const RedItem *)(dev + L.o_items), (const RedTile *)(dev + L.o_tiles),
+                     (const float *const *)(dev + L.o_parts), (const int64_t *)(dev + L.o_lds), L.nparts, L.vec_ok ? 1 : 0);
+  DMM_HIP(hipGetLastError());
+  return DMM_OK;
+}

@@ -739,6 +739,7 @@ const char *dmm_strerror(int status) {
     case DMM_ENOMEM: return "out of memory";
     case DMM_EHIP: return "a HIP call failed (see dmm_last_hip_error)";
     case DMM_ELD: return "leading dimension smaller than the tile width";
+    case DMM_ELIMIT: return "work tables larger than the library's static device buffer";
     default: return "unknown status";
   }
 }

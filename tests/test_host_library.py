@@ -175,6 +175,7 @@ def test_null_arguments_rejected():
     assert L.dmm_plan_num_tasks(None) == 0
     assert L.dmm_execute(None, 1, None, None, None, None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_reduce_replicas(None, None, None, 0, None) == binding.DMM_EINVAL
+    assert L.dmm_reduce_replicas_static(None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_plan_ran_k_split(None) == 0
     L.dmm_plan_destroy(None)
 
