@@ -7,24 +7,32 @@
 
 One step = one pass of the whole path over one batch of synthetic input already
 resident in HBM: ``dmm_plan`` on the descriptors (host slicing + grouping), then
-``dmm_execute`` (work-table upload, the grouped-GEMM launch and, when C is
-replicated, the replica-sum launch).  W untimed steps, then exactly K timed
-steps between two device synchronisations; one JSON line on stdout.
+``dmm_execute`` (work-table upload and the grouped-GEMM launches; when C is
+replicated, the replica sum rides in the epilogue of replica 0's macro-tiles,
+which run in a second launch behind those of the other replicas).  W untimed
+steps, then exactly K timed steps between two device synchronisations; one JSON
+line on stdout.
 
 The line also carries
   roofline      the grouped-GEMM kernel against the dense bf16 (or fp32) MFMA
-                peak: algorithmic FLOPs (2 M N K per launch) / its average
-                duration, taken from HIP events the library records around the
-                launch on the launch stream (DMM_TIMING) on every one of 24 more
-                steps run right after the timed region (which carries no events);
+                peak: algorithmic FLOPs (2 m n k of the ops behind the launch) / its
+                average duration, taken from HIP events the library records around
+                the launch on the launch stream (DMM_TIMING) on every one of 24 more
+                steps run right after the timed region (which carries no events).
+                With a replicated C that is the first of the step's two launches (the
+                plain kernel over the macro-tiles of replicas 1, 2, ...);
+  roofline_fused_launch   the second launch (replica 0's macro-tiles, whose epilogue adds
+                the other replicas' partial sums and stores the sum to every replica):
+                its FLOPs against the MFMA peak and the bytes of the sum it also moves;
   per_config    (default workload only) the other configurations, a short run each:
                 plan + execute rate, kernel rate and fraction of the MFMA peak of the
                 configuration's element type, parity of a sample of rows;
+  separate_replica_sum   (replicated C) the same plan + execute steps with
+                DMM_SEPARATE_REDUCE: one GEMM launch over all macro-tiles, then the
+                replica-sum kernel; reported beside `value`, never as it, with
+  roofline_gemm_separate   that one GEMM launch against the MFMA peak, and
   roofline_replica_sum   the replica-sum kernel against peak HBM bandwidth:
                 (c + 1) * 4 bytes per C element / its average duration;
-  fused_replica_sum   (replicated C) the same plan + execute steps with DMM_FUSED_REDUCE:
-                replica 0's macro-tiles add the other replicas' partial sums in their epilogue
-                and no replica-sum kernel runs; reported beside `value`, never as it;
   cpu_baseline  the CPU oracle (fp64 triple loop, as it stands) timed on the
                 host cores on a bounded sample of rows of the same product;
   context       (bf16 workloads) what the vendor library reaches on this very box
@@ -98,7 +106,7 @@ def short_run(name, ld_multiple, np, torch, workloads, binding, DeviceProblem, o
         inflight.pop(0).destroy()
     g, r = [], []
     for _ in range(kernel_steps):
-        p = one(binding.DMM_TIMING)
+        p = one(binding.DMM_TIMING | binding.DMM_SEPARATE_REDUCE)   # one GEMM launch, then the replica-sum kernel
         gm, rm = p.elapsed_ms()
         p.destroy()
         g.append(gm)
@@ -108,7 +116,7 @@ def short_run(name, ld_multiple, np, torch, workloads, binding, DeviceProblem, o
            "ran_merged": prob.plan.ran_merged(), "steps": steps,
            "ms_per_step": round(ms, 4), "value": round(fl / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
            "pct_of_mfma_peak": round(100.0 * fl / (ms * 1e-3) / 1e12 / peak, 2),
-           "gemm_kernel": {"avg_ms": round(float(np.mean(g)), 4), "median_ms": round(float(np.median(g)), 4),
+           "gemm_kernel": {"launch": "all macro-tiles in one launch (DMM_SEPARATE_REDUCE)", "avg_ms": round(float(np.mean(g)), 4), "median_ms": round(float(np.median(g)), 4),
                            "best_ms": round(float(np.min(g)), 4), "launches_timed": len(g),
                            "achieved": round(fl / (float(np.mean(g)) * 1e-3) / 1e12, 2), "peak": peak, "unit": "TFLOP/s",
                            "frac": round(fl / (float(np.mean(g)) * 1e-3) / 1e12 / peak, 4)},
@@ -170,7 +178,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU oracle computes (0 = auto)")
     ap.add_argument("--no-context", action="store_true", help="skip the vendor-library GEMM timing")
-    ap.add_argument("--no-fused", action="store_true", help="skip the extra timing of the DMM_FUSED_REDUCE variant")
+    ap.add_argument("--reduce", choices=["fused", "separate"], default="fused",
+                    help="replicated C: the replica sum in the GEMM's epilogue (the library's default) or, with "
+                         "DMM_SEPARATE_REDUCE, in the kernel of its own, on every step of this run")
+    ap.add_argument("--no-separate", action="store_true",
+                    help="skip the extra steps with DMM_SEPARATE_REDUCE (one GEMM launch + the replica-sum kernel)")
     ap.add_argument("--no-reduce-large", action="store_true",
                     help="skip the stand-alone replica sum at c = 4 on 16384 x 16384 (5.4 GB moved)")
     ap.add_argument("--no-per-config", action="store_true",
@@ -212,6 +224,8 @@ def main() -> int:
         cfg = dict(cfg, merge_always=True)
     plan_flags = binding.DMM_MERGE_ALWAYS if args.merge == "always" else 0
     exec_flags = binding.DMM_NO_MERGE if args.merge == "never" else 0
+    if args.reduce == "separate":
+        exec_flags |= binding.DMM_SEPARATE_REDUCE
     A, B = workloads.make_operands(cfg)
     prob = DeviceProblem(cfg, A, B, ld_multiple=args.ld_multiple, c_dtype=args.c_dtype)
     stream = torch.cuda.current_stream().cuda_stream
@@ -227,7 +241,7 @@ def main() -> int:
     host_s = [0.0, 0.0]       # host seconds spent issuing (plan + execute), and waiting for finished steps
     DEPTH = 3                 # steps in flight: a plan is read back and destroyed three steps after its launch
     inflight = []
-    gemm_ms, red_ms = [], []
+    gemm_ms, red_ms, launch_ms = [], [], []
 
     KERNEL_STEPS = 24         # steps after the timed region whose kernels are bracketed by HIP events (the
                               # events cost the stream about 20 us per step, so the timed steps carry none)
@@ -247,10 +261,13 @@ def main() -> int:
     def retire():
         plan, record = inflight.pop(0)
         g, r = plan.elapsed_ms()          # waits for that step's events
+        two = plan.gemm_launch_ms() if record else None
         plan.destroy()
         if record and g >= 0.0:
             gemm_ms.append(g)
             red_ms.append(r)
+            if two[0][0] >= 0.0:
+                launch_ms.append(two)
 
     # The interpreter's cyclic collector stays off inside the loop: one full collection takes tens of
     # milliseconds here (it walks torch's objects) and would show up as a GPU idle gap of that length.
@@ -276,42 +293,42 @@ def main() -> int:
         retire()
     torch.cuda.synchronize()
 
-    # the same steps with the replica sum fused into the GEMM (DMM_FUSED_REDUCE), for the record: no
-    # replica-sum kernel, replica 0's macro-tiles add the other replicas' partial sums before they store
-    fused = None
-    if c_rep > 1 and not args.no_fused and args.merge != "always" and not prob.plan.num_merged_items():
-        fms = []
-
-        def fstep(record):
+    # the same steps with the replica sum in a kernel of its own (DMM_SEPARATE_REDUCE), for the record
+    # and for the roofline of that kernel: one GEMM launch over all macro-tiles, then the sum
+    separate = None
+    sep_gemm, sep_red = [], []
+    if c_rep > 1 and not args.no_separate and args.reduce == "fused":
+        def sstep(record):
             plan = binding.Plan(cfg["A"], cfg["B"], cfg["C"], cfg["nranks"], plan_flags)
-            plan.execute_marshalled(prob.dtype_code, prob.args, DMM_TIMING | binding.DMM_FUSED_REDUCE | exec_flags, stream)
+            plan.execute_marshalled(prob.dtype_code, prob.args, (DMM_TIMING if record else 0) | binding.DMM_SEPARATE_REDUCE | exec_flags,
+                                    stream)
             inflight.append((plan, record))
             if len(inflight) > DEPTH:
-                p0, rec = inflight.pop(0)
+                sretire()
+
+        def sretire():
+            p0, rec = inflight.pop(0)
+            if rec:
                 g, r = p0.elapsed_ms()
-                p0.destroy()
-                if rec:
-                    fms.append((g, r))
+                sep_gemm.append(g)
+                sep_red.append(r)
+            p0.destroy()
         for _ in range(10):
-            fstep(False)
+            sstep(False)
         torch.cuda.synchronize()
         tf0 = time.perf_counter()
         for _ in range(args.steps):
-            fstep(True)
+            sstep(False)
         torch.cuda.synchronize()
         tf1 = time.perf_counter()
+        for _ in range(KERNEL_STEPS):
+            sstep(True)
         while inflight:
-            p0, rec = inflight.pop(0)
-            g, r = p0.elapsed_ms()
-            p0.destroy()
-            if rec:
-                fms.append((g, r))
+            sretire()
         f_ms = (tf1 - tf0) * 1e3 / args.steps
-        fused = {"flag": "DMM_FUSED_REDUCE", "ms_per_step": round(f_ms, 4),
-                 "value": round(workloads.flops(cfg) / (f_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
-                 "gemm_both_launches_avg_ms": round(float(np.mean([g for g, _ in fms])), 4),
-                 "replica_sum_kernel_ran": bool(any(r >= 0 for _, r in fms)),
-                 "note": "same final contents of every C replica, bit for bit; not the default, not `value`"}
+        separate = {"flag": "DMM_SEPARATE_REDUCE", "ms_per_step": round(f_ms, 4),
+                    "value": round(workloads.flops(cfg) / (f_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+                    "note": "same final contents of every C replica, bit for bit; not the default, not `value`"}
 
     # the same step without re-planning (one plan, tables already resident), for the record
     torch.cuda.synchronize()
@@ -340,15 +357,44 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     fl = workloads.flops(cfg)
     value = fl / (ms_per_step * 1e-3) / 1e12
-    g_avg = float(np.mean(gemm_ms))
-    g_best = float(np.min(gemm_ms))
-    achieved = fl / (g_avg * 1e-3) / 1e12
     peak = PEAK_TFLOPS[cfg["dtype"]]
 
     traffic = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(cfg["name"], {})
+
+    def mfma_line(kernel, flops, times, **more):
+        avg, best = float(np.mean(times)), float(np.min(times))
+        ach = flops / (avg * 1e-3) / 1e12
+        return dict({"kernel": kernel, "bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(ach / peak, 4), "avg_ms": round(avg, 4), "median_ms": round(float(np.median(times)), 4),
+                     "best_ms": round(best, 4), "launches_timed": len(times),
+                     "best_frac": round(flops / (best * 1e-3) / 1e12 / peak, 4)}, **more)
+
+    es_tag = "2" if cfg["dtype"] == "bf16" else "4"
+    fused_launches = prob.plan.ran_fused()        # of the execute-only steps above: same flags as the timed steps
+    sum_read = (c_rep - 1) * 4.0 * cfg["M"] * cfg["N"]      # what a fused epilogue reads on top of the plain one
+    roof_fused = None
+    if fused_launches == 2 and launch_ms:
+        # the step's two launches, each against the MFMA peak with the FLOPs of the ops behind it
+        f0, f1 = launch_ms[0][0][1], launch_ms[0][1][1]
+        roof = mfma_line(f"grouped_gemm_kernel<{es_tag}, false>", f0, [t[0][0] for t in launch_ms],
+                         launch="first of the step's two GEMM launches: the macro-tiles of replicas 1.. "
+                                f"({f0 / fl:.3f} of the step's FLOPs)", traffic=traffic.get("gemm_bytes"))
+        roof_fused = mfma_line(f"grouped_gemm_kernel<{es_tag}, true>", f1, [t[1][0] for t in launch_ms],
+                               launch="second launch: replica 0's macro-tiles, whose epilogue adds the other replicas' "
+                                      "partial sums", partial_sum_bytes_read=sum_read)
+    elif fused_launches == 1:
+        roof = mfma_line(f"grouped_gemm_kernel<{es_tag}, true>", fl, gemm_ms,
+                         launch="the step's one launch: the macro-tiles of replicas 1.. first, then replica 0's, whose "
+                                "epilogue adds the other replicas' partial sums (written by the same workgroup earlier "
+                                "in the launch)", partial_sum_bytes_read=sum_read, traffic=traffic.get("gemm_fused_bytes"))
+    else:
+        roof = mfma_line("grouped_gemm_comp_kernel" if ran_merged else f"grouped_gemm_kernel<{es_tag}, false>", fl, gemm_ms,
+                         traffic=traffic.get("gemm_bytes"))
+    achieved = roof["achieved"]
+    fused_ran = fused_launches > 0
 
     out = {
         "metric": "plan-execute TFLOP/s and % of MFMA peak per partitioning config (1 GPU)",
@@ -359,7 +405,9 @@ def main() -> int:
                    "virtual_ranks": cfg["nranks"], "tasks": prob.plan.num_tasks(), "groups": prob.plan.num_groups(),
                    "work_items": prob.plan.num_items(), "merged_work_items": prob.plan.num_merged_items(),
                    "ran_merged": ran_merged, "merge": args.merge, "ld_multiple": args.ld_multiple, "c_dtype": args.c_dtype,
-                   "step": "dmm_plan + dmm_execute (grouped GEMM + replica sum)", "kernel_event_steps_after_the_timed_region": KERNEL_STEPS, "plan_host_us": round(plan_us, 1),
+                   "step": "dmm_plan + dmm_execute (grouped GEMM" + (" with the replica sum in its epilogue)" if fused_ran
+                                                                   else " + replica sum)" if c_rep > 1 else ")"),
+                   "kernel_event_steps_after_the_timed_region": KERNEL_STEPS, "plan_host_us": round(plan_us, 1),
                    "plan_with_op_list_host_us": round(list_us, 1),
                    "execute_only_ms_per_step": round(exec_only_ms, 4),
                    "execute_only_tflops": round(workloads.flops(cfg) / (exec_only_ms * 1e-3) / 1e12, 2),
@@ -369,25 +417,26 @@ def main() -> int:
         "device": {"name": dprop.name, "gcn_arch": getattr(dprop, "gcnArchName", ""), "compute_units": dprop.multi_processor_count,
                    "peak_used": f"{peak} TFLOP/s = published dense {cfg['dtype']} MFMA peak of MI355X "
                                 "(256 CUs x 4 SIMDs x 1024 flop/cycle x 2.4 GHz for bf16)"},
-        "roofline": {"kernel": "grouped_gemm_comp_kernel" if ran_merged else "grouped_gemm_kernel", "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "avg_ms": round(g_avg, 4), "median_ms": round(float(np.median(gemm_ms)), 4),
-                     "best_ms": round(g_best, 4), "launches_timed": len(gemm_ms),
-                     "best_frac": round(fl / (g_best * 1e-3) / 1e12 / peak, 4),
-                     "traffic": traffic.get("gemm_bytes")},
+        "roofline": roof,
     }
-    if c_rep > 1:
-        r_avg = float(np.mean(red_ms))
-        r_best = float(np.min(red_ms))
+    if roof_fused:
+        out["roofline_fused_launch"] = roof_fused
+        out["gemm_both_launches"] = {"avg_ms": round(float(np.mean(gemm_ms)), 4),
+                                     "frac_of_mfma_peak": round(fl / (float(np.mean(gemm_ms)) * 1e-3) / 1e12 / peak, 4)}
+    if separate:
+        out["separate_replica_sum"] = separate
+        out["roofline_gemm_separate"] = mfma_line(f"grouped_gemm_kernel<{es_tag}, false>", fl, sep_gemm,
+                                                  launch="all macro-tiles in one launch (DMM_SEPARATE_REDUCE)")
+    red_times = sep_red if separate else [r for r in red_ms if r >= 0.0]
+    if red_times:
+        r_avg = float(np.mean(red_times))
+        r_best = float(np.min(red_times))
         red_bytes = (c_rep + 1) * 4.0 * cfg["M"] * cfg["N"]
         out["roofline_replica_sum"] = {"kernel": "reduce_replicas_kernel", "bound": "hbm",
                                        "achieved": round(red_bytes / (r_avg * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                                        "unit": "GB/s", "frac": round(red_bytes / (r_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                                       "avg_ms": round(r_avg, 4), "best_ms": round(r_best, 4),
+                                       "avg_ms": round(r_avg, 4), "best_ms": round(r_best, 4), "launches_timed": len(red_times),
                                        "traffic": traffic.get("reduce_bytes")}
-
-    if fused:
-        out["fused_replica_sum"] = fused
 
     # parity spot check on the output of the timed run, and the CPU baseline
     from oracle import matmul as omatmul
@@ -441,7 +490,7 @@ def main() -> int:
         zp = DeviceProblem(cfg, np.zeros_like(A), np.zeros_like(B), ld_multiple=args.ld_multiple, c_dtype=args.c_dtype)
         zt = []
         for i in range(40):
-            zp.plan.execute_marshalled(zp.dtype_code, zp.args, DMM_TIMING | zp.c_flags | exec_flags, stream)
+            zp.plan.execute_marshalled(zp.dtype_code, zp.args, DMM_TIMING | binding.DMM_SEPARATE_REDUCE | zp.c_flags | exec_flags, stream)
             if i >= 10:
                 zt.append(zp.plan.elapsed_ms()[0])
         zp.close()

@@ -73,12 +73,16 @@ typedef enum { DMM_BF16 = 1, DMM_F32 = 2 } dmm_dtype;
                                 (DMM_EINVAL otherwise): the partial sums of a replicated C stay fp32, since one
                                 rounding to bf16 already costs a relative error of up to 2^-8 per element */
 #define DMM_NO_MERGE 0x800u  /* run the macro-tiles of dmm_plan_items even where the plan has merged ones */
-#define DMM_FUSED_REDUCE 0x1000u /* replicated C: no replica-sum kernel; the macro-tiles of replicas 1, 2, ...
-                                run first, those of replica 0 in a second launch behind them, where each adds
-                                the other replicas' partial sums of its region to its own, ((own + C_1) + C_2)
-                                ..., before it stores.  Same final contents of every replica, bit for bit, as
-                                without the flag.  Ignored where it does not apply: one replica of C,
-                                DMM_NO_REDUCE, merged macro-tiles, macro-tiles cut along K */
+#define DMM_SEPARATE_REDUCE 0x1000u /* replicated C: sum the replicas in a kernel of its own behind the GEMM
+                                (the one dmm_reduce_replicas runs).  Without the flag the sum is fused into the
+                                GEMM wherever that is possible: the macro-tiles of replicas 1, 2, ... run
+                                first, those of replica 0 behind them (in the same launch where each finds
+                                its partial sums written by its own workgroup, else in a second launch), and
+                                each of these adds the other replicas' partial sums of its region to its own,
+                                ((own + C_1) + C_2) ..., before it stores.  Same final contents of every
+                                replica, bit for bit, either way: the sum in replica 0, their partial sums in
+                                the others.  The separate kernel also runs, flag or not, where the fused form
+                                does not apply: merged macro-tiles, macro-tiles cut along K */
 
 /* Distributed matrix descriptor (Section 3): shape, partition object, replication
  * factor.  The partition is a tile grid given by cut points (a uniform tile
@@ -192,7 +196,7 @@ const dmm_merged_item *dmm_plan_merged_items(const dmm_plan_t *p);
  *   a_tiles, b_tiles      host arrays of device pointers, one per (replica, tile) in table order
  *   c_tiles               host array of device pointers to fp32 tiles (bf16 tiles with DMM_C_BF16)
  *   a_ld, b_ld, c_ld      host arrays, leading dimension in elements, >= the tile's width
- *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING, DMM_C_BF16, DMM_NO_MERGE, DMM_FUSED_REDUCE
+ *   flags                 0 or any of DMM_NO_REDUCE, DMM_TIMING, DMM_C_BF16, DMM_NO_MERGE, DMM_SEPARATE_REDUCE
  *   hip_stream            hipStream_t, may be null (default stream)
  * Pointers of empty tiles may be null.  Tile buffers are caller-owned and must
  * stay valid until the stream work completes.  Asynchronous: returns after
@@ -255,12 +259,27 @@ int dmm_plan_ran_merged(const dmm_plan_t *p);
  * can hold descriptors for), else 0.  Such a run sums in another order than an uncut one. */
 int dmm_plan_ran_k_split(const dmm_plan_t *p);
 
+/* How the last dmm_execute on this plan summed the replicas of C: 0 = not in the GEMM (one
+ * replica, DMM_NO_REDUCE, DMM_SEPARATE_REDUCE, or the fused form did not apply), 1 = in the GEMM,
+ * one launch, 2 = in the GEMM, replica 0's macro-tiles in a second launch (see
+ * DMM_SEPARATE_REDUCE). */
+int dmm_plan_ran_fused(const dmm_plan_t *p);
+
 /* Device time of the two kernels of the last dmm_execute(..., DMM_TIMING, ...) on this
  * plan, in milliseconds, excluding the work-table upload.  Blocks until those kernels
  * have finished.  A kernel that was not timed (or did not run) reports -1.  Either
  * output pointer may be null.  (Measurement aid for the roofline figures: Section 5.2
  * reports the best of repeated runs.) */
 int dmm_plan_elapsed_ms(dmm_plan_t *p, float *gemm_ms, float *reduce_ms);
+
+/* The two GEMM launches of a fused replica sum that needed two, one by one, for the last
+ * dmm_execute that ran with DMM_TIMING: ms[0] and flops[0] are the duration of the launch over the
+ * macro-tiles of replicas 1, 2, ... and the 2 m n k of the ops behind it, ms[1] and flops[1] those
+ * of the launch over replica 0's macro-tiles, which also adds the other replicas' partial sums.
+ * Blocks until that call's launches have finished.  ms = -1 and flops = 0 where there was nothing
+ * to report (no timing, no fused sum, a fused sum in one launch).  Errors: DMM_EINVAL (null
+ * argument), DMM_EHIP. */
+int dmm_plan_gemm_launch_ms(dmm_plan_t *p, float ms[2], double flops[2]);
 
 /* Measurement aid, independent of any plan: the rate the matrix pipes of the current device
  * sustain right now with nothing else going on.  Every SIMD of every CU issues independent
@@ -279,8 +298,9 @@ void dmm_plan_destroy(dmm_plan_t *p);
 
 const char *dmm_strerror(int status);
 int dmm_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread, 0 if none */
-int dmm_version(void);         /* 3: flag values of dmm_plan and dmm_execute disjoint, dmm_reduce_replicas_static,
-                                  dmm_plan_ran_k_split */
+int dmm_version(void);         /* 4: the replica sum is fused into the GEMM unless DMM_SEPARATE_REDUCE asks
+                                  for the kernel of its own (3: flag values of dmm_plan and dmm_execute disjoint,
+                                  dmm_reduce_replicas_static, dmm_plan_ran_k_split) */
 
 #ifdef __cplusplus
 }

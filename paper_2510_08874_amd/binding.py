@@ -24,7 +24,7 @@ DMM_NO_REDUCE = 0x100         # dmm_execute flags (bits 8 .. 15)
 DMM_TIMING = 0x200
 DMM_C_BF16 = 0x400
 DMM_NO_MERGE = 0x800
-DMM_FUSED_REDUCE = 0x1000
+DMM_SEPARATE_REDUCE = 0x1000
 DMM_STATIC_SCRATCH_BYTES = 1 << 20
 STATIONARY_FLAGS = {"C": 0, "B": DMM_STATIONARY_B, "A": DMM_STATIONARY_A}
 STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EREPL", -4: "ENOMEM", -5: "EHIP", -6: "ELD", -7: "ELIMIT"}
@@ -107,6 +107,8 @@ def lib() -> C.CDLL:
         L.dmm_plan_merged_items.argtypes = [P]
         L.dmm_plan_ran_merged.restype = C.c_int
         L.dmm_plan_ran_merged.argtypes = [P]
+        L.dmm_plan_ran_fused.restype = C.c_int
+        L.dmm_plan_ran_fused.argtypes = [P]
         L.dmm_plan_ran_k_split.restype = C.c_int
         L.dmm_plan_ran_k_split.argtypes = [P]
         L.dmm_plan_macro_tile.restype = C.c_int32
@@ -121,6 +123,8 @@ def lib() -> C.CDLL:
         L.dmm_reduce_replicas_static.argtypes = [P, P, P, C.c_int32, P]
         L.dmm_plan_elapsed_ms.restype = C.c_int
         L.dmm_plan_elapsed_ms.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        L.dmm_plan_gemm_launch_ms.restype = C.c_int
+        L.dmm_plan_gemm_launch_ms.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_double)]
         L.dmm_plan_destroy.restype = None
         L.dmm_plan_destroy.argtypes = [P]
         L.dmm_strerror.restype = C.c_char_p
@@ -135,9 +139,9 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
-           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged", "dmm_plan_ran_k_split",
+           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged", "dmm_plan_ran_k_split", "dmm_plan_ran_fused",
            "dmm_reduce_replicas_static",
-           "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_destroy", "dmm_strerror",
+           "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_gemm_launch_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
 
 
@@ -220,6 +224,10 @@ class Plan:
     def ran_merged(self) -> bool:
         return bool(lib().dmm_plan_ran_merged(self._h))
 
+    def ran_fused(self) -> int:
+        """0: the last execute did not sum C's replicas in the GEMM; 1: it did, in one launch; 2: in two."""
+        return int(lib().dmm_plan_ran_fused(self._h))
+
     def ran_k_split(self) -> bool:
         return bool(lib().dmm_plan_ran_k_split(self._h))
 
@@ -277,6 +285,15 @@ class Plan:
         if rc != DMM_OK:
             raise DmmError(rc, "dmm_plan_elapsed_ms")
         return float(g.value), float(r.value)
+
+    def gemm_launch_ms(self):
+        """((ms, flops) of the launch over replicas 1.., (ms, flops) of the launch over replica 0) of the last
+        execute with DMM_TIMING that fused the replica sum; ms = -1 where there is nothing to report."""
+        ms, fl = (C.c_float * 2)(), (C.c_double * 2)()
+        rc = lib().dmm_plan_gemm_launch_ms(self._h, ms, fl)
+        if rc != DMM_OK:
+            raise DmmError(rc, "dmm_plan_gemm_launch_ms")
+        return (float(ms[0]), float(fl[0])), (float(ms[1]), float(fl[1]))
 
     def destroy(self) -> None:
         if getattr(self, "_h", None):

@@ -5,14 +5,19 @@ from __future__ import annotations
 
 import os
 import re
+import shutil
 import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OUT = os.path.join(HERE, "_build")          # objects and the compiler's intermediate files
 LIB = os.path.join(HERE, "libdmm.so")
-SOURCES = ["plan.cpp", "exec.hip"]
+# (source, object name, extra flags): the grouped-GEMM kernels are compiled one instantiation per
+# object file (gemm_instance.hip, DMM_INSTANCE = 0 .. 5), side by side
+UNITS = [("plan.cpp", "plan", []), ("exec.hip", "exec", [])] + \
+        [("gemm_instance.hip", f"gemm_instance_{i}", [f"-DDMM_INSTANCE={i}"]) for i in range(6)]
 
 # packed-fp32 ops are switched off for all device code (a target feature of the
 # device pass; the host pass prints a harmless "not recognized" note).
@@ -22,43 +27,123 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def check_resources(remarks: str) -> None:
+def check_resources(remarks: str, want_kernel: bool) -> None:
     """The grouped GEMM keeps 256 accumulators per lane in the accumulator file and needs every
     other register to stay out of memory: fail the build if the compiler reports scratch use or
     spills for it (a change to its epilogue once cost 36 bytes of scratch per lane unnoticed)."""
-    blocks = re.split(r"remark: Function Name: ", remarks)[1:]
+    blocks = re.split(r"Function Name: ", remarks)[1:]
     seen = 0
     for b in blocks:
         name = b.split()[0]
         if "grouped_gemm_kernel" not in name:
             continue
         seen += 1
-        usage = {k: int(v) for k, v in re.findall(r"remark:\s+(ScratchSize \[bytes/lane\]|VGPRs Spill|SGPRs Spill|AGPRs): (\d+)", b)}
+        usage = {k: int(v) for k, v in re.findall(r"\s(ScratchSize \[bytes/lane\]|VGPRs Spill|SGPRs Spill|AGPRs): (\d+)", b)}
         if usage.get("ScratchSize [bytes/lane]", 0) or usage.get("VGPRs Spill", 0) or usage.get("AGPRs") != 256:
             raise RuntimeError(f"{name}: unexpected register use {usage}")
-    if seen == 0:
+    if want_kernel and seen == 0:
         raise RuntimeError("no resource report for grouped_gemm_kernel in the compiler's remarks")
+
+
+def _scalar_regs(token: str) -> set:
+    m = re.fullmatch(r"s\[(\d+):(\d+)\]", token)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.fullmatch(r"s(\d+)", token)
+    return {int(m.group(1))} if m else set()
+
+
+def check_wait_states(asm_path: str) -> None:
+    """A memory instruction must not read a scalar register within five cycles of a vector
+    instruction writing it (v_readlane from a spill lane, v_readfirstlane, a compare into a scalar
+    pair).  The compiler spaces its own instructions accordingly but does not look into inline
+    assembly, and the kernels' loads and stores are inline assembly with scalar base addresses:
+    one such pair, unspaced, sent a store to a wild address.  Walk the device assembly and fail
+    the build where a memory instruction inside an assembly statement reads a scalar register
+    less than five wait states after a vector instruction wrote it."""
+    recent = []            # (registers, wait states since, line)
+    inside = False
+    bad = []
+    with open(asm_path) as f:
+        for ln, line in enumerate(f, 1):
+            t = line.strip()
+            if t.startswith(";;#ASMSTART"):
+                inside = True
+                continue
+            if t.startswith(";;#ASMEND"):
+                inside = False
+                continue
+            t = t.split(";")[0].strip()
+            if not t or t.startswith(".") or t.endswith(":"):
+                continue
+            op, _, rest = t.partition(" ")
+            toks = rest.replace(",", " ").split()
+            if inside and re.match(r"(global_|buffer_|flat_|scratch_)", op):
+                used = set()
+                for x in toks:
+                    used |= _scalar_regs(x)
+                for regs, age, where in recent:
+                    if age < 5 and regs & used:
+                        bad.append(f"{asm_path}:{ln}: `{t}` reads a scalar register written by the vector "
+                                   f"instruction of line {where}, {age} wait states earlier")
+            step = int(toks[0], 0) + 1 if op == "s_nop" and toks else 1
+            recent = [(r, a + step, w) for r, a, w in recent if a + step < 8]
+            if toks and (op.startswith("v_readlane_b32") or op.startswith("v_readfirstlane_b32") or
+                         (op.startswith("v_cmp") and toks[0].startswith("s"))):
+                recent.append((_scalar_regs(toks[0]), 0, ln))
+    if bad:
+        raise RuntimeError("missing wait states in front of inline assembly (%d places), first:\n%s" % (len(bad), "\n".join(bad[:4])))
+
+
+def _device_asm(name: str) -> str:
+    for f in os.listdir(os.path.join(OUT, name)):
+        if "-hip-amdgcn" in f and f.endswith(".s"):
+            return os.path.join(OUT, name, f)
+    raise RuntimeError(f"no device assembly for {name} among the compiler's intermediate files")
 
 
 def build(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objs = []
-    for src in SOURCES:
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    shutil.rmtree(OUT, ignore_errors=True)
+    jobs = []
+    for src, name, more in UNITS:
+        # a directory per unit: the compiler names its intermediate files after the source, and
+        # gemm_instance.hip is compiled six times
+        os.makedirs(os.path.join(OUT, name))
+        obj = os.path.join(OUT, name, name + ".o")
+        cmd = [hipcc, *FLAGS, *more, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         if src.endswith(".hip"):
-            cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
-        if verbose:
-            print(" ".join(cmd), flush=True)
+            cmd[1:1] = ["-Rpass-analysis=kernel-resource-usage", "-save-temps=obj"]
+        jobs.append((src, name, obj, cmd))
+    # all units side by side, at most as many as the machine has cores (or MAX_JOBS)
+    limit = max(1, min(int(os.environ.get("MAX_JOBS", os.cpu_count() or 1)), len(jobs)))
+    running, objs, todo = [], [], list(jobs)
+
+    def finish(job, proc):
+        src, name, obj, cmd = job
+        _, err = proc.communicate()
+        sys.stderr.write("".join(l + "\n" for l in err.splitlines()
+                                 if "kernel-resource-usage" not in l and not re.match(r"^\s+(\d+ )?\|", l)
+                                 and "packed-fp32-ops" not in l and "argument unused during compilation" not in l))
+        if proc.returncode != 0:
+            raise subprocess.CalledProcessError(proc.returncode, cmd)
         if src.endswith(".hip"):
-            done = subprocess.run(cmd, check=False, stderr=subprocess.PIPE, text=True)
-            sys.stderr.write("".join(l + "\n" for l in done.stderr.splitlines()
-                                     if "kernel-resource-usage" not in l and not re.match(r"^\s+(\d+ )?\|", l)))
-            done.check_returncode()
-            check_resources(done.stderr)
-        else:
-            subprocess.run(cmd, check=True)
-        objs.append(obj)
+            check_resources(err, want_kernel=src == "gemm_instance.hip" and name[-1] in "0123")
+            check_wait_states(_device_asm(name))
+
+    try:
+        while todo or running:
+            while todo and len(running) < limit:
+                job = todo.pop(0)
+                if verbose:
+                    print(" ".join(job[3]), flush=True)
+                running.append((job, subprocess.Popen(job[3], stderr=subprocess.PIPE, text=True, cwd=os.path.dirname(job[2]))))
+            job, proc = running.pop(0)
+            finish(job, proc)
+            objs.append(job[2])
+    finally:
+        for _, proc in running:
+            proc.kill()
     # (the named ranges for tracing tools come from the ROCm profiler SDK's marker library)
     cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs,
            "-L/opt/rocm/lib", "-lrocprofiler-sdk-roctx", "-Wl,-rpath,/opt/rocm/lib"]

@@ -250,9 +250,12 @@ struct DeviceState {
   hipEvent_t last_use = nullptr;      // recorded after the last launch of every call
   bool last_use_recorded = false;
   hipEvent_t t_gemm[2] = {nullptr, nullptr}, t_red[2] = {nullptr, nullptr};  // DMM_TIMING
-  bool gemm_timed = false, red_timed = false;
+  hipEvent_t t_mid = nullptr;         // ... between the two GEMM launches of a fused replica sum
+  bool gemm_timed = false, red_timed = false, mid_timed = false;
+  double launch_flops[2] = {0.0, 0.0};  // 2 m n k of the ops behind each of those two launches
   bool ran_merged = false;            // the last dmm_execute ran the merged macro-tiles
   bool ran_k_split = false;           // ... and cut macro-tiles along K
+  int ran_fused = 0;                  // ... and fused the replica sum into the GEMM: in 1 launch, in 2; 0 = not
 };
 
 void destroy_device_state(DeviceState *d) {
@@ -267,6 +270,7 @@ void destroy_device_state(DeviceState *d) {
     if (d->t_gemm[i]) (void)hipEventDestroy(d->t_gemm[i]);
     if (d->t_red[i]) (void)hipEventDestroy(d->t_red[i]);
   }
+  if (d->t_mid) (void)hipEventDestroy(d->t_mid);
   delete d;
 }
 

@@ -16,6 +16,7 @@
 #include "aux_kernels.hpp"
 #include "device_state.hpp"
 #include "gemm_kernel.hpp"
+#include "gemm_launch.hpp"
 #include "plan_internal.h"
 
 namespace dmm {
@@ -57,19 +58,11 @@ int ensure_state(dmm_plan_t *P) {
   {
     std::lock_guard<std::mutex> g(mu);
     if (!done[device]) {
-      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  LDS_BYTES));
-      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  LDS_BYTES));
-      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  LDS_BYTES));
-      DMM_HIP(hipFuncSetAttribute((const void *)grouped_gemm_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  LDS_BYTES));
-      const bool ok =
-             hipFuncSetAttribute((const void *)grouped_gemm_comp_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 LDS_BYTES + DESC_LDS) == hipSuccess &&
-             hipFuncSetAttribute((const void *)grouped_gemm_comp_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 LDS_BYTES + DESC_LDS) == hipSuccess;
+      DMM_HIP(gemm_allow_lds_0());
+      DMM_HIP(gemm_allow_lds_1());
+      DMM_HIP(gemm_allow_lds_2());
+      DMM_HIP(gemm_allow_lds_3());
+      const bool ok = gemm_allow_lds_4() == hipSuccess && gemm_allow_lds_5() == hipSuccess;
       if (!ok) (void)hipGetLastError();
       g_comp_ok[device] = ok;
       done[device] = true;
@@ -553,7 +546,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   using namespace dmm;
   if (!P || !a_tiles || !a_ld || !b_tiles || !b_ld || !c_tiles || !c_ld) return DMM_EINVAL;
   if (dtype != DMM_BF16 && dtype != DMM_F32) return DMM_EINVAL;
-  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING | DMM_C_BF16 | DMM_NO_MERGE | DMM_FUSED_REDUCE)) return DMM_EINVAL;
+  if (flags & ~(DMM_NO_REDUCE | DMM_TIMING | DMM_C_BF16 | DMM_NO_MERGE | DMM_SEPARATE_REDUCE)) return DMM_EINVAL;
   const bool timed = (flags & DMM_TIMING) != 0;
   // bf16 C tiles only where a tile receives a final sum: partial sums of a replicated C stay fp32
   if ((flags & DMM_C_BF16) && P->C.c != 1) return DMM_EINVAL;
@@ -575,6 +568,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   TraceRange whole("dmm_execute");
   try {
     if ((rc = ensure_state(P))) return rc;
+    P->dev->gemm_timed = P->dev->red_timed = P->dev->mid_timed = false;
     int device = 0;
     DMM_HIP(hipGetDevice(&device));
     if (P->merged.valid && !(flags & DMM_NO_MERGE) && g_comp_ok[device]) {
@@ -598,14 +592,8 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         if ((rc = timing_events(P->dev->t_gemm))) return rc;
         DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
       }
-      if (dtype == DMM_BF16)
-        hipLaunchKernelGGL(grouped_gemm_comp_kernel<2>, dim3((unsigned)ml.n_items), dim3(NT), LDS_BYTES + DESC_LDS, stream,
-                           (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a), (const PieceDev *)(d + ml.o_b),
-                           (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
-      else
-        hipLaunchKernelGGL(grouped_gemm_comp_kernel<4>, dim3((unsigned)ml.n_items), dim3(NT), LDS_BYTES + DESC_LDS, stream,
-                           (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a), (const PieceDev *)(d + ml.o_b),
-                           (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
+      launch_grouped_gemm_comp((int)es, (unsigned)ml.n_items, stream, (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a),
+                               (const PieceDev *)(d + ml.o_b), (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
       DMM_HIP(hipGetLastError());
       if (ml.n_fix > 0) {
         hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(ml.n_fix * (BM / FIX_ROWS))), dim3(256), 0, stream,
@@ -619,6 +607,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       gemm.end();
       P->dev->ran_merged = true;
       P->dev->ran_k_split = ml.n_fix > 0;
+      P->dev->ran_fused = 0;
       {
         TraceRange tr("replica_sum");
         if ((rc = fire_reduce(P, red, stream, timed))) return rc;
@@ -627,6 +616,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
     }
     P->dev->ran_merged = false;
     P->dev->ran_k_split = false;
+    P->dev->ran_fused = 0;
     TraceRange tables("tables");
     if ((rc = materialize(P))) return rc;
     // The tables of all kernels go up in one copy in front of the GEMM launch, so that nothing
@@ -739,19 +729,25 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         }
       for (FixItem &f : fixes) f.parts = (const float *)(P->dev->split_buf + (uintptr_t)f.parts);
     }
-    // Fused replica sum: the macro-tiles of replicas 1, 2, ... go first, in a launch of their own;
-    // those of replica 0 follow in a second launch (stream order: every partial sum is complete by
-    // then) and add the others' partial sums to their own before they store.  No replica-sum
+    // Fused replica sum: the macro-tiles of replicas 1, 2, ... go first, those of replica 0 behind
+    // them, and these add the others' partial sums to their own before they store.  No replica-sum
     // kernel runs.  (Not together with the K-split, whose runs store through a scratch buffer.)
-    const bool fuse = (flags & DMM_FUSED_REDUCE) && !(flags & DMM_NO_REDUCE) && P->C.c > 1 && n_runs == 0;
+    // One launch where every macro-tile of replica 0 finds the partial sums of its region written
+    // by its own workgroup earlier in the same launch (workgroup w walks items w, w + grid, ... in
+    // order, and a wave reads back exactly the elements it stored itself); otherwise two launches,
+    // replica 0's second (stream order: every partial sum is complete by then).
+    const bool fuse = !(flags & (DMM_SEPARATE_REDUCE | DMM_NO_REDUCE)) && P->C.c > 1 && n_runs == 0;
     std::vector<RedSrc> reds;
     size_t n_first = hi.size();               // items of the first launch
+    bool one_launch = false;
     if (fuse) {
       std::vector<ItemDev> others, origin;
       others.reserve(hi.size());
       origin.reserve(hi.size());
+      std::vector<std::vector<uint32_t>> of_rep((size_t)P->C.c);     // per replica: plan items in list order
       for (size_t i = 0; i < n_plan_items; ++i) {
         const dmm_work_item &w = P->items[i];
+        of_rep[(size_t)w.c_rep].push_back((uint32_t)i);
         if (w.c_rep != 0) {
           others.push_back(hi[i]);
           continue;
@@ -770,6 +766,25 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         origin.push_back(d);
       }
       n_first = others.size();
+      // One launch?  Replica r's k-th macro-tile has to cover the region of replica 0's k-th, and sit
+      // a multiple of the grid in front of it in the combined list.
+      const size_t grid = std::min<size_t>(n_plan_items, (size_t)cus);
+      one_launch = grid > 0 && !origin.empty();
+      std::vector<uint32_t> pos(n_plan_items, 0);                    // position in `others` of a plan item
+      {
+        uint32_t at = 0;
+        for (size_t i = 0; i < n_plan_items; ++i)
+          if (P->items[i].c_rep != 0) pos[i] = at++;
+      }
+      for (int32_t r = 1; r < P->C.c && one_launch; ++r) {
+        if (of_rep[(size_t)r].size() != of_rep[0].size()) one_launch = false;
+        for (size_t k = 0; k < of_rep[0].size() && one_launch; ++k) {
+          const dmm_work_item &o = P->items[of_rep[0][k]], &s = P->items[of_rep[(size_t)r][k]];
+          if (o.c_ti != s.c_ti || o.c_tj != s.c_tj || o.m0 != s.m0 || o.n0 != s.n0 || o.m_ext != s.m_ext ||
+              o.n_ext != s.n_ext || (n_first + k - pos[of_rep[(size_t)r][k]]) % grid != 0)
+            one_launch = false;
+        }
+      }
       hi = std::move(others);
       hi.insert(hi.end(), origin.begin(), origin.end());
     }
@@ -802,22 +817,23 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
         DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
       }
       const RedSrc *dr = (const RedSrc *)(P->dev->gemm_table.dev() + o_red);
-      const size_t part[2][2] = {{0, n_first}, {n_first, n_items - n_first}};   // {first item, count} per launch
+      // {first item, count} per launch
+      const size_t part[2][2] = {{0, one_launch ? n_items : n_first}, {n_first, one_launch ? 0 : n_items - n_first}};
       for (int l = 0; l < 2; ++l) {
         if (part[l][1] == 0) continue;
-        const bool sums = fuse && l == 1;       // the launch whose macro-tiles add the other replicas' partial sums
+        const bool sums = fuse && (l == 1 || one_launch);   // the launch whose macro-tiles add the other replicas' partial sums
         // one workgroup per CU at most: workgroup w walks items w, w + grid, w + 2 grid, ... of its launch
         const int count = (int)part[l][1];
-        const dim3 grid((unsigned)std::min(count, cus));
-        if (dtype == DMM_BF16 && !sums)
-          hipLaunchKernelGGL((grouped_gemm_kernel<2, false>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
-        else if (dtype == DMM_BF16)
-          hipLaunchKernelGGL((grouped_gemm_kernel<2, true>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
-        else if (!sums)
-          hipLaunchKernelGGL((grouped_gemm_kernel<4, false>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
-        else
-          hipLaunchKernelGGL((grouped_gemm_kernel<4, true>), grid, dim3(NT), LDS_BYTES, stream, di + part[l][0], ds, dr, count);
+        launch_grouped_gemm((int)es, sums, (unsigned)std::min(count, cus), stream, di + part[l][0], ds, dr, count);
         DMM_HIP(hipGetLastError());
+        if (timed && fuse && !one_launch && l == 0 && part[1][1] > 0) {
+          if (!P->dev->t_mid) DMM_HIP(hipEventCreate(&P->dev->t_mid));
+          DMM_HIP(hipEventRecord(P->dev->t_mid, stream));
+          P->dev->mid_timed = true;
+          P->dev->launch_flops[0] = P->dev->launch_flops[1] = 0.0;
+          for (const dmm_task &t : P->tasks)
+            P->dev->launch_flops[t.c_rep == 0 ? 1 : 0] += 2.0 * (double)(t.m1 - t.m0) * (double)(t.n1 - t.n0) * (double)(t.k1 - t.k0);
+        }
       }
       if (!fixes.empty()) {
         hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(fixes.size() * (BM / FIX_ROWS))), dim3(256), 0, stream,
@@ -830,6 +846,7 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
       }
     }
     P->dev->ran_k_split = n_runs > 0;
+    P->dev->ran_fused = !fuse ? 0 : one_launch ? 1 : 2;
     {
       TraceRange tr("replica_sum");
       if ((rc = fire_reduce(P, red, stream, timed))) return rc;
@@ -839,6 +856,22 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
     return DMM_ENOMEM;
   }
 }
+
+int dmm_plan_gemm_launch_ms(dmm_plan_t *P, float ms[2], double flops[2]) {
+  using namespace dmm;
+  if (!P || !ms || !flops) return DMM_EINVAL;
+  ms[0] = ms[1] = -1.f;
+  flops[0] = flops[1] = 0.0;
+  if (!P->dev || !P->dev->gemm_timed || !P->dev->mid_timed) return DMM_OK;
+  DMM_HIP(hipEventSynchronize(P->dev->t_gemm[1]));
+  DMM_HIP(hipEventElapsedTime(&ms[0], P->dev->t_gemm[0], P->dev->t_mid));
+  DMM_HIP(hipEventElapsedTime(&ms[1], P->dev->t_mid, P->dev->t_gemm[1]));
+  flops[0] = P->dev->launch_flops[0];
+  flops[1] = P->dev->launch_flops[1];
+  return DMM_OK;
+}
+
+int dmm_plan_ran_fused(const dmm_plan_t *P) { return P && P->dev ? P->dev->ran_fused : 0; }
 
 int dmm_plan_ran_k_split(const dmm_plan_t *P) { return P && P->dev && P->dev->ran_k_split ? 1 : 0; }
 

@@ -219,11 +219,14 @@ __device__ __forceinline__ void load_to_lds_16(gptr base, unsigned lane_off, uns
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base)
-               : "memory", "m0");
+               : "memory");
 }
-// (All forms name M0, and the masked ones EXEC, as clobbered.  The masked ones leave EXEC at all
-// ones: they are only ever reached in wave-uniform control flow with every lane active, which is
-// how the whole of run_item runs; the divergent repairs of publish_fix use none of them.)
+// (M0 and EXEC cannot be named as clobbered: the compiler treats both as reserved, refuses them
+// in a clobber list with a warning, and never carries a value of its own in M0 across a statement:
+// it writes M0 right in front of each instruction of its own that reads it.  The masked forms
+// leave EXEC at all ones: they are only ever reached in wave-uniform control flow with every lane
+// active, which is how the whole of run_item runs; the divergent repairs of publish_fix use none
+// of them.)
 // The form used in the K loop: the LDS address is a wave-uniform base plus a compile-time
 // constant, and the lanes that take part are given as an exec mask (all ones for an ordinary
 // step, fewer when some lanes would overrun a tile buffer, zero when there is nothing to load),
@@ -237,7 +240,7 @@ __device__ __forceinline__ void load_to_lds_16_masked(gptr base, unsigned lane_o
                "global_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base), "n"(IMM), "s"(lo), "s"(hi)
-               : "memory", "scc", "m0", "exec");
+               : "memory", "scc");
 }
 
 // The form of the quiet iterations of the K loop, where every lane takes part for certain: no exec
@@ -248,14 +251,14 @@ __device__ __forceinline__ void load_to_lds_16_plain(gptr base, unsigned lane_of
   asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_base), "n"(IMM)
-               : "memory", "scc", "m0");
+               : "memory", "scc");
 }
 template <int IMM>
 __device__ __forceinline__ void load_to_lds_16_plain_v(gptr addr, unsigned lds_base) {
   asm volatile("s_add_u32 m0, %1, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(addr), "s"(lds_base), "n"(IMM)
-               : "memory", "scc", "m0");
+               : "memory", "scc");
 }
 
 // The same two forms with a full 64-bit address per lane (merged macro-tiles: the lanes of one
@@ -264,7 +267,7 @@ __device__ __forceinline__ void load_to_lds_16_v(gptr addr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(addr), "s"(lds_base)
-               : "memory", "m0");
+               : "memory");
 }
 template <int IMM>
 __device__ __forceinline__ void load_to_lds_16_masked_v(gptr addr, unsigned lds_base, unsigned lo, unsigned hi) {
@@ -272,7 +275,7 @@ __device__ __forceinline__ void load_to_lds_16_masked_v(gptr addr, unsigned lds_
                "global_load_lds_dwordx4 %0, off\n\ts_mov_b64 exec, -1"
                :
                : "v"(addr), "s"(lds_base), "n"(IMM), "s"(lo), "s"(hi)
-               : "memory", "scc", "m0", "exec");
+               : "memory", "scc");
 }
 
 // p + d where the caller knows that the low half of the address does not carry.
@@ -357,10 +360,24 @@ __device__ __forceinline__ void acc_clear() {
   asm volatile("s_nop 7" : "+v"(z));
   acc_clear_tiles<ES>(z, std::make_integer_sequence<int, FM * FN>{});
 }
-// partial sum number REG to base + off + IMM (a non-temporal store straight from the accumulator file)
+// partial sum number REG to base + off + IMM (a non-temporal store straight from the accumulator file).
+// The base travels in a scalar register pair.  Where the compiler has only just fetched that pair with
+// a vector instruction (v_readlane from a spill lane, v_readfirstlane), a memory instruction must not
+// read it for five cycles; the compiler inserts such wait states between its own instructions but does
+// not look into assembly, so the statement brings them along.
 template <int REG, int IMM>
 __device__ __forceinline__ void acc_store(unsigned off, const __attribute__((address_space(1))) char *base) {
-  asm volatile("global_store_dword %0, a[%2], %1 offset:%3 nt" : : "v"(off), "s"(base), "n"(REG), "n"(IMM) : "memory");
+  asm volatile("s_nop 4\n\tglobal_store_dword %0, a[%2], %1 offset:%3 nt" : : "v"(off), "s"(base), "n"(REG), "n"(IMM) : "memory");
+}
+// one row of a full macro-tile: partial sums R0, R0 + 16, R0 + 32, R0 + 48 (the row's four column blocks)
+template <int R0>
+__device__ __forceinline__ void acc_store_row(unsigned off, const __attribute__((address_space(1))) char *base) {
+  asm volatile("s_nop 4\n\t"
+               "global_store_dword %0, a[%2], %1 offset:0 nt\n\t"
+               "global_store_dword %0, a[%3], %1 offset:128 nt\n\t"
+               "global_store_dword %0, a[%4], %1 offset:256 nt\n\t"
+               "global_store_dword %0, a[%5], %1 offset:384 nt"
+               : : "v"(off), "s"(base), "n"(R0), "n"(R0 + 16), "n"(R0 + 32), "n"(R0 + 48) : "memory");
 }
 // partial sum number REG (= 16 t + r) as a value
 template <int REG>
@@ -511,7 +528,7 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
   int lead_seg = 0, lead_kpos = 0;                       // lead cursor
   int lead_left = 0;                                     // steps left in its segment, the current one included
   bool lead_tail = false;                                // the segment's last step is a K tail
-  bool lead_seg_safe = true;                             // no step of the segment can overrun a tile buffer
+  int lead_unsafe = 0;                                   // the segment's last this-many steps may overrun a tile buffer
   bool lead_seg_carry = false;                           // (merged items) some lane's address crosses a 4 GB line in it
   unsigned ld_a_pitch = 0, ld_b_pitch = 0;               // row pitch in bytes of the lead segment's A and B tiles
   unsigned ld_a_off[LOADS], ld_b_off[LOADS];             // this lane's byte offsets at those pitches (per segment)
@@ -552,9 +569,15 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
     int64_t a_left, b_left, a_need, b_need;
     step_geometry(sd, kpos0, ld_a, ld_b, a_left, b_left);
     step_need(sd, a_need, b_need);
-    // the last step of the segment reads furthest: if it is safe, all are
-    lead_seg_safe = a_left - (int64_t)(lead_left - 1) * (BK * ES) >= a_need &&
-                    b_left - (int64_t)(lead_left - 1) * ld_b_step >= b_need;
+    // A later step reads further.  Where a segment ends at the end of its tile, its last step (a K
+    // tail, as a rule) reaches past the tile buffer in the tile's last rows, and only that step:
+    // so the question is how many steps at the end of the segment are not safe, not whether all are.
+    lead_unsafe = lead_left;
+#pragma unroll
+    for (int u = 3; u >= 0; --u) {
+      const int64_t last = (int64_t)lead_left - 1 - u;   // the step in front of the last u
+      if (last >= 0 && a_left - last * (BK * ES) >= a_need && b_left - last * ld_b_step >= b_need) lead_unsafe = u;
+    }
   };
   auto open_lead = [&](int kpos0) {                      // lead enters segment lead_seg at kpos0 (a multiple of BK)
     if constexpr (COMP) {
@@ -563,12 +586,13 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
       lead_left = (klen - kpos0 + BK - 1) / BK;
       lead_tail = klen % BK != 0;
       const int64_t more = lead_left - 1;                // the segment's last step reads furthest
-      bool overrun = false, carry = false;
+      bool overrun = false, overrun1 = false, carry = false;   // overrun1: already in the step before the last
 #pragma unroll
       for (int i = 0; i < LOADS; ++i) {
         int64_t room;
         a_chunk(lead_seg, kpos0, i, ca[i], room);
         overrun |= room - more * (BK * ES) < 16;
+        overrun1 |= room - (more - 1) * (BK * ES) < 16;
         carry |= (uint64_t)(uint32_t)(uintptr_t)ca[i] + (uint64_t)more * (BK * ES) > 0xFFFFFFFFull;
       }
 #pragma unroll
@@ -577,11 +601,14 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
         b_chunk(lead_seg, kpos0, i, cbv[i], room);
         bstep[i] = (unsigned)BK * cx.bd[lead_seg * cx.Q + bp[i]].pitch;
         overrun |= room - more * (int64_t)bstep[i] < 16;
+        overrun1 |= room - (more - 1) * (int64_t)bstep[i] < 16;
         carry |= (uint64_t)(uint32_t)(uintptr_t)cbv[i] + (uint64_t)more * bstep[i] > 0xFFFFFFFFull;
       }
       lead_seg_carry = __builtin_amdgcn_ballot_w64(carry) != 0;
-      overrun |= lead_seg_carry;
-      lead_seg_safe = __builtin_amdgcn_ballot_w64(overrun) == 0;
+      // none, the last step only, or (also where an address would carry) all of them
+      lead_unsafe = lead_seg_carry ? lead_left
+                    : __builtin_amdgcn_ballot_w64(overrun) == 0 ? 0
+                    : (more >= 1 && __builtin_amdgcn_ballot_w64(overrun1) == 0) ? 1 : lead_left;
       return;
     }
     open_lead_at(segs[it.seg_begin + lead_seg], kpos0);
@@ -608,7 +635,7 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
     if (exists) {
       fix = lead_tail && lead_left == 1 ? 1u : 0u;
       all = ~0u;
-      if (__builtin_expect(!lead_seg_safe, 0)) {
+      if (__builtin_expect(lead_left <= lead_unsafe, 0)) {
         if constexpr (COMP) {
           // (addresses computed afresh: in a segment with a carry the slots' own may have wrapped)
           bool a_ok[LOADS], b_ok[LOADS], bad = lead_seg_carry;
@@ -831,7 +858,7 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
                      "global_load_lds_dwordx4 %0, off"
                      :
                      : "v"(addr), "s"(stage_base), "n"(IMM), "v"(f.a[i]), "v"(u.v), "n"(16 * n), "n"(16 * n + 15)
-                     : "memory", "scc", "m0", DMM_ACC_REGS);
+                     : "memory", "scc", DMM_ACC_REGS);
         addr = add_low(addr, j < LOADS ? (unsigned)(BK * ES) : bstep[j < LOADS ? 0 : j - LOADS]);
       } else {
         const unsigned off = j < LOADS ? ld_a_off[j < LOADS ? j : 0] : ld_b_off[j < LOADS ? 0 : j - LOADS];
@@ -840,7 +867,7 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
                      "global_load_lds_dwordx4 %0, %1"
                      :
                      : "v"(off), "s"(base), "s"(stage_base), "n"(IMM), "v"(f.a[i]), "v"(u.v), "n"(16 * n), "n"(16 * n + 15)
-                     : "memory", "scc", "m0", DMM_ACC_REGS);
+                     : "memory", "scc", DMM_ACC_REGS);
       }
     }
   };
@@ -937,8 +964,10 @@ __device__ __forceinline__ void run_item(const ItemDev &first_item, const SegDev
   // advances follow it.  Their effect on the cursor is booked here, in advance.
   auto plan_quiet = [&](int lead_idx) {
     int q = 0;
-    if (loads_on && lead_seg_safe && (fix_bits & 7u) == 0u) {
-      q = lead_left - 1 - (lead_tail ? 1 : 0);           // inside the segment, short of its K tail
+    if (loads_on && (fix_bits & 7u) == 0u) {
+      // inside the segment, short of its K tail and of the steps that may overrun a tile buffer
+      const int keep = lead_tail && lead_unsafe == 0 ? 1 : lead_unsafe;
+      q = lead_left - 1 - keep;
       const int r = n - 1 - lead_idx;                    // inside the item
       q = q < r ? q : r;
       q = q > 0 ? q : 0;
@@ -1113,7 +1142,10 @@ __device__ __forceinline__ void store_macro_tile(const ItemDev &it, const RedSrc
       constexpr int i = decltype(xc)::value / 16, r = decltype(xc)::value % 16;
       constexpr int dr = i * 32 + 8 * (r >> 2) + (r & 3);
       asm volatile("" : "+v"(o));
-      if (FULL || row0 + dr < it.m_ext) {
+      if constexpr (FULL && wide) {
+        static_assert(FN == 4, "acc_store_row stores four column blocks");
+        acc_store_row<16 * i * FN + r>(o, cbytes);
+      } else if (FULL || row0 + dr < it.m_ext) {
         static_for<FN>([&](auto jc) {
           constexpr int j = decltype(jc)::value;
           constexpr int REG = 16 * (i * FN + j) + r;

@@ -744,6 +744,6 @@ const char *dmm_strerror(int status) {
   }
 }
 
-int dmm_version(void) { return 3; }
+int dmm_version(void) { return 4; }
 
 }  // extern "C"

@@ -658,7 +658,7 @@ def test_merged_macro_tiles(dims, nb, dtype, ldm, reps, p):
             assert torch.isnan(t[:, c1 - c0:]).all(), "padding of a C tile was written"
     prob.close()
     plain = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
-    plain.execute(flags=binding.DMM_NO_MERGE)
+    plain.execute(flags=binding.DMM_NO_MERGE | binding.DMM_SEPARATE_REDUCE)
     assert not plain.plan.ran_merged()
     # The merged and the per-group work lists sum every C element over the same K-segments in the
     # same order, so they agree bit for bit, unless the library cut macro-tiles of one of the runs
@@ -797,25 +797,34 @@ def test_merged_macro_tiles_across_a_4gb_line():
     prob.close()
 
 
-# ---- fused replica sum (DMM_FUSED_REDUCE) -----------------------------------------------------
+# ---- fused replica sum (the default) against DMM_SEPARATE_REDUCE -----------------------------------------------------
 
-def _fused_against_plain(cfg, A, B, ldm=1, must_fuse=True):
+def _fused_against_plain(cfg, A, B, ldm=1, must_fuse=True, launches=2):
     from paper_2510_08874_amd import binding
     c = cfg["C"]["replication"]
     plain = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
-    plain.execute(flags=binding.DMM_NO_MERGE)
+    plain.execute(flags=binding.DMM_NO_MERGE | binding.DMM_SEPARATE_REDUCE)
     want = [plain.c_global(r) for r in range(c)]
     red_ms = None
-    plain.execute(flags=binding.DMM_NO_MERGE | binding.DMM_TIMING)
+    plain.execute(flags=binding.DMM_NO_MERGE | binding.DMM_SEPARATE_REDUCE | binding.DMM_TIMING)
     torch.cuda.synchronize()
     assert plain.plan.elapsed_ms()[1] >= 0.0            # the replica-sum kernel ran
     plain.close()
     fused = _device_problem(cfg, A, B, ld_multiple=ldm, c_fill=float("nan"))
-    fused.execute(flags=binding.DMM_NO_MERGE | binding.DMM_FUSED_REDUCE | binding.DMM_TIMING)
+    fused.execute(flags=binding.DMM_NO_MERGE | binding.DMM_TIMING)
     torch.cuda.synchronize()
     red_ms = fused.plan.elapsed_ms()[1]
     if must_fuse:
         assert red_ms < 0.0, "the replica-sum kernel ran although the sum was to be fused"
+        assert fused.plan.ran_fused() == launches
+        (ms0, fl0), (ms1, fl1) = fused.plan.gemm_launch_ms()      # the two launches, one by one
+        if launches == 2:
+            assert ms0 > 0.0 and ms1 > 0.0 and abs(ms0 + ms1 - fused.plan.elapsed_ms()[0]) < 1e-3
+            assert fl0 + fl1 == 2.0 * cfg["M"] * cfg["K"] * cfg["N"] and fl0 > 0.0 and fl1 > 0.0
+        else:
+            assert ms0 < 0.0 and ms1 < 0.0 and fused.plan.elapsed_ms()[0] > 0.0
+    else:
+        assert fused.plan.ran_fused() in (0, 2)
     for r in range(c):
         assert np.array_equal(want[r], fused.c_global(r)), f"replica {r} differs"
     fused.close()
@@ -831,6 +840,18 @@ def test_fused_replica_sum_families(name, dims, ldm):
     cfg = workloads.scaled_config(name, *dims)
     A, B = workloads.make_operands(cfg)
     C0 = _fused_against_plain(cfg, A, B, ldm)
+    _check(C0, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+
+
+def test_fused_replica_sum_in_one_launch():
+    """Where replica 1's k-th macro-tile sits a whole number of rounds in front of replica 0's k-th in the
+    work list, one launch does both: the workgroup that stored a partial sum reads it back itself.
+    (2.5D on 4096 x 4096: 256 macro-tiles per replica, one round of a 256-CU device each.)"""
+    if torch.cuda.get_device_properties(0).multi_processor_count != 256:
+        pytest.skip("the work list is laid out for one round per replica on 256 compute units")
+    cfg = workloads.scaled_config("cfg4", 4096, 512, 4096)
+    A, B = workloads.make_operands(cfg)
+    C0 = _fused_against_plain(cfg, A, B, launches=1)
     _check(C0, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
 
 

@@ -177,13 +177,19 @@ def test_null_arguments_rejected():
     assert L.dmm_reduce_replicas(None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_reduce_replicas_static(None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_plan_ran_k_split(None) == 0
+    assert L.dmm_plan_ran_fused(None) == 0
+    assert L.dmm_plan_gemm_launch_ms(None, None, None) == binding.DMM_EINVAL
+    ok = dict(rows=8, cols=8, row_cuts=(0, 8), col_cuts=(0, 8), proc_rows=1, proc_cols=1, replication=1)
+    fresh = binding.Plan(ok, ok, ok, 1)
+    assert fresh.gemm_launch_ms() == ((-1.0, 0.0), (-1.0, 0.0))      # nothing ran: nothing to report, no device call
+    fresh.destroy()
     L.dmm_plan_destroy(None)
 
 
 def test_plan_and_execute_flags_share_no_bit():
     """A flag handed to the wrong call is rejected instead of being taken for another one."""
     plan_flags = binding.DMM_STATIONARY_B | binding.DMM_STATIONARY_A | binding.DMM_ITERATION_OFFSET | binding.DMM_MERGE_ALWAYS
-    exec_flags = [binding.DMM_NO_REDUCE, binding.DMM_TIMING, binding.DMM_C_BF16, binding.DMM_NO_MERGE, binding.DMM_FUSED_REDUCE]
+    exec_flags = [binding.DMM_NO_REDUCE, binding.DMM_TIMING, binding.DMM_C_BF16, binding.DMM_NO_MERGE, binding.DMM_SEPARATE_REDUCE]
     ok = dict(rows=8, cols=8, row_cuts=(0, 8), col_cuts=(0, 8), proc_rows=1, proc_cols=1, replication=1)
     for f in exec_flags:
         assert f & plan_flags == 0
@@ -192,7 +198,7 @@ def test_plan_and_execute_flags_share_no_bit():
         assert e.value.kind == "EINVAL"
     header = open(os.path.join(ROOT, "include", "dmm.h")).read()
     for name in ("DMM_STATIONARY_B", "DMM_STATIONARY_A", "DMM_ITERATION_OFFSET", "DMM_MERGE_ALWAYS", "DMM_NO_REDUCE",
-                 "DMM_TIMING", "DMM_C_BF16", "DMM_NO_MERGE", "DMM_FUSED_REDUCE"):
+                 "DMM_TIMING", "DMM_C_BF16", "DMM_NO_MERGE", "DMM_SEPARATE_REDUCE"):
         value = int(re.search(r"#define %s (0x[0-9a-fA-F]+)u" % name, header).group(1), 16)
         assert value == getattr(binding, name), name
 
