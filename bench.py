@@ -335,8 +335,10 @@ def main() -> int:
     te0 = time.perf_counter()
     for _ in range(args.steps):
         prob.plan.execute_marshalled(prob.dtype_code, prob.args, prob.c_flags | exec_flags, stream)
+    exec_only_host_us = (time.perf_counter() - te0) * 1e6 / args.steps     # host time of the calls alone
     torch.cuda.synchronize()
     exec_only_ms = (time.perf_counter() - te0) * 1e3 / args.steps
+    tables_reused = prob.plan.table_reused()
     gc.enable()
 
     # host-only cost of planning, for the record
@@ -411,6 +413,7 @@ def main() -> int:
                    "plan_with_op_list_host_us": round(list_us, 1),
                    "execute_only_ms_per_step": round(exec_only_ms, 4),
                    "execute_only_tflops": round(workloads.flops(cfg) / (exec_only_ms * 1e-3) / 1e12, 2),
+                   "execute_only_host_us_per_call": round(exec_only_host_us, 1), "execute_only_tables_reused": tables_reused,
                    "host_issue_us_per_step": round(host_s[0] / args.steps * 1e6, 1),
                    "host_wait_us_per_step": round(host_s[1] / args.steps * 1e6, 1)},
         "pct_of_mfma_peak": round(100.0 * value / peak, 2),

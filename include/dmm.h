@@ -259,6 +259,12 @@ int dmm_plan_ran_merged(const dmm_plan_t *p);
  * can hold descriptors for), else 0.  Such a run sums in another order than an uncut one. */
 int dmm_plan_ran_k_split(const dmm_plan_t *p);
 
+/* 1 if the last dmm_execute on this plan found the work tables of the call before it in place
+ * and launched from them (same element type, same flags apart from DMM_TIMING, same device, same
+ * contents of all six pointer and leading-dimension tables), 0 if it assembled and uploaded
+ * them.  The tables hold addresses, not data: what the tiles contain plays no part. */
+int dmm_plan_table_reused(const dmm_plan_t *p);
+
 /* How the last dmm_execute on this plan summed the replicas of C: 0 = not in the GEMM (one
  * replica, DMM_NO_REDUCE, DMM_SEPARATE_REDUCE, or the fused form did not apply), 1 = in the GEMM,
  * one launch, 2 = in the GEMM, replica 0's macro-tiles in a second launch (see

@@ -107,6 +107,8 @@ def lib() -> C.CDLL:
         L.dmm_plan_merged_items.argtypes = [P]
         L.dmm_plan_ran_merged.restype = C.c_int
         L.dmm_plan_ran_merged.argtypes = [P]
+        L.dmm_plan_table_reused.restype = C.c_int
+        L.dmm_plan_table_reused.argtypes = [P]
         L.dmm_plan_ran_fused.restype = C.c_int
         L.dmm_plan_ran_fused.argtypes = [P]
         L.dmm_plan_ran_k_split.restype = C.c_int
@@ -139,7 +141,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
-           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged", "dmm_plan_ran_k_split", "dmm_plan_ran_fused",
+           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged", "dmm_plan_ran_k_split", "dmm_plan_ran_fused", "dmm_plan_table_reused",
            "dmm_reduce_replicas_static",
            "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_gemm_launch_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
@@ -223,6 +225,10 @@ class Plan:
 
     def ran_merged(self) -> bool:
         return bool(lib().dmm_plan_ran_merged(self._h))
+
+    def table_reused(self) -> bool:
+        """The last execute launched from the work tables the call before it had left on the device."""
+        return bool(lib().dmm_plan_table_reused(self._h))
 
     def ran_fused(self) -> int:
         """0: the last execute did not sum C's replicas in the GEMM; 1: it did, in one launch; 2: in two."""

@@ -173,6 +173,12 @@ struct Uploader {
     resident.assign((const char *)src, (const char *)src + bytes);
     return DMM_OK;
   }
+  // Orders `stream` behind the copy that put the resident bytes in place (for a caller that knows
+  // by other means that they are the bytes it wants).
+  int order_behind_copy(hipStream_t stream) {
+    if (slab.dev && ev_used[cur]) DMM_HIP(hipStreamWaitEvent(stream, slab.ev[cur], 0));
+    return DMM_OK;
+  }
   // The caller guarantees that no stream work still uses the slab: in particular its last copy has
   // completed, so the mirror describes the buffer.
   void release() {
@@ -241,6 +247,31 @@ ScratchPool &scratch_pool() {
   return *p;
 }
 
+// Where the replica sum's (or the broadcast's) tables sit in a device buffer.
+struct RedLaunch {
+  char *dev_base = nullptr;   // device address of the buffer the offsets below refer to
+  size_t n_items = 0;
+  size_t o_items = 0, o_tiles = 0, o_parts = 0, o_lds = 0;
+  int nparts = 0;
+  bool vec_ok = true;
+};
+
+// Where the merged macro-tiles' tables sit in the plan's device table.
+struct MergedLaunch {
+  size_t n_items = 0, o_a = 0, o_b = 0, o_c = 0, o_k = 0, o_fix = 0, n_fix = 0, total = 0;
+};
+
+// What the launches of a dmm_execute need to know besides the device table itself.
+struct ExecLayout {
+  bool merged = false;
+  MergedLaunch ml;                                                       // merged macro-tiles
+  size_t n_items = 0, o_segs = 0, o_fix = 0, o_red = 0, n_first = 0, n_fix = 0;   // per-group macro-tiles
+  bool fuse = false, one_launch = false;
+  size_t n_runs = 0;
+  bool uses_split = false;      // some macro-tiles store through the plan's scratch buffer
+  RedLaunch red;                // the replica-sum launch behind the GEMM (n_items == 0: none)
+};
+
 struct DeviceState {
   char *split_buf = nullptr;   // partial sums of K-split items
   size_t split_cap = 0;
@@ -256,6 +287,13 @@ struct DeviceState {
   bool ran_merged = false;            // the last dmm_execute ran the merged macro-tiles
   bool ran_k_split = false;           // ... and cut macro-tiles along K
   int ran_fused = 0;                  // ... and fused the replica sum into the GEMM: in 1 launch, in 2; 0 = not
+  // The inputs of the last successful dmm_execute (element type, flags, device, the six pointer
+  // and leading-dimension arrays) and the layout of the device table it left in gemm_table: a call
+  // with the same inputs launches from that table as it stands.
+  std::vector<char> exec_key, key_scratch;
+  ExecLayout exec_layout;
+  bool exec_cached = false;
+  bool table_reused = false;          // the last dmm_execute did
 };
 
 void destroy_device_state(DeviceState *d) {

@@ -121,14 +121,6 @@ int check_lds(const Grid &G, const int64_t *ld) {
 
 // The replica sum in two halves, so that dmm_execute can put the table upload in front of the
 // GEMM launch and nothing but the launch itself behind it.
-struct RedLaunch {
-  char *dev_base = nullptr;   // device address of the buffer the offsets below refer to
-  size_t n_items = 0;
-  size_t o_items = 0, o_tiles = 0, o_parts = 0, o_lds = 0;
-  int nparts = 0;
-  bool vec_ok = true;
-};
-
 // Appends the replica sum's tables to *h at byte offset `base` (a multiple of 8).
 int build_reduce(dmm_plan_t *P, void *const *c_tiles, const int64_t *c_ld, int32_t origin, std::vector<char> *hp,
                  size_t base, RedLaunch *L) {
@@ -236,10 +228,6 @@ int fire_reduce(dmm_plan_t *P, const RedLaunch &L, hipStream_t stream, bool time
 //   CompItemDev[items] | PieceDev a[...] | PieceDev b[...] | PieceDev c[...] | int32 klen[...]
 // A slices are numbered (replica, row interval, segment), B slices (replica, segment, column
 // interval), C slices (replica, row interval, column interval).
-struct MergedLaunch {
-  size_t n_items = 0, o_a = 0, o_b = 0, o_c = 0, o_k = 0, o_fix = 0, n_fix = 0, total = 0;
-};
-
 constexpr int32_t MIN_RUN = 64;   // K steps a run of a macro-tile cut along K has at least (see dmm_execute)
 
 // Scratch buffer of the plan for `n_runs` partial tiles; orders this call behind the plan's last one.
@@ -540,6 +528,339 @@ done:
   return rc;
 }
 
+namespace dmm {
+namespace {
+
+struct ExecArgs {
+  int dtype;
+  int64_t es, bk, c_es;
+  const void *const *a_tiles;
+  const int64_t *a_ld;
+  const void *const *b_tiles;
+  const int64_t *b_ld;
+  void *const *c_tiles;
+  const int64_t *c_ld;
+  uint32_t flags;
+  int device;
+};
+
+// Work tables of the merged macro-tiles:  merged tables | replica-sum tables, one copy.
+int build_merged_exec(dmm_plan_t *P, const ExecArgs &x, hipStream_t stream, ExecLayout *L) {
+  int rc;
+  RedLaunch red;
+  MergedLaunch ml;
+  std::vector<char> &h = P->dev->host;
+  h.clear();
+  int cus = 0;
+  if ((rc = device_cus(&cus))) return rc;
+  if ((rc = build_merged_tables(P, x.es, x.bk, x.c_es, x.a_tiles, x.a_ld, x.b_tiles, x.b_ld, x.c_tiles, x.c_ld, cus, stream, &h, &ml)))
+    return rc;
+  if (!(x.flags & DMM_NO_REDUCE) && (rc = build_reduce(P, x.c_tiles, x.c_ld, 0, &h, ml.total, &red))) return rc;
+  if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
+  red.dev_base = P->dev->gemm_table.dev();
+  L->merged = true;
+  L->ml = ml;
+  L->red = red;
+  L->uses_split = ml.n_fix > 0;
+  return DMM_OK;
+}
+
+// Work tables of the per-group macro-tiles.  The tables of all kernels go up in one copy in front
+// of the GEMM launch, so that nothing but the launches separates them:
+// ItemDev[] | SegDev[] | FixItem[] | RedSrc[] | replica-sum tables.
+int build_group_exec(dmm_plan_t *P, const ExecArgs &x, hipStream_t stream, ExecLayout *L) {
+  int rc;
+  const int64_t es = x.es, bk = x.bk, c_es = x.c_es;
+  const void *const *a_tiles = x.a_tiles;
+  const void *const *b_tiles = x.b_tiles;
+  void *const *c_tiles = x.c_tiles;
+  const int64_t *a_ld = x.a_ld, *b_ld = x.b_ld, *c_ld = x.c_ld;
+  const uint32_t flags = x.flags;
+  if ((rc = materialize(P))) return rc;
+    RedLaunch red;
+  const size_t n_plan_items = P->items.size();
+  const size_t n_segs = P->tasks.size();
+  std::vector<SegDev> hs(n_segs);
+  std::vector<ItemDev> hi(n_plan_items);
+  std::vector<FixItem> fixes;
+  // segments in grouped order: segment index = position in `order`
+  for (size_t pos = 0; pos < n_segs; ++pos) {
+    const dmm_task &t = P->tasks[P->order[pos]];
+    const int64_t ai = P->A.table_index(t.a_rep, t.a_ti, t.a_tj);
+    const int64_t bi = P->B.table_index(t.b_rep, t.b_ti, t.b_tj);
+    if (!a_tiles[ai] || !b_tiles[bi]) return DMM_EINVAL;
+    SegDev sg;
+    sg.lda = a_ld[ai];
+    sg.ldb = b_ld[bi];
+    sg.a = (const char *)a_tiles[ai] + ((t.m0 - P->A.rc[t.a_ti]) * sg.lda + (t.k0 - P->A.cc[t.a_tj])) * es;
+    sg.b = (const char *)b_tiles[bi] + ((t.k0 - P->B.rc[t.b_ti]) * sg.ldb + (t.n0 - P->B.cc[t.b_tj])) * es;
+    // bytes that may be read from the segment's origin to the end of the tile buffer
+    // ((rows - 1) * ld + cols elements are guaranteed to exist)
+    const int64_t a_h = P->A.rc[t.a_ti + 1] - P->A.rc[t.a_ti], a_w = P->A.cc[t.a_tj + 1] - P->A.cc[t.a_tj];
+    const int64_t b_h = P->B.rc[t.b_ti + 1] - P->B.rc[t.b_ti], b_w = P->B.cc[t.b_tj + 1] - P->B.cc[t.b_tj];
+    sg.a_bytes = ((a_h - 1) * sg.lda + a_w - ((t.m0 - P->A.rc[t.a_ti]) * sg.lda + (t.k0 - P->A.cc[t.a_tj]))) * es;
+    sg.b_bytes = ((b_h - 1) * sg.ldb + b_w - ((t.k0 - P->B.rc[t.b_ti]) * sg.ldb + (t.n0 - P->B.cc[t.b_tj]))) * es;
+    sg.klen = (int32_t)(t.k1 - t.k0);
+    sg.pad = 0;
+    hs[pos] = sg;
+  }
+  for (size_t i = 0; i < n_plan_items; ++i) {
+    const dmm_work_item &w = P->items[i];
+    const int64_t ci = P->C.table_index(w.c_rep, w.c_ti, w.c_tj);
+    if (!c_tiles[ci]) return DMM_EINVAL;
+    ItemDev d;
+    d.ldc = c_ld[ci];
+    d.c = (char *)c_tiles[ci] + ((w.m0 - P->C.rc[w.c_ti]) * d.ldc + (w.n0 - P->C.cc[w.c_tj])) * c_es;
+    if (w.group >= 0) {
+      const Group &G = P->groups[(size_t)w.group];
+      d.seg_begin = (int32_t)G.first;
+      d.nsteps = 0;
+      for (int64_t q = 0; q < G.count; ++q) d.nsteps += (int32_t)((hs[(size_t)(G.first + q)].klen + bk - 1) / bk);
+      d.m_off = (int32_t)(w.m0 - G.m0);
+      d.n_off = (int32_t)(w.n0 - G.n0);
+    } else {
+      d.seg_begin = 0;
+      d.nsteps = 0;
+      d.m_off = d.n_off = 0;
+    }
+    d.m_ext = w.m_ext;
+    d.n_ext = w.n_ext;
+    d.first_step = 0;
+    d.c_es = (int32_t)c_es;
+    d.red_first = d.red_count = 0;
+    hi[i] = d;
+  }
+  // K-split of the last round (see sum_parts_kernel): with W working items on `cus` CUs the
+  // last W % cus of them run alone; if they are few, each is cut into up to cus / (W % cus) runs
+  // of at least MIN_RUN K steps.  Run 0 takes the item's place in the launch order, the others
+  // go to the end; all of them write to the scratch buffer.  A run pays a prologue and an
+  // epilogue of its own (about 13 K steps' worth) and the pass that adds the runs up is one more
+  // launch: measured, runs of 32 steps lose (2048^3: 45 -> 66 us), so a run is 64 steps at least.
+  int cus = 0;
+  if ((rc = device_cus(&cus))) return rc;
+  size_t working = 0;
+  for (const ItemDev &d : hi) working += d.nsteps > 0;
+  const size_t tail = working % (size_t)cus;
+  size_t n_runs = 0;
+  if (tail > 0 && tail <= (size_t)cus / 2) {
+    const int32_t max_runs = (int32_t)((size_t)cus / tail);
+    size_t seen = 0;
+    for (size_t i = n_plan_items; i-- > 0 && seen < tail;) {
+      if (hi[i].nsteps <= 0) continue;
+      ++seen;
+      int32_t runs = std::min(max_runs, hi[i].nsteps / MIN_RUN);
+      if (runs < 2) continue;
+      const int32_t per = (hi[i].nsteps + runs - 1) / runs;
+      runs = (hi[i].nsteps + per - 1) / per;
+      const ItemDev whole = hi[i];
+      FixItem f;
+      f.dst = whole.c;
+      f.ldc = whole.ldc;
+      f.parts = (const float *)(uintptr_t)(n_runs * sizeof(float) * BM * BN);   // offset for now, base added below
+      f.m_ext = whole.m_ext;
+      f.n_ext = whole.n_ext;
+      f.nparts = runs;
+      f.c_es = whole.c_es;
+      f.row0 = f.col0 = 0;
+      fixes.push_back(f);
+      for (int32_t j = 0; j < runs; ++j) {
+        ItemDev r = whole;
+        r.c = (void *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);        // offset for now
+        r.ldc = BN;
+        r.first_step = j * per;
+        r.nsteps = std::min(per, whole.nsteps - j * per);
+        r.c_es = -4;                                                                        // fp32; negative marks "c is a scratch offset"
+        if (j == 0) hi[i] = r;
+        else hi.push_back(r);
+      }
+      n_runs += (size_t)runs;
+    }
+  }
+  if (n_runs > 0) {
+    if ((rc = acquire_split_buffer(P, n_runs, stream))) return rc;
+    for (ItemDev &d : hi)
+      if (d.c_es < 0) {
+        d.c = (void *)(P->dev->split_buf + (uintptr_t)d.c);
+        d.c_es = 4;
+      }
+    for (FixItem &f : fixes) f.parts = (const float *)(P->dev->split_buf + (uintptr_t)f.parts);
+  }
+  // Fused replica sum: the macro-tiles of replicas 1, 2, ... go first, those of replica 0 behind
+  // them, and these add the others' partial sums to their own before they store.  No replica-sum
+  // kernel runs.  (Not together with the K-split, whose runs store through a scratch buffer.)
+  // One launch where every macro-tile of replica 0 finds the partial sums of its region written
+  // by its own workgroup earlier in the same launch (workgroup w walks items w, w + grid, ... in
+  // order, and a wave reads back exactly the elements it stored itself); otherwise two launches,
+  // replica 0's second (stream order: every partial sum is complete by then).
+  const bool fuse = !(flags & (DMM_SEPARATE_REDUCE | DMM_NO_REDUCE)) && P->C.c > 1 && n_runs == 0;
+  std::vector<RedSrc> reds;
+  size_t n_first = hi.size();               // items of the first launch
+  bool one_launch = false;
+  if (fuse) {
+    std::vector<ItemDev> others, origin;
+    others.reserve(hi.size());
+    origin.reserve(hi.size());
+    std::vector<std::vector<uint32_t>> of_rep((size_t)P->C.c);     // per replica: plan items in list order
+    for (size_t i = 0; i < n_plan_items; ++i) {
+      const dmm_work_item &w = P->items[i];
+      of_rep[(size_t)w.c_rep].push_back((uint32_t)i);
+      if (w.c_rep != 0) {
+        others.push_back(hi[i]);
+        continue;
+      }
+      ItemDev d = hi[i];
+      d.red_first = (int32_t)reds.size();
+      d.red_count = P->C.c - 1;
+      for (int32_t r = 1; r < P->C.c; ++r) {
+        const int64_t idx = P->C.table_index(r, w.c_ti, w.c_tj);
+        if (!c_tiles[idx]) return DMM_EINVAL;
+        RedSrc src;
+        src.ld = c_ld[idx];
+        src.p = (const float *)c_tiles[idx] + (w.m0 - P->C.rc[w.c_ti]) * src.ld + (w.n0 - P->C.cc[w.c_tj]);
+        reds.push_back(src);
+      }
+      origin.push_back(d);
+    }
+    n_first = others.size();
+    // One launch?  Replica r's k-th macro-tile has to cover the region of replica 0's k-th, and sit
+    // a multiple of the grid in front of it in the combined list.
+    const size_t grid = std::min<size_t>(n_plan_items, (size_t)cus);
+    one_launch = grid > 0 && !origin.empty();
+    std::vector<uint32_t> pos(n_plan_items, 0);                    // position in `others` of a plan item
+    {
+      uint32_t at = 0;
+      for (size_t i = 0; i < n_plan_items; ++i)
+        if (P->items[i].c_rep != 0) pos[i] = at++;
+    }
+    for (int32_t r = 1; r < P->C.c && one_launch; ++r) {
+      if (of_rep[(size_t)r].size() != of_rep[0].size()) one_launch = false;
+      for (size_t k = 0; k < of_rep[0].size() && one_launch; ++k) {
+        const dmm_work_item &o = P->items[of_rep[0][k]], &s = P->items[of_rep[(size_t)r][k]];
+        if (o.c_ti != s.c_ti || o.c_tj != s.c_tj || o.m0 != s.m0 || o.n0 != s.n0 || o.m_ext != s.m_ext ||
+            o.n_ext != s.n_ext || (n_first + k - pos[of_rep[(size_t)r][k]]) % grid != 0)
+          one_launch = false;
+      }
+    }
+    hi = std::move(others);
+    hi.insert(hi.end(), origin.begin(), origin.end());
+  }
+  const size_t n_items = hi.size();
+  const size_t o_segs = n_items * sizeof(ItemDev);
+  const size_t o_fix = o_segs + n_segs * sizeof(SegDev);
+  const size_t o_red = o_fix + fixes.size() * sizeof(FixItem);
+  const size_t total = n_items > 0 ? o_red + reds.size() * sizeof(RedSrc) : 0;
+  std::vector<char> &h = P->dev->host;
+  h.clear();
+  h.resize(total);
+  if (n_items > 0) {
+    std::memcpy(h.data(), hi.data(), n_items * sizeof(ItemDev));
+    std::memcpy(h.data() + o_segs, hs.data(), n_segs * sizeof(SegDev));
+    if (!fixes.empty()) std::memcpy(h.data() + o_fix, fixes.data(), fixes.size() * sizeof(FixItem));
+    if (!reds.empty()) std::memcpy(h.data() + o_red, reds.data(), reds.size() * sizeof(RedSrc));
+  }
+  if (!(flags & DMM_NO_REDUCE) && !fuse && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, total, &red))) return rc;
+  if (!h.empty()) {
+    if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
+    red.dev_base = P->dev->gemm_table.dev();
+  }
+  L->merged = false;
+  L->n_items = n_items;
+  L->o_segs = o_segs;
+  L->o_fix = o_fix;
+  L->o_red = o_red;
+  L->n_first = n_first;
+  L->n_fix = fixes.size();
+  L->fuse = fuse;
+  L->one_launch = one_launch;
+  L->uses_split = n_runs > 0;
+  L->n_runs = n_runs;
+  L->red = red;
+  return DMM_OK;
+}
+
+// The launches of one dmm_execute, from the device table the layout describes.
+int launch_exec(dmm_plan_t *P, const ExecLayout &L, int64_t es, hipStream_t stream, bool timed) {
+  int rc;
+  char *d = P->dev->gemm_table.dev();
+  if (L.merged) {
+    const MergedLaunch &ml = L.ml;
+    TraceRange gemm("gemm");
+    if (timed) {
+      if ((rc = timing_events(P->dev->t_gemm))) return rc;
+      DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
+    }
+    launch_grouped_gemm_comp((int)es, (unsigned)ml.n_items, stream, (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a),
+                             (const PieceDev *)(d + ml.o_b), (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
+    DMM_HIP(hipGetLastError());
+    if (ml.n_fix > 0) {
+      hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(ml.n_fix * (BM / FIX_ROWS))), dim3(256), 0, stream,
+                         (const FixItem *)(d + ml.o_fix));
+      DMM_HIP(hipGetLastError());
+    }
+    if (timed) {
+      DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
+      P->dev->gemm_timed = true;
+    }
+    gemm.end();
+    P->dev->ran_merged = true;
+    P->dev->ran_k_split = ml.n_fix > 0;
+    P->dev->ran_fused = 0;
+  } else {
+    P->dev->ran_merged = false;
+    if (L.n_items > 0) {
+      int cus = 0;
+      if ((rc = device_cus(&cus))) return rc;
+      const size_t n_items = L.n_items, n_first = L.n_first;
+      const bool fuse = L.fuse, one_launch = L.one_launch;
+      TraceRange gemm("gemm");
+      const ItemDev *di = (const ItemDev *)d;
+      const SegDev *ds = (const SegDev *)(d + L.o_segs);
+      if (timed) {
+        if ((rc = timing_events(P->dev->t_gemm))) return rc;
+        DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
+      }
+      const RedSrc *dr = (const RedSrc *)(d + L.o_red);
+      // {first item, count} per launch
+      const size_t part[2][2] = {{0, one_launch ? n_items : n_first}, {n_first, one_launch ? 0 : n_items - n_first}};
+      for (int l = 0; l < 2; ++l) {
+        if (part[l][1] == 0) continue;
+        const bool sums = fuse && (l == 1 || one_launch);   // the launch whose macro-tiles add the other replicas' partial sums
+        // one workgroup per CU at most: workgroup w walks items w, w + grid, w + 2 grid, ... of its launch
+        const int count = (int)part[l][1];
+        launch_grouped_gemm((int)es, sums, (unsigned)std::min(count, cus), stream, di + part[l][0], ds, dr, count);
+        DMM_HIP(hipGetLastError());
+        if (timed && fuse && !one_launch && l == 0 && part[1][1] > 0) {
+          if (!P->dev->t_mid) DMM_HIP(hipEventCreate(&P->dev->t_mid));
+          DMM_HIP(hipEventRecord(P->dev->t_mid, stream));
+          P->dev->mid_timed = true;
+          P->dev->launch_flops[0] = P->dev->launch_flops[1] = 0.0;
+          for (const dmm_task &t : P->tasks)
+            P->dev->launch_flops[t.c_rep == 0 ? 1 : 0] += 2.0 * (double)(t.m1 - t.m0) * (double)(t.n1 - t.n0) * (double)(t.k1 - t.k0);
+        }
+      }
+      if (L.n_fix > 0) {
+        hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(L.n_fix * (BM / FIX_ROWS))), dim3(256), 0, stream,
+                           (const FixItem *)(d + L.o_fix));
+        DMM_HIP(hipGetLastError());
+      }
+      if (timed) {
+        DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
+        P->dev->gemm_timed = true;
+      }
+    }
+    P->dev->ran_k_split = L.n_runs > 0;
+    P->dev->ran_fused = !L.fuse ? 0 : L.one_launch ? 1 : 2;
+  }
+  {
+    TraceRange tr("replica_sum");
+    if ((rc = fire_reduce(P, L.red, stream, timed))) return rc;
+  }
+  return mark_use(P, stream);
+}
+
+}  // namespace
+}  // namespace dmm
+
 int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int64_t *a_ld,
                 const void *const *b_tiles, const int64_t *b_ld, void *const *c_tiles, const int64_t *c_ld,
                 uint32_t flags, void *hip_stream) {
@@ -571,291 +892,48 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
     P->dev->gemm_timed = P->dev->red_timed = P->dev->mid_timed = false;
     int device = 0;
     DMM_HIP(hipGetDevice(&device));
-    if (P->merged.valid && !(flags & DMM_NO_MERGE) && g_comp_ok[device]) {
+    // The call's inputs, side by side: when they are those of the plan's last dmm_execute, the
+    // device table of that call is still in place and describes this one too (DMM_TIMING changes
+    // nothing in it), so the assembly of the tables and their upload are skipped.
+    std::vector<char> &key = P->dev->key_scratch;
+    key.clear();
+    auto put = [&key](const void *p, size_t bytes) { key.insert(key.end(), (const char *)p, (const char *)p + bytes); };
+    const int64_t head[3] = {dtype, (int64_t)(flags & ~DMM_TIMING), device};
+    put(head, sizeof head);
+    const size_t na = (size_t)(P->A.c * P->A.tiles_per_rep()), nb = (size_t)(P->B.c * P->B.tiles_per_rep()),
+                 nc = (size_t)(P->C.c * P->C.tiles_per_rep());
+    put(a_tiles, na * sizeof(void *));
+    put(a_ld, na * sizeof(int64_t));
+    put(b_tiles, nb * sizeof(void *));
+    put(b_ld, nb * sizeof(int64_t));
+    put(c_tiles, nc * sizeof(void *));
+    put(c_ld, nc * sizeof(int64_t));
+    ExecLayout L;
+    if (P->dev->exec_cached && key == P->dev->exec_key) {
+      L = P->dev->exec_layout;
+      P->dev->table_reused = true;
+      if ((rc = P->dev->gemm_table.order_behind_copy(stream))) return rc;
+      // (the scratch buffer of macro-tiles cut along K is shared by all calls on this plan)
+      if (L.uses_split && P->dev->last_use_recorded) DMM_HIP(hipStreamWaitEvent(stream, P->dev->last_use, 0));
+    } else {
+      P->dev->exec_cached = false;
+      P->dev->table_reused = false;
       TraceRange tables("tables");
-      // merged macro-tiles:  merged tables | replica-sum tables, one copy, then the launches
-      RedLaunch red;
-      MergedLaunch ml;
-      std::vector<char> &h = P->dev->host;
-      h.clear();
-      int cus = 0;
-      if ((rc = device_cus(&cus))) return rc;
-      if ((rc = build_merged_tables(P, es, bk, c_es, a_tiles, a_ld, b_tiles, b_ld, c_tiles, c_ld, cus, stream, &h, &ml)))
-        return rc;
-      if (!(flags & DMM_NO_REDUCE) && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, ml.total, &red))) return rc;
-      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
-      char *d = P->dev->gemm_table.dev();
-      red.dev_base = d;
-      tables.end();
-      TraceRange gemm("gemm");
-      if (timed) {
-        if ((rc = timing_events(P->dev->t_gemm))) return rc;
-        DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
-      }
-      launch_grouped_gemm_comp((int)es, (unsigned)ml.n_items, stream, (const CompItemDev *)d, (const PieceDev *)(d + ml.o_a),
-                               (const PieceDev *)(d + ml.o_b), (const PieceDev *)(d + ml.o_c), (const int32_t *)(d + ml.o_k));
-      DMM_HIP(hipGetLastError());
-      if (ml.n_fix > 0) {
-        hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(ml.n_fix * (BM / FIX_ROWS))), dim3(256), 0, stream,
-                           (const FixItem *)(d + ml.o_fix));
-        DMM_HIP(hipGetLastError());
-      }
-      if (timed) {
-        DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
-        P->dev->gemm_timed = true;
-      }
-      gemm.end();
-      P->dev->ran_merged = true;
-      P->dev->ran_k_split = ml.n_fix > 0;
-      P->dev->ran_fused = 0;
-      {
-        TraceRange tr("replica_sum");
-        if ((rc = fire_reduce(P, red, stream, timed))) return rc;
-      }
-      return mark_use(P, stream);
+      const ExecArgs x = {dtype, es, bk, c_es, a_tiles, a_ld, b_tiles, b_ld, c_tiles, c_ld, flags, device};
+      if (P->merged.valid && !(flags & DMM_NO_MERGE) && g_comp_ok[device]) rc = build_merged_exec(P, x, stream, &L);
+      else rc = build_group_exec(P, x, stream, &L);
+      if (rc) return rc;
+      P->dev->exec_key = key;
+      P->dev->exec_layout = L;
+      P->dev->exec_cached = true;
     }
-    P->dev->ran_merged = false;
-    P->dev->ran_k_split = false;
-    P->dev->ran_fused = 0;
-    TraceRange tables("tables");
-    if ((rc = materialize(P))) return rc;
-    // The tables of all kernels go up in one copy in front of the GEMM launch, so that nothing
-    // but the launches separates them:  ItemDev[] | SegDev[] | FixItem[] | RedSrc[] | replica-sum tables.
-    RedLaunch red;
-    const size_t n_plan_items = P->items.size();
-    const size_t n_segs = P->tasks.size();
-    std::vector<SegDev> hs(n_segs);
-    std::vector<ItemDev> hi(n_plan_items);
-    std::vector<FixItem> fixes;
-    // segments in grouped order: segment index = position in `order`
-    for (size_t pos = 0; pos < n_segs; ++pos) {
-      const dmm_task &t = P->tasks[P->order[pos]];
-      const int64_t ai = P->A.table_index(t.a_rep, t.a_ti, t.a_tj);
-      const int64_t bi = P->B.table_index(t.b_rep, t.b_ti, t.b_tj);
-      if (!a_tiles[ai] || !b_tiles[bi]) return DMM_EINVAL;
-      SegDev sg;
-      sg.lda = a_ld[ai];
-      sg.ldb = b_ld[bi];
-      sg.a = (const char *)a_tiles[ai] + ((t.m0 - P->A.rc[t.a_ti]) * sg.lda + (t.k0 - P->A.cc[t.a_tj])) * es;
-      sg.b = (const char *)b_tiles[bi] + ((t.k0 - P->B.rc[t.b_ti]) * sg.ldb + (t.n0 - P->B.cc[t.b_tj])) * es;
-      // bytes that may be read from the segment's origin to the end of the tile buffer
-      // ((rows - 1) * ld + cols elements are guaranteed to exist)
-      const int64_t a_h = P->A.rc[t.a_ti + 1] - P->A.rc[t.a_ti], a_w = P->A.cc[t.a_tj + 1] - P->A.cc[t.a_tj];
-      const int64_t b_h = P->B.rc[t.b_ti + 1] - P->B.rc[t.b_ti], b_w = P->B.cc[t.b_tj + 1] - P->B.cc[t.b_tj];
-      sg.a_bytes = ((a_h - 1) * sg.lda + a_w - ((t.m0 - P->A.rc[t.a_ti]) * sg.lda + (t.k0 - P->A.cc[t.a_tj]))) * es;
-      sg.b_bytes = ((b_h - 1) * sg.ldb + b_w - ((t.k0 - P->B.rc[t.b_ti]) * sg.ldb + (t.n0 - P->B.cc[t.b_tj]))) * es;
-      sg.klen = (int32_t)(t.k1 - t.k0);
-      sg.pad = 0;
-      hs[pos] = sg;
-    }
-    for (size_t i = 0; i < n_plan_items; ++i) {
-      const dmm_work_item &w = P->items[i];
-      const int64_t ci = P->C.table_index(w.c_rep, w.c_ti, w.c_tj);
-      if (!c_tiles[ci]) return DMM_EINVAL;
-      ItemDev d;
-      d.ldc = c_ld[ci];
-      d.c = (char *)c_tiles[ci] + ((w.m0 - P->C.rc[w.c_ti]) * d.ldc + (w.n0 - P->C.cc[w.c_tj])) * c_es;
-      if (w.group >= 0) {
-        const Group &G = P->groups[(size_t)w.group];
-        d.seg_begin = (int32_t)G.first;
-        d.nsteps = 0;
-        for (int64_t q = 0; q < G.count; ++q) d.nsteps += (int32_t)((hs[(size_t)(G.first + q)].klen + bk - 1) / bk);
-        d.m_off = (int32_t)(w.m0 - G.m0);
-        d.n_off = (int32_t)(w.n0 - G.n0);
-      } else {
-        d.seg_begin = 0;
-        d.nsteps = 0;
-        d.m_off = d.n_off = 0;
-      }
-      d.m_ext = w.m_ext;
-      d.n_ext = w.n_ext;
-      d.first_step = 0;
-      d.c_es = (int32_t)c_es;
-      d.red_first = d.red_count = 0;
-      hi[i] = d;
-    }
-    // K-split of the last round (see sum_parts_kernel): with W working items on `cus` CUs the
-    // last W % cus of them run alone; if they are few, each is cut into up to cus / (W % cus) runs
-    // of at least MIN_RUN K steps.  Run 0 takes the item's place in the launch order, the others
-    // go to the end; all of them write to the scratch buffer.  A run pays a prologue and an
-    // epilogue of its own (about 13 K steps' worth) and the pass that adds the runs up is one more
-    // launch: measured, runs of 32 steps lose (2048^3: 45 -> 66 us), so a run is 64 steps at least.
-    int cus = 0;
-    if ((rc = device_cus(&cus))) return rc;
-    size_t working = 0;
-    for (const ItemDev &d : hi) working += d.nsteps > 0;
-    const size_t tail = working % (size_t)cus;
-    size_t n_runs = 0;
-    if (tail > 0 && tail <= (size_t)cus / 2) {
-      const int32_t max_runs = (int32_t)((size_t)cus / tail);
-      size_t seen = 0;
-      for (size_t i = n_plan_items; i-- > 0 && seen < tail;) {
-        if (hi[i].nsteps <= 0) continue;
-        ++seen;
-        int32_t runs = std::min(max_runs, hi[i].nsteps / MIN_RUN);
-        if (runs < 2) continue;
-        const int32_t per = (hi[i].nsteps + runs - 1) / runs;
-        runs = (hi[i].nsteps + per - 1) / per;
-        const ItemDev whole = hi[i];
-        FixItem f;
-        f.dst = whole.c;
-        f.ldc = whole.ldc;
-        f.parts = (const float *)(uintptr_t)(n_runs * sizeof(float) * BM * BN);   // offset for now, base added below
-        f.m_ext = whole.m_ext;
-        f.n_ext = whole.n_ext;
-        f.nparts = runs;
-        f.c_es = whole.c_es;
-        f.row0 = f.col0 = 0;
-        fixes.push_back(f);
-        for (int32_t j = 0; j < runs; ++j) {
-          ItemDev r = whole;
-          r.c = (void *)(uintptr_t)((n_runs + (size_t)j) * sizeof(float) * BM * BN);        // offset for now
-          r.ldc = BN;
-          r.first_step = j * per;
-          r.nsteps = std::min(per, whole.nsteps - j * per);
-          r.c_es = -4;                                                                        // fp32; negative marks "c is a scratch offset"
-          if (j == 0) hi[i] = r;
-          else hi.push_back(r);
-        }
-        n_runs += (size_t)runs;
-      }
-    }
-    if (n_runs > 0) {
-      if ((rc = acquire_split_buffer(P, n_runs, stream))) return rc;
-      for (ItemDev &d : hi)
-        if (d.c_es < 0) {
-          d.c = (void *)(P->dev->split_buf + (uintptr_t)d.c);
-          d.c_es = 4;
-        }
-      for (FixItem &f : fixes) f.parts = (const float *)(P->dev->split_buf + (uintptr_t)f.parts);
-    }
-    // Fused replica sum: the macro-tiles of replicas 1, 2, ... go first, those of replica 0 behind
-    // them, and these add the others' partial sums to their own before they store.  No replica-sum
-    // kernel runs.  (Not together with the K-split, whose runs store through a scratch buffer.)
-    // One launch where every macro-tile of replica 0 finds the partial sums of its region written
-    // by its own workgroup earlier in the same launch (workgroup w walks items w, w + grid, ... in
-    // order, and a wave reads back exactly the elements it stored itself); otherwise two launches,
-    // replica 0's second (stream order: every partial sum is complete by then).
-    const bool fuse = !(flags & (DMM_SEPARATE_REDUCE | DMM_NO_REDUCE)) && P->C.c > 1 && n_runs == 0;
-    std::vector<RedSrc> reds;
-    size_t n_first = hi.size();               // items of the first launch
-    bool one_launch = false;
-    if (fuse) {
-      std::vector<ItemDev> others, origin;
-      others.reserve(hi.size());
-      origin.reserve(hi.size());
-      std::vector<std::vector<uint32_t>> of_rep((size_t)P->C.c);     // per replica: plan items in list order
-      for (size_t i = 0; i < n_plan_items; ++i) {
-        const dmm_work_item &w = P->items[i];
-        of_rep[(size_t)w.c_rep].push_back((uint32_t)i);
-        if (w.c_rep != 0) {
-          others.push_back(hi[i]);
-          continue;
-        }
-        ItemDev d = hi[i];
-        d.red_first = (int32_t)reds.size();
-        d.red_count = P->C.c - 1;
-        for (int32_t r = 1; r < P->C.c; ++r) {
-          const int64_t idx = P->C.table_index(r, w.c_ti, w.c_tj);
-          if (!c_tiles[idx]) return DMM_EINVAL;
-          RedSrc src;
-          src.ld = c_ld[idx];
-          src.p = (const float *)c_tiles[idx] + (w.m0 - P->C.rc[w.c_ti]) * src.ld + (w.n0 - P->C.cc[w.c_tj]);
-          reds.push_back(src);
-        }
-        origin.push_back(d);
-      }
-      n_first = others.size();
-      // One launch?  Replica r's k-th macro-tile has to cover the region of replica 0's k-th, and sit
-      // a multiple of the grid in front of it in the combined list.
-      const size_t grid = std::min<size_t>(n_plan_items, (size_t)cus);
-      one_launch = grid > 0 && !origin.empty();
-      std::vector<uint32_t> pos(n_plan_items, 0);                    // position in `others` of a plan item
-      {
-        uint32_t at = 0;
-        for (size_t i = 0; i < n_plan_items; ++i)
-          if (P->items[i].c_rep != 0) pos[i] = at++;
-      }
-      for (int32_t r = 1; r < P->C.c && one_launch; ++r) {
-        if (of_rep[(size_t)r].size() != of_rep[0].size()) one_launch = false;
-        for (size_t k = 0; k < of_rep[0].size() && one_launch; ++k) {
-          const dmm_work_item &o = P->items[of_rep[0][k]], &s = P->items[of_rep[(size_t)r][k]];
-          if (o.c_ti != s.c_ti || o.c_tj != s.c_tj || o.m0 != s.m0 || o.n0 != s.n0 || o.m_ext != s.m_ext ||
-              o.n_ext != s.n_ext || (n_first + k - pos[of_rep[(size_t)r][k]]) % grid != 0)
-            one_launch = false;
-        }
-      }
-      hi = std::move(others);
-      hi.insert(hi.end(), origin.begin(), origin.end());
-    }
-    const size_t n_items = hi.size();
-    const size_t o_segs = n_items * sizeof(ItemDev);
-    const size_t o_fix = o_segs + n_segs * sizeof(SegDev);
-    const size_t o_red = o_fix + fixes.size() * sizeof(FixItem);
-    const size_t total = n_items > 0 ? o_red + reds.size() * sizeof(RedSrc) : 0;
-    std::vector<char> &h = P->dev->host;
-    h.clear();
-    h.resize(total);
-    if (n_items > 0) {
-      std::memcpy(h.data(), hi.data(), n_items * sizeof(ItemDev));
-      std::memcpy(h.data() + o_segs, hs.data(), n_segs * sizeof(SegDev));
-      if (!fixes.empty()) std::memcpy(h.data() + o_fix, fixes.data(), fixes.size() * sizeof(FixItem));
-      if (!reds.empty()) std::memcpy(h.data() + o_red, reds.data(), reds.size() * sizeof(RedSrc));
-    }
-    if (!(flags & DMM_NO_REDUCE) && !fuse && (rc = build_reduce(P, c_tiles, c_ld, 0, &h, total, &red))) return rc;
-    if (!h.empty()) {
-      if ((rc = P->dev->gemm_table.upload(h.data(), h.size(), stream, busy_event(P)))) return rc;
-      red.dev_base = P->dev->gemm_table.dev();
-    }
-    tables.end();
-    if (n_items > 0) {
-      TraceRange gemm("gemm");
-      const ItemDev *di = (const ItemDev *)P->dev->gemm_table.dev();
-      const SegDev *ds = (const SegDev *)(P->dev->gemm_table.dev() + o_segs);
-      if (timed) {
-        if ((rc = timing_events(P->dev->t_gemm))) return rc;
-        DMM_HIP(hipEventRecord(P->dev->t_gemm[0], stream));
-      }
-      const RedSrc *dr = (const RedSrc *)(P->dev->gemm_table.dev() + o_red);
-      // {first item, count} per launch
-      const size_t part[2][2] = {{0, one_launch ? n_items : n_first}, {n_first, one_launch ? 0 : n_items - n_first}};
-      for (int l = 0; l < 2; ++l) {
-        if (part[l][1] == 0) continue;
-        const bool sums = fuse && (l == 1 || one_launch);   // the launch whose macro-tiles add the other replicas' partial sums
-        // one workgroup per CU at most: workgroup w walks items w, w + grid, w + 2 grid, ... of its launch
-        const int count = (int)part[l][1];
-        launch_grouped_gemm((int)es, sums, (unsigned)std::min(count, cus), stream, di + part[l][0], ds, dr, count);
-        DMM_HIP(hipGetLastError());
-        if (timed && fuse && !one_launch && l == 0 && part[1][1] > 0) {
-          if (!P->dev->t_mid) DMM_HIP(hipEventCreate(&P->dev->t_mid));
-          DMM_HIP(hipEventRecord(P->dev->t_mid, stream));
-          P->dev->mid_timed = true;
-          P->dev->launch_flops[0] = P->dev->launch_flops[1] = 0.0;
-          for (const dmm_task &t : P->tasks)
-            P->dev->launch_flops[t.c_rep == 0 ? 1 : 0] += 2.0 * (double)(t.m1 - t.m0) * (double)(t.n1 - t.n0) * (double)(t.k1 - t.k0);
-        }
-      }
-      if (!fixes.empty()) {
-        hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(fixes.size() * (BM / FIX_ROWS))), dim3(256), 0, stream,
-                           (const FixItem *)(P->dev->gemm_table.dev() + o_fix));
-        DMM_HIP(hipGetLastError());
-      }
-      if (timed) {
-        DMM_HIP(hipEventRecord(P->dev->t_gemm[1], stream));
-        P->dev->gemm_timed = true;
-      }
-    }
-    P->dev->ran_k_split = n_runs > 0;
-    P->dev->ran_fused = !fuse ? 0 : one_launch ? 1 : 2;
-    {
-      TraceRange tr("replica_sum");
-      if ((rc = fire_reduce(P, red, stream, timed))) return rc;
-    }
-    return mark_use(P, stream);
+    return launch_exec(P, L, es, stream, timed);
   } catch (const std::bad_alloc &) {
     return DMM_ENOMEM;
   }
 }
+
+int dmm_plan_table_reused(const dmm_plan_t *P) { return P && P->dev && P->dev->table_reused ? 1 : 0; }
 
 int dmm_plan_gemm_launch_ms(dmm_plan_t *P, float ms[2], double flops[2]) {
   using namespace dmm;

@@ -255,6 +255,57 @@ def test_work_table_grows_between_two_streams():
     prob.close()
 
 
+@pytest.mark.parametrize("name,dims,path", [("cfg4", (515, 771, 1030), "groups"), ("cfg4", (300, 16384, 300), "k-split"),
+                                            ("bc128", (700, 333, 517), "merged")])
+def test_repeated_execute_reuses_the_work_tables(name, dims, path):
+    """A call with the inputs of the call before it (same tables of pointers and leading dimensions,
+    same flags apart from DMM_TIMING) launches from the device tables that call left; any other call
+    assembles its own.  Per-group macro-tiles, macro-tiles cut along K (their partial tiles share
+    one scratch buffer across calls) and merged macro-tiles; results bitwise the same either way."""
+    from paper_2510_08874_amd import binding
+    from paper_2510_08874_amd.tiles import TileSet
+    cfg = workloads.scaled_config(name, *dims)
+    A, B = workloads.make_operands(cfg)
+    prob = _device_problem(cfg, A, B, c_fill=float("nan"))
+    stream = torch.cuda.current_stream().cuda_stream
+    c = cfg["C"]["replication"]
+    base = 0 if path == "merged" else binding.DMM_NO_MERGE
+    prob.execute(flags=base)
+    assert not prob.plan.table_reused()
+    assert prob.plan.ran_merged() == (path == "merged")
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        assert prob.plan.ran_k_split() == (path == "k-split")
+    first = [prob.c_global(r) for r in range(c)]
+    _check(first[0], omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+    for t in prob.C.tensors:
+        if t is not None:
+            t.fill_(float("nan"))
+    prob.execute(flags=base | binding.DMM_TIMING)                # same inputs: the tables stay
+    assert prob.plan.table_reused() and prob.plan.elapsed_ms()[0] > 0.0
+    for r in range(c):
+        assert np.array_equal(first[r], prob.c_global(r)), f"replica {r} differs on the reused tables"
+    other = TileSet(cfg["C"], torch.float32, "cuda", 1, fill=float("nan"))
+    args2 = prob.plan.marshal(prob.A.tensors, prob.A.ld, prob.B.tensors, prob.B.ld, other.tensors, other.ld)
+    prob.plan.execute_marshalled(prob.dtype_code, args2, base, stream)   # other C tiles: new tables
+    assert not prob.plan.table_reused()
+    prob.plan.execute_marshalled(prob.dtype_code, args2, base, stream)
+    assert prob.plan.table_reused()
+    for r in range(c):
+        assert np.array_equal(first[r], other.gather(r)), f"replica {r} differs in the second set of C tiles"
+    prob.execute(flags=base)                                     # back to the first set: not the last call's inputs
+    assert not prob.plan.table_reused()
+    if c > 1:
+        prob.execute(flags=base | binding.DMM_NO_REDUCE)         # other flags: new tables
+        assert not prob.plan.table_reused()
+        prob.execute(flags=base | binding.DMM_NO_REDUCE)
+        assert prob.plan.table_reused()
+        total = prob.c_global(0)
+        for r in range(1, c):
+            total = total + prob.c_global(r)                     # fp32 (p0 + p1) + ..., as the replica sum computes it
+        assert np.array_equal(total, first[0])
+    prob.close()
+
+
 def test_iteration_offset_leaves_the_result_bitwise_unchanged():
     cfg = workloads.scaled_config("cfg5", 700, 900, 650)
     A, B = workloads.make_operands(cfg)

@@ -178,6 +178,7 @@ def test_null_arguments_rejected():
     assert L.dmm_reduce_replicas_static(None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_plan_ran_k_split(None) == 0
     assert L.dmm_plan_ran_fused(None) == 0
+    assert L.dmm_plan_table_reused(None) == 0
     assert L.dmm_plan_gemm_launch_ms(None, None, None) == binding.DMM_EINVAL
     ok = dict(rows=8, cols=8, row_cuts=(0, 8), col_cuts=(0, 8), proc_rows=1, proc_cols=1, replication=1)
     fresh = binding.Plan(ok, ok, ok, 1)
