@@ -386,6 +386,11 @@ __device__ __forceinline__ float acc_read() {
   asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(REG));
   return v;
 }
+// partial sum number REG := v
+template <int REG>
+__device__ __forceinline__ void acc_write(float v) {
+  asm volatile("v_accvgpr_write_b32 a[%0], %1" : : "n"(REG), "v"(v) : DMM_ACC_REGS);
+}
 
 template <bool FUSE>
 __device__ __forceinline__ void store_macro_tile(const ItemDev &it, const RedSrc *__restrict__ red, int wm, int wn, int lane);
@@ -1163,60 +1168,52 @@ __device__ __forceinline__ void store_macro_tile(const ItemDev &it, const RedSrc
       o += (r & 3) == 3 ? pitch5 : pitch;
     });
   };
-  // Fused replica sum (fp32 C only): the macro-tile of the origin replica, launched after the other
-  // replicas' macro-tiles have finished, adds their partial sums to its own, ((own + p_1) + p_2) ...,
-  // the order and precision of the replica-sum kernel, and stores the total.  Eight rows of a 32 x 32
-  // tile at a time: 32 sums and 32 loaded values per lane, all loads of a batch in flight before the
-  // first add (the registers of the next item's first loads are live here as well).
-  auto store_sum = [&](auto full_tag) {
+  // Fused replica sum (fp32 C only): the macro-tile of the origin replica adds the other replicas'
+  // partial sums of its region to its own, ((own + p_1) + p_2) ..., the order and precision of the
+  // replica-sum kernel, and then stores like any other macro-tile.  The sums go back into the
+  // accumulator file, so that this phase has nothing but loads in flight: with loads and stores
+  // mixed, the one counter that tracks both says nothing about which of them has returned, and
+  // every batch of loads would have to wait for the whole queue to drain.  Eight rows of a 32 x 32
+  // tile per batch (32 values per lane), DEPTH batches in flight.
+  auto add_partials = [&](auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr int RB = 8;                                  // accumulator registers (rows) per batch
-    static_for<FM * (16 / RB)>([&](auto xc) {
-      constexpr int i = decltype(xc)::value / (16 / RB), rb = (decltype(xc)::value % (16 / RB)) * RB;
-      float sum[RB][FN];
-      static_for<RB * FN>([&](auto yc) {
-        constexpr int r = decltype(yc)::value / FN, j = decltype(yc)::value % FN;
-        sum[r][j] = acc_read<16 * (i * FN + j) + rb + r>();
-      });
-      for (int q = 0; q < it.red_count; ++q) {
-        const RedSrc src = red[it.red_first + q];
-        const __attribute__((address_space(1))) char *pbytes = (const __attribute__((address_space(1))) char *)src.p;
-        const unsigned ppitch = (unsigned)src.ld * 4u;
-        const unsigned poff = (unsigned)row0 * ppitch + (unsigned)col0 * 4u;
-        float v[RB][FN];
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-          const int dr = i * 32 + 8 * ((rb + r) >> 2) + ((rb + r) & 3);
-          const unsigned o = poff + (unsigned)dr * ppitch;
-#pragma unroll
-          for (int j = 0; j < FN; ++j) {
-            v[r][j] = 0.f;
-            if (FULL || (row0 + dr < it.m_ext && col0 + j * 32 < it.n_ext))
-              v[r][j] = __builtin_nontemporal_load((const __attribute__((address_space(1))) float *)(pbytes + o + j * 128));
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < RB; ++r)
-#pragma unroll
-          for (int j = 0; j < FN; ++j) sum[r][j] = sum[r][j] + v[r][j];
-      }
-#pragma unroll
-      for (int r = 0; r < RB; ++r) {
-        const int dr = i * 32 + 8 * ((rb + r) >> 2) + ((rb + r) & 3);
-        const unsigned o = voff + (unsigned)dr * pitch;
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
+    constexpr int NB = FM * (16 / RB);                     // batches per macro-tile
+    constexpr int DEPTH = 3;
+    for (int q = 0; q < it.red_count; ++q) {
+      const RedSrc src = red[it.red_first + q];
+      const __attribute__((address_space(1))) char *pbytes = (const __attribute__((address_space(1))) char *)src.p;
+      const unsigned ppitch = (unsigned)src.ld * 4u;
+      const unsigned poff = (unsigned)row0 * ppitch + (unsigned)col0 * 4u;
+      float v[DEPTH][RB][FN];
+      auto issue = [&](auto bc) {
+        constexpr int b = decltype(bc)::value, i = b / (16 / RB), rb = (b % (16 / RB)) * RB, slot = b % DEPTH;
+        static_for<RB * FN>([&](auto yc) {
+          constexpr int r = decltype(yc)::value / FN, j = decltype(yc)::value % FN;
+          constexpr int dr = i * 32 + 8 * ((rb + r) >> 2) + ((rb + r) & 3);
+          v[slot][r][j] = 0.f;
           if (FULL || (row0 + dr < it.m_ext && col0 + j * 32 < it.n_ext))
-            __builtin_nontemporal_store(sum[r][j], (gfloat_ptr)(cbytes + o + j * 128));
-      }
-    });
+            v[slot][r][j] = __builtin_nontemporal_load(
+                (const __attribute__((address_space(1))) float *)(pbytes + (poff + (unsigned)dr * ppitch) + j * 128));
+        });
+      };
+      static_for<DEPTH - 1>([&](auto bc) { issue(bc); });
+      static_for<NB>([&](auto bc) {
+        constexpr int b = decltype(bc)::value, i = b / (16 / RB), rb = (b % (16 / RB)) * RB, slot = b % DEPTH;
+        if constexpr (b + DEPTH - 1 < NB) issue(std::integral_constant<int, b + DEPTH - 1>{});
+        static_for<RB * FN>([&](auto yc) {
+          constexpr int r = decltype(yc)::value / FN, j = decltype(yc)::value % FN;
+          constexpr int REG = 16 * (i * FN + j) + rb + r;
+          acc_write<REG>(acc_read<REG>() + v[slot][r][j]);
+        });
+      });
+    }
   };
   const bool full = it.m_ext == BM && it.n_ext == BN;
   if constexpr (FUSE) {
     if (it.red_count > 0) {
-      if (full) store_sum(std::true_type{});
-      else store_sum(std::false_type{});
-      return;
+      if (full) add_partials(std::true_type{});
+      else add_partials(std::false_type{});
     }
   }
   if (wide) {

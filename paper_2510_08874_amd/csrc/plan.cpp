@@ -553,8 +553,6 @@ void build_merged(dmm_plan_t *P, uint32_t flags) {
   // replicated (only the rank that performs a box differs), so the same work list serves; their
   // replicas split M or N instead of K, which this list does not describe.
   if ((flags & (DMM_STATIONARY_B | DMM_STATIONARY_A)) && (A.c != 1 || B.c != 1 || C.c != 1)) return;
-  // every rank of a C replica has to read the same replica of A and of B
-  if (C.c % A.c != 0 || C.c % B.c != 0) return;
   const int64_t M = A.rows, K = A.cols, N = B.cols, lim = (int64_t)1 << 31;
   if (M <= 0 || K <= 0 || N <= 0 || M >= lim || K >= lim || N >= lim) return;
   G.mc = merged_cuts({&A.rc, &C.rc});
@@ -569,8 +567,14 @@ void build_merged(dmm_plan_t *P, uint32_t flags) {
     for (int64_t c : kall)
       if (c > lo && c < hi) R.kc.push_back(c);
     R.kc.push_back(hi);
-    R.a_rep = rep / (C.c / A.c);
-    R.b_rep = rep / (C.c / B.c);
+    // One replica of A and one of B serve all macro-tiles of a C replica.  Where the replication
+    // factor of A (B) divides that of C this is the replica every rank of the C replica reads by
+    // the replication rule (Section 4.1).  Otherwise the ranks of one C replica read several
+    // replicas of A (B), tile by tile, which a macro-tile across tiles cannot follow; replicas of
+    // an input are copies of each other (Section 3), so reading the first of them gives the same
+    // product, bit for bit.  (The op list, written out by materialize, keeps the rule's replica.)
+    R.a_rep = (int32_t)((int64_t)rep * A.c / C.c);
+    R.b_rep = (int32_t)((int64_t)rep * B.c / C.c);
     const int64_t S = (int64_t)R.kc.size() - 1;
     cap = std::min(cap, (kDescBytes - 4 * ((S + 3) & ~(int64_t)3)) / (48 * S));
     longest = std::max(longest, S);

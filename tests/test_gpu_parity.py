@@ -685,6 +685,9 @@ def _bc(dims, nb, dtype, reps=(1, 1, 1), p=8):
     ((640, 900, 512), 64, "bf16", 1, (2, 2, 2), 16),       # replicated: every replica its share of k, then the replica sum
     ((640, 900, 512), 64, "f32", 4, (1, 2, 4), 32),        # C replicas read different replicas of B, all the one A
     ((515, 130, 260), 100, "bf16", 1, (1, 1, 1), 8),       # cuts at 100, 200: column pieces not at multiples of 8: tiles end there
+    ((640, 900, 512), 64, "bf16", 1, (2, 1, 1), 16),       # A replicated, C not: the ranks of C read both replicas of A, tile by tile
+    ((520, 600, 530), 40, "f32", 1, (1, 4, 2), 32),        # four replicas of B for two of C
+    ((640, 900, 512), 64, "bf16", 1, (3, 1, 2), 24),       # three replicas of A for two of C: neither number divides the other
 ])
 def test_merged_macro_tiles(dims, nb, dtype, ldm, reps, p):
     """Where the tiles are small against the macro-tile the library runs macro-tiles that span
@@ -728,8 +731,7 @@ def test_merged_macro_tiles(dims, nb, dtype, ldm, reps, p):
 def test_merged_macro_tiles_random_partitionings(seed, dtype):
     """The merged kernel forced (DMM_MERGE_ALWAYS) onto random grids: uneven and empty tiles, odd
     leading dimensions, K tails in every segment, column cuts at any position, replication.  Plans
-    that cannot have a merged list (C replicas reading several replicas of A or B, empty shares)
-    run the per-group path; either way parity, and bitwise the per-group result."""
+    that cannot have a merged list (empty shares of K) run the per-group path; either way parity, and bitwise the per-group result."""
     from paper_2510_08874_amd import binding
     prob = helpers.random_problem(seed + 300, max_dim=700, allow_empty=(seed % 2 == 1))
     cfg = dict(prob, name=f"random-merged{seed}", dtype=dtype, dist=("normal", 1.0), seeds=(seed, seed + 900),

@@ -306,7 +306,7 @@ def test_merged_items_tile_every_replica_of_c_once(seed):
         else:
             assert other.num_merged_items() == 0
         other.destroy()
-    eligible = cC % cA == 0 and cC % cB == 0 and all((r * K) // cC < ((r + 1) * K) // cC for r in range(cC))
+    eligible = all((r * K) // cC < ((r + 1) * K) // cC for r in range(cC))      # no replica of C with an empty share of K
     if not eligible:
         assert plan.num_merged_items() == 0
     if plan.num_merged_items():
