@@ -271,9 +271,11 @@ int dmm_plan_table_reused(const dmm_plan_t *p);
  * DMM_SEPARATE_REDUCE). */
 int dmm_plan_ran_fused(const dmm_plan_t *p);
 
-/* Device time of the two kernels of the last dmm_execute(..., DMM_TIMING, ...) on this
- * plan, in milliseconds, excluding the work-table upload.  Blocks until those kernels
- * have finished.  A kernel that was not timed (or did not run) reports -1.  Either
+/* Device time of the kernels of the last dmm_execute(..., DMM_TIMING, ...) on this plan, in
+ * milliseconds, excluding the work-table upload: gemm_ms from in front of the first GEMM launch
+ * to behind the last (one launch, two with a fused replica sum that needs two, plus the pass
+ * that adds up macro-tiles cut along K), reduce_ms the replica-sum kernel.  Blocks until those
+ * kernels have finished.  A kernel that was not timed (or did not run) reports -1.  Either
  * output pointer may be null.  (Measurement aid for the roofline figures: Section 5.2
  * reports the best of repeated runs.) */
 int dmm_plan_elapsed_ms(dmm_plan_t *p, float *gemm_ms, float *reduce_ms);
