@@ -8,10 +8,10 @@
 One step = one pass of the whole path over one batch of synthetic input already
 resident in HBM: ``dmm_plan`` on the descriptors (host slicing + grouping), then
 ``dmm_execute`` (work-table upload and the grouped-GEMM launches; when C is
-replicated, the replica sum rides in the epilogue of replica 0's macro-tiles,
-which run in a second launch behind those of the other replicas).  W untimed
-steps, then exactly K timed steps between two device synchronisations; one JSON
-line on stdout.
+replicated, the replica sum rides in the epilogue of replica 0's macro-tiles).
+60 ms of the same steps untimed to bring the device out of its idle state
+(SETTLE_MS below), W untimed warm-up steps, then exactly K timed steps between
+two device synchronisations; one JSON line on stdout.
 
 The line also carries
   roofline      the grouped-GEMM kernel against the dense bf16 (or fp32) MFMA
@@ -59,6 +59,23 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+SETTLE_MS = 60.0     # untimed load in front of the warm-up steps: after an idle spell the device runs its first
+                     # 25 ms or so of matrix work up to a third slower than it then settles to (measured per step:
+                     # 0.92, 1.05, 1.19, 1.19, 1.12, 1.05 ... 0.90 ms at step 20, 0.87 from step 30 on, flat to step
+                     # 600), so a handful of warm-up steps alone would leave that transient in the timed region
+
+
+def settle(one_step, sync, min_ms=SETTLE_MS, min_steps=5):
+    """Untimed steps until the device has been under load for `min_ms`; returns how many."""
+    n = 0
+    t0 = time.perf_counter()
+    while n < min_steps or (time.perf_counter() - t0) * 1e3 < min_ms:
+        one_step()
+        n += 1
+        if n % 8 == 0:
+            sync()            # (so that wall time is device time: the steps are issued asynchronously)
+    sync()
+    return n
 
 
 def parity_sample(prob, cfg, A, B, np, omatmul):
@@ -96,6 +113,7 @@ def short_run(name, ld_multiple, np, torch, workloads, binding, DeviceProblem, o
             inflight.append(one(0))
             if len(inflight) > 3:
                 inflight.pop(0).destroy()
+    settle(lambda: run(1), torch.cuda.synchronize)
     run(5)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -273,6 +291,7 @@ def main() -> int:
     # milliseconds here (it walks torch's objects) and would show up as a GPU idle gap of that length.
     gc.collect()
     gc.disable()
+    settle_steps = settle(lambda: step(False, timed=False), torch.cuda.synchronize)
     for _ in range(args.warmup):
         step(False)
     while inflight:
@@ -409,7 +428,8 @@ def main() -> int:
                    "ran_merged": ran_merged, "merge": args.merge, "ld_multiple": args.ld_multiple, "c_dtype": args.c_dtype,
                    "step": "dmm_plan + dmm_execute (grouped GEMM" + (" with the replica sum in its epilogue)" if fused_ran
                                                                    else " + replica sum)" if c_rep > 1 else ")"),
-                   "kernel_event_steps_after_the_timed_region": KERNEL_STEPS, "plan_host_us": round(plan_us, 1),
+                   "kernel_event_steps_after_the_timed_region": KERNEL_STEPS,
+                   "settle": f"{settle_steps} untimed steps ({SETTLE_MS:.0f} ms of load) in front of the warm-up steps", "plan_host_us": round(plan_us, 1),
                    "plan_with_op_list_host_us": round(list_us, 1),
                    "execute_only_ms_per_step": round(exec_only_ms, 4),
                    "execute_only_tflops": round(workloads.flops(cfg) / (exec_only_ms * 1e-3) / 1e12, 2),

@@ -688,10 +688,11 @@ int build_group_exec(dmm_plan_t *P, const ExecArgs &x, hipStream_t stream, ExecL
   // Fused replica sum: the macro-tiles of replicas 1, 2, ... go first, those of replica 0 behind
   // them, and these add the others' partial sums to their own before they store.  No replica-sum
   // kernel runs.  (Not together with the K-split, whose runs store through a scratch buffer.)
-  // One launch where every macro-tile of replica 0 finds the partial sums of its region written
-  // by its own workgroup earlier in the same launch (workgroup w walks items w, w + grid, ... in
-  // order, and a wave reads back exactly the elements it stored itself); otherwise two launches,
-  // replica 0's second (stream order: every partial sum is complete by then).
+  // One launch where the list can be laid out so that every macro-tile of replica 0 finds the
+  // partial sums of its region written by its own workgroup earlier in the same launch (workgroup
+  // w walks items w, w + grid, ... in order, and a wave reads back exactly the elements it stored
+  // itself); otherwise two launches, replica 0's second (stream order: every partial sum is
+  // complete by then).
   const bool fuse = !(flags & (DMM_SEPARATE_REDUCE | DMM_NO_REDUCE)) && P->C.c > 1 && n_runs == 0;
   std::vector<RedSrc> reds;
   size_t n_first = hi.size();               // items of the first launch
@@ -722,27 +723,60 @@ int build_group_exec(dmm_plan_t *P, const ExecArgs &x, hipStream_t stream, ExecL
       origin.push_back(d);
     }
     n_first = others.size();
-    // One launch?  Replica r's k-th macro-tile has to cover the region of replica 0's k-th, and sit
-    // a multiple of the grid in front of it in the combined list.
+    // One launch?  Every replica has to have as many macro-tiles as replica 0, the k-th of each
+    // covering the region of replica 0's k-th, and that number has to be a whole number of rounds
+    // of the grid: then the list can be laid out so that workgroup w (which walks positions w,
+    // w + grid, ...) meets the partial sums of a region before it meets replica 0's macro-tile of it.
     const size_t grid = std::min<size_t>(n_plan_items, (size_t)cus);
-    one_launch = grid > 0 && !origin.empty();
-    std::vector<uint32_t> pos(n_plan_items, 0);                    // position in `others` of a plan item
-    {
-      uint32_t at = 0;
-      for (size_t i = 0; i < n_plan_items; ++i)
-        if (P->items[i].c_rep != 0) pos[i] = at++;
-    }
+    const size_t n0 = of_rep[0].size();
+    one_launch = grid > 0 && n0 > 0 && n0 % grid == 0;
     for (int32_t r = 1; r < P->C.c && one_launch; ++r) {
-      if (of_rep[(size_t)r].size() != of_rep[0].size()) one_launch = false;
-      for (size_t k = 0; k < of_rep[0].size() && one_launch; ++k) {
+      if (of_rep[(size_t)r].size() != n0) one_launch = false;
+      for (size_t k = 0; k < n0 && one_launch; ++k) {
         const dmm_work_item &o = P->items[of_rep[0][k]], &s = P->items[of_rep[(size_t)r][k]];
-        if (o.c_ti != s.c_ti || o.c_tj != s.c_tj || o.m0 != s.m0 || o.n0 != s.n0 || o.m_ext != s.m_ext ||
-            o.n_ext != s.n_ext || (n_first + k - pos[of_rep[(size_t)r][k]]) % grid != 0)
+        if (o.c_ti != s.c_ti || o.c_tj != s.c_tj || o.m0 != s.m0 || o.n0 != s.n0 || o.m_ext != s.m_ext || o.n_ext != s.n_ext)
           one_launch = false;
       }
     }
-    hi = std::move(others);
-    hi.insert(hi.end(), origin.begin(), origin.end());
+    if (one_launch) {
+      // Chunk j = macro-tiles j grid .. (j + 1) grid - 1 of every replica (a round of the planner's
+      // order: the 32 workgroups of an XCD on one block of neighbouring tiles).  Per workgroup and
+      // chunk: `o` = the other replicas' macro-tiles, `s` = replica 0's, which adds their partial
+      // sums.  All workgroups in step would read their partial sums at the same moments, at the
+      // memory's pace with the matrix pipes idle; so the XCDs alternate between two schedules,
+      //   o0 s0 o1 s1 o2 s2 ...      and      o0 o1 s0 o2 s1 ... s(last),
+      // whose `s` fall into different rounds except the last (cfg4, four chunks: 2 % off the step
+      // against o0 o1 o2 o3 s0 s1 s2 s3 everywhere; the first schedule everywhere: 1 % on).
+      const size_t Q = n0 / grid;
+      std::vector<ItemDev> laid(hi.size());
+      std::vector<std::pair<bool, size_t>> seq;                      // (is s, chunk)
+      for (size_t w = 0; w < grid; ++w) {
+        seq.clear();
+        if (((w % 8) & 1) == 0 || Q < 2) {
+          for (size_t j = 0; j < Q; ++j) {
+            seq.push_back({false, j});
+            seq.push_back({true, j});
+          }
+        } else {
+          seq.push_back({false, 0});
+          for (size_t j = 0; j < Q; ++j) {
+            if (j + 1 < Q) seq.push_back({false, j + 1});
+            seq.push_back({true, j});
+          }
+        }
+        size_t t = 0;
+        for (const auto &e : seq) {
+          const size_t k = e.second * grid + w;
+          if (e.first) laid[(t++) * grid + w] = origin[k];
+          else
+            for (int32_t r = 1; r < P->C.c; ++r) laid[(t++) * grid + w] = hi[of_rep[(size_t)r][k]];
+        }
+      }
+      hi = std::move(laid);
+    } else {
+      hi = std::move(others);
+      hi.insert(hi.end(), origin.begin(), origin.end());
+    }
   }
   const size_t n_items = hi.size();
   const size_t o_segs = n_items * sizeof(ItemDev);

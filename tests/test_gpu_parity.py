@@ -896,13 +896,16 @@ def test_fused_replica_sum_families(name, dims, ldm):
     _check(C0, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
 
 
-def test_fused_replica_sum_in_one_launch():
-    """Where replica 1's k-th macro-tile sits a whole number of rounds in front of replica 0's k-th in the
-    work list, one launch does both: the workgroup that stored a partial sum reads it back itself.
-    (2.5D on 4096 x 4096: 256 macro-tiles per replica, one round of a 256-CU device each.)"""
+@pytest.mark.parametrize("dims", [(4096, 512, 4096), (8192, 256, 8192)])
+def test_fused_replica_sum_in_one_launch(dims):
+    """Where every replica has the same macro-tiles, a whole number of rounds of them, one launch
+    does everything: the work list is laid out so that the workgroup that stored a partial sum is
+    the one that reads it back.  (2.5D on 4096 x 4096: 256 macro-tiles per replica, one round of a
+    256-CU device each; on 8192 x 8192 four rounds each, where the XCDs alternate between two
+    orders of their macro-tiles.)"""
     if torch.cuda.get_device_properties(0).multi_processor_count != 256:
-        pytest.skip("the work list is laid out for one round per replica on 256 compute units")
-    cfg = workloads.scaled_config("cfg4", 4096, 512, 4096)
+        pytest.skip("the work list is laid out for whole rounds per replica on 256 compute units")
+    cfg = workloads.scaled_config("cfg4", *dims)
     A, B = workloads.make_operands(cfg)
     C0 = _fused_against_plain(cfg, A, B, launches=1)
     _check(C0, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
