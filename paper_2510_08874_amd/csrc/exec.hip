@@ -228,7 +228,11 @@ int fire_reduce(dmm_plan_t *P, const RedLaunch &L, hipStream_t stream, bool time
 //   CompItemDev[items] | PieceDev a[...] | PieceDev b[...] | PieceDev c[...] | int32 klen[...]
 // A slices are numbered (replica, row interval, segment), B slices (replica, segment, column
 // interval), C slices (replica, row interval, column interval).
-constexpr int32_t MIN_RUN = 64;   // K steps a run of a macro-tile cut along K has at least (see dmm_execute)
+// K steps a run of a macro-tile cut along K has at least (see build_group_exec): 64 with bf16
+// operands, measured; a K step of fp32 operands keeps the matrix pipes busy eight times as long
+// (128 MFMAs of 64 cycles against 32 of 32), so there a run of the same duration is 8 steps.
+constexpr int32_t MIN_RUN = 64;
+inline int32_t min_run_steps(int64_t es) { return es == 4 ? MIN_RUN / 8 : MIN_RUN; }
 
 // Scratch buffer of the plan for `n_runs` partial tiles; orders this call behind the plan's last one.
 int acquire_split_buffer(dmm_plan_t *P, size_t n_runs, hipStream_t stream) {
@@ -341,7 +345,7 @@ int build_merged_tables(dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, con
     items[x] = d;
   }
   // K-split of the last round, as for the per-group macro-tiles: the last W % cus macro-tiles, if
-  // they are at most half a round, are cut into runs of at least MIN_RUN K steps; every run writes
+  // they are at most half a round, are cut into runs of at least min_run_steps() K steps; every run writes
   // a plain partial tile to the scratch buffer, and the partial tiles of a macro-tile are added up
   // piece by piece (one FixItem per row piece and column piece, each with its own C slice).
   std::vector<FixItem> fixes;
@@ -372,7 +376,7 @@ int build_merged_tables(dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, con
   // the descriptors of all of a macro-tile's segments would not fit beside eight pieces per axis),
   // (b) the macro-tiles fill the device badly: at most half a round of them in all, or a last round
   // that is at most half full (then its macro-tiles only), as for the per-group macro-tiles.  A run
-  // is a range of at least MIN_RUN K steps; its workgroup stages the descriptors of the segments
+  // is a range of at least min_run_steps() K steps; its workgroup stages the descriptors of the segments
   // the range touches only, starts `first_step` steps into the first of them and writes a plain
   // partial tile.  Launch order: the first run of every macro-tile in the macro-tiles' own order,
   // then the second of every one, ...
@@ -396,7 +400,7 @@ int build_merged_tables(dmm_plan_t *P, int64_t es, int64_t bk, int64_t c_es, con
     const CompItemDev whole = items[x];
     const std::vector<int32_t> &before = steps_before[(size_t)G.items[x].rep];
     const int32_t least = G.window > 0 && whole.S > G.window ? (whole.S + G.window - 1) / G.window : 1;
-    int32_t runs = std::max(least, std::min(want[x], whole.nsteps / MIN_RUN));
+    int32_t runs = std::max(least, std::min(want[x], whole.nsteps / min_run_steps(es)));
     if (runs < 2) continue;
     // ranges of `per` steps; more runs if some range touches more segments than fit
     int32_t per = 0;
@@ -632,10 +636,11 @@ int build_group_exec(dmm_plan_t *P, const ExecArgs &x, hipStream_t stream, ExecL
   }
   // K-split of the last round (see sum_parts_kernel): with W working items on `cus` CUs the
   // last W % cus of them run alone; if they are few, each is cut into up to cus / (W % cus) runs
-  // of at least MIN_RUN K steps.  Run 0 takes the item's place in the launch order, the others
+  // of at least min_run_steps() K steps.  Run 0 takes the item's place in the launch order, the others
   // go to the end; all of them write to the scratch buffer.  A run pays a prologue and an
   // epilogue of its own (about 13 K steps' worth) and the pass that adds the runs up is one more
-  // launch: measured, runs of 32 steps lose (2048^3: 45 -> 66 us), so a run is 64 steps at least.
+  // launch: measured with bf16 operands, runs of 32 steps lose (2048^3: 45 -> 66 us), so a run is
+  // 64 steps at least (8 of fp32 operands, the same duration).
   int cus = 0;
   if ((rc = device_cus(&cus))) return rc;
   size_t working = 0;
@@ -648,7 +653,7 @@ int build_group_exec(dmm_plan_t *P, const ExecArgs &x, hipStream_t stream, ExecL
     for (size_t i = n_plan_items; i-- > 0 && seen < tail;) {
       if (hi[i].nsteps <= 0) continue;
       ++seen;
-      int32_t runs = std::min(max_runs, hi[i].nsteps / MIN_RUN);
+      int32_t runs = std::min(max_runs, hi[i].nsteps / min_run_steps(es));
       if (runs < 2) continue;
       const int32_t per = (hi[i].nsteps + runs - 1) / runs;
       runs = (hi[i].nsteps + per - 1) / per;
