@@ -1174,39 +1174,50 @@ __device__ __forceinline__ void store_macro_tile(const ItemDev &it, const RedSrc
   // accumulator file, so that this phase has nothing but loads in flight: with loads and stores
   // mixed, the one counter that tracks both says nothing about which of them has returned, and
   // every batch of loads would have to wait for the whole queue to drain.  Eight rows of a 32 x 32
-  // tile per batch (32 values per lane), DEPTH batches in flight.
+  // tile per batch (32 values per lane), three batches in flight.
   auto add_partials = [&](auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr int RB = 8;                                  // accumulator registers (rows) per batch
-    constexpr int NB = FM * (16 / RB);                     // batches per macro-tile
-    constexpr int DEPTH = 3;
-    for (int q = 0; q < it.red_count; ++q) {
-      const RedSrc src = red[it.red_first + q];
+    constexpr int NB = FM * (16 / RB);                     // batches per macro-tile and source
+    constexpr int DEPTH = 4;                               // ring of batches: DEPTH - 1 in flight
+    static_assert(NB % DEPTH == 0 && NB >= DEPTH, "a batch's place in the ring must not depend on the source");
+    float v[DEPTH][RB][FN];
+    // the loads of batch b of the partial sum `src` (the macro-tile's region of another replica)
+    auto issue = [&](auto bc, const RedSrc &src) {
+      constexpr int b = decltype(bc)::value, i = b / (16 / RB), rb = (b % (16 / RB)) * RB, slot = b % DEPTH;
       const __attribute__((address_space(1))) char *pbytes = (const __attribute__((address_space(1))) char *)src.p;
       const unsigned ppitch = (unsigned)src.ld * 4u;
       const unsigned poff = (unsigned)row0 * ppitch + (unsigned)col0 * 4u;
-      float v[DEPTH][RB][FN];
-      auto issue = [&](auto bc) {
-        constexpr int b = decltype(bc)::value, i = b / (16 / RB), rb = (b % (16 / RB)) * RB, slot = b % DEPTH;
-        static_for<RB * FN>([&](auto yc) {
-          constexpr int r = decltype(yc)::value / FN, j = decltype(yc)::value % FN;
-          constexpr int dr = i * 32 + 8 * ((rb + r) >> 2) + ((rb + r) & 3);
-          v[slot][r][j] = 0.f;
-          if (FULL || (row0 + dr < it.m_ext && col0 + j * 32 < it.n_ext))
-            v[slot][r][j] = __builtin_nontemporal_load(
-                (const __attribute__((address_space(1))) float *)(pbytes + (poff + (unsigned)dr * ppitch) + j * 128));
-        });
-      };
-      static_for<DEPTH - 1>([&](auto bc) { issue(bc); });
+      static_for<RB * FN>([&](auto yc) {
+        constexpr int r = decltype(yc)::value / FN, j = decltype(yc)::value % FN;
+        constexpr int dr = i * 32 + 8 * ((rb + r) >> 2) + ((rb + r) & 3);
+        v[slot][r][j] = 0.f;
+        if (FULL || (row0 + dr < it.m_ext && col0 + j * 32 < it.n_ext))
+          v[slot][r][j] = __builtin_nontemporal_load(
+              (const __attribute__((address_space(1))) float *)(pbytes + (poff + (unsigned)dr * ppitch) + j * 128));
+      });
+    };
+    // ((own + p_1) + p_2) ...: one pass over the macro-tile per source, the sources' passes back to
+    // back in one stream of batches (the last batches of a pass already load the next source's first)
+    RedSrc src = red[it.red_first];
+    static_for<DEPTH - 1>([&](auto bc) { issue(bc, src); });
+    for (int q = 0; q < it.red_count; ++q) {
+      const bool more = q + 1 < it.red_count;
+      const RedSrc next = more ? red[it.red_first + q + 1] : src;
       static_for<NB>([&](auto bc) {
         constexpr int b = decltype(bc)::value, i = b / (16 / RB), rb = (b % (16 / RB)) * RB, slot = b % DEPTH;
-        if constexpr (b + DEPTH - 1 < NB) issue(std::integral_constant<int, b + DEPTH - 1>{});
+        if constexpr (b + DEPTH - 1 < NB) {
+          issue(std::integral_constant<int, b + DEPTH - 1>{}, src);
+        } else {
+          if (more) issue(std::integral_constant<int, b + DEPTH - 1 - NB>{}, next);
+        }
         static_for<RB * FN>([&](auto yc) {
           constexpr int r = decltype(yc)::value / FN, j = decltype(yc)::value % FN;
           constexpr int REG = 16 * (i * FN + j) + rb + r;
           acc_write<REG>(acc_read<REG>() + v[slot][r][j]);
         });
       });
+      src = next;
     }
   };
   const bool full = it.m_ext == BM && it.n_ext == BN;
