@@ -911,6 +911,23 @@ def test_fused_replica_sum_in_one_launch(dims):
     _check(C0, omatmul.matmul(A, B, bf16=True), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
 
 
+@pytest.mark.parametrize("c,dims,dtype", [(4, (4096, 1024, 8192), "bf16"), (3, (4096, 768, 4096), "f32")])
+def test_fused_replica_sum_in_one_launch_of_several_replicas(c, dims, dtype):
+    """More than two replicas of C (2.5D with c = 4 and c = 3): replica 0's macro-tiles add c - 1
+    partial sums, ((own + p_1) + p_2) + ..., whose loads run as one stream of batches; every round of
+    the work list is c - 1 rounds of other replicas' macro-tiles and one of replica 0's."""
+    if torch.cuda.get_device_properties(0).multi_processor_count != 256:
+        pytest.skip("the work list is laid out for whole rounds per replica on 256 compute units")
+    M, K, N = dims
+    g = 2
+    cfg = dict(name=f"2.5d-c{c}-{dtype}@{M}x{K}x{N}", M=M, K=K, N=N, dtype=dtype, nranks=c * g * g,
+               A=workloads.block_desc(M, K, g, g, replication=c), B=workloads.block_desc(K, N, g, g, replication=c),
+               C=workloads.block_desc(M, N, g, g, replication=c), dist=("normal", 1.0), seeds=(81, 82))
+    A, B = workloads.make_operands(cfg)
+    C0 = _fused_against_plain(cfg, A, B, launches=1)
+    _check(C0, omatmul.matmul(A, B, bf16=(dtype == "bf16")), _to_f64(A, cfg), _to_f64(B, cfg), cfg, cfg["name"])
+
+
 @pytest.mark.parametrize("seed", [2, 3, 4, 6, 8, 13, 15, 21, 24, 27])
 @pytest.mark.parametrize("mode", ["C", "B", "A"])
 def test_fused_replica_sum_random_partitionings(seed, mode):
