@@ -248,28 +248,28 @@ int dmm_reduce_replicas_static(dmm_plan_t *p, void *const *c_tiles, const int64_
 
 /* ---- measurement and test aids (not steps of the method) ---------------------------------- */
 
-/* 1 if the last dmm_execute on this plan ran the merged macro-tiles (the plan has such a list,
- * DMM_NO_MERGE was not given and the device grants a workgroup the 160 KB of LDS their kernel
- * asks for), else 0. */
-int dmm_plan_ran_merged(const dmm_plan_t *p);
-
-/* 1 if the last dmm_execute on this plan cut macro-tiles along K (partial tiles through a scratch
- * buffer, added up in ascending k by a second kernel: the last round of workgroups would have
- * left most of the device idle, or a merged macro-tile had more K-segments than its workgroup
- * can hold descriptors for), else 0.  Such a run sums in another order than an uncut one. */
-int dmm_plan_ran_k_split(const dmm_plan_t *p);
-
-/* 1 if the last dmm_execute on this plan found the work tables of the call before it in place
- * and launched from them (same element type, same flags apart from DMM_TIMING, same device, same
- * contents of all six pointer and leading-dimension tables), 0 if it assembled and uploaded
- * them.  The tables hold addresses, not data: what the tiles contain plays no part. */
-int dmm_plan_table_reused(const dmm_plan_t *p);
-
-/* How the last dmm_execute on this plan summed the replicas of C: 0 = not in the GEMM (one
- * replica, DMM_NO_REDUCE, DMM_SEPARATE_REDUCE, or the fused form did not apply), 1 = in the GEMM,
- * one launch, 2 = in the GEMM, replica 0's macro-tiles in a second launch (see
- * DMM_SEPARATE_REDUCE). */
-int dmm_plan_ran_fused(const dmm_plan_t *p);
+/* What the last dmm_execute on a plan did.
+ *   ran_merged    1: it ran the merged macro-tiles (the plan has such a list, DMM_NO_MERGE was not
+ *                 given and the device grants a workgroup the 160 KB of LDS their kernel asks for)
+ *   ran_k_split   1: it cut macro-tiles along K (partial tiles through a scratch buffer, added up
+ *                 in ascending k by a second kernel: the last round of workgroups would have left
+ *                 most of the device idle, or a merged macro-tile had more K-segments than its
+ *                 workgroup can hold descriptors for).  Such a run sums in another order than an
+ *                 uncut one
+ *   ran_fused     how it summed the replicas of C: 0 = not in the GEMM (one replica,
+ *                 DMM_NO_REDUCE, DMM_SEPARATE_REDUCE, or the fused form did not apply), 1 = in the
+ *                 GEMM, one launch, 2 = in the GEMM, replica 0's macro-tiles in a second launch
+ *                 (see DMM_SEPARATE_REDUCE)
+ *   table_reused  1: it found the work tables of the call before it in place and launched from
+ *                 them (same element type, same flags apart from DMM_TIMING, same device, same
+ *                 contents of all six pointer and leading-dimension tables); 0: it assembled and
+ *                 uploaded them.  The tables hold addresses, not data: what the tiles contain
+ *                 plays no part
+ * All zero for a plan that has not been executed, and for a null plan.  DMM_EINVAL if out is null. */
+typedef struct {
+  int32_t ran_merged, ran_k_split, ran_fused, table_reused;
+} dmm_execute_report;
+int dmm_plan_last_execute(const dmm_plan_t *p, dmm_execute_report *out);
 
 /* Device time of the kernels of the last dmm_execute(..., DMM_TIMING, ...) on this plan, in
  * milliseconds, excluding the work-table upload: gemm_ms from in front of the first GEMM launch
@@ -307,8 +307,9 @@ void dmm_plan_destroy(dmm_plan_t *p);
 const char *dmm_strerror(int status);
 int dmm_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread, 0 if none */
 int dmm_version(void);         /* 4: the replica sum is fused into the GEMM unless DMM_SEPARATE_REDUCE asks
-                                  for the kernel of its own (3: flag values of dmm_plan and dmm_execute disjoint,
-                                  dmm_reduce_replicas_static, dmm_plan_ran_k_split) */
+                                  for the kernel of its own; dmm_plan_last_execute replaces the
+                                  dmm_plan_ran_* accessors (3: flag values of dmm_plan and dmm_execute disjoint,
+                                  dmm_reduce_replicas_static) */
 
 #ifdef __cplusplus
 }

@@ -63,6 +63,10 @@ class dmm_merged_item(C.Structure):
                 ("reserved", C.c_int32)]
 
 
+class dmm_execute_report(C.Structure):
+    _fields_ = [("ran_merged", C.c_int32), ("ran_k_split", C.c_int32), ("ran_fused", C.c_int32), ("table_reused", C.c_int32)]
+
+
 class DmmError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -105,14 +109,8 @@ def lib() -> C.CDLL:
         L.dmm_plan_num_merged_items.argtypes = [P]
         L.dmm_plan_merged_items.restype = C.POINTER(dmm_merged_item)
         L.dmm_plan_merged_items.argtypes = [P]
-        L.dmm_plan_ran_merged.restype = C.c_int
-        L.dmm_plan_ran_merged.argtypes = [P]
-        L.dmm_plan_table_reused.restype = C.c_int
-        L.dmm_plan_table_reused.argtypes = [P]
-        L.dmm_plan_ran_fused.restype = C.c_int
-        L.dmm_plan_ran_fused.argtypes = [P]
-        L.dmm_plan_ran_k_split.restype = C.c_int
-        L.dmm_plan_ran_k_split.argtypes = [P]
+        L.dmm_plan_last_execute.restype = C.c_int
+        L.dmm_plan_last_execute.argtypes = [P, C.POINTER(dmm_execute_report)]
         L.dmm_plan_macro_tile.restype = C.c_int32
         L.dmm_plan_macro_tile.argtypes = [P]
         L.dmm_execute.restype = C.c_int
@@ -141,7 +139,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("dmm_plan", "dmm_plan_num_tasks", "dmm_plan_tasks", "dmm_plan_order", "dmm_plan_num_groups",
            "dmm_plan_group_offsets", "dmm_plan_num_items", "dmm_plan_items", "dmm_plan_macro_tile",
-           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_ran_merged", "dmm_plan_ran_k_split", "dmm_plan_ran_fused", "dmm_plan_table_reused",
+           "dmm_plan_num_merged_items", "dmm_plan_merged_items", "dmm_plan_last_execute",
            "dmm_reduce_replicas_static",
            "dmm_execute", "dmm_reduce_replicas", "dmm_broadcast_replica", "dmm_plan_elapsed_ms", "dmm_plan_gemm_launch_ms", "dmm_plan_destroy", "dmm_strerror",
            "dmm_last_hip_error", "dmm_version", "dmm_measure_mfma_rate")
@@ -223,19 +221,27 @@ class Plan:
         return [{f: int(getattr(p[i], f)) for f, _ in dmm_merged_item._fields_ if f != "reserved"}
                 for i in range(self.num_merged_items())]
 
+    def last_execute(self) -> "dmm_execute_report":
+        """What the last execute on this plan did (dmm_plan_last_execute)."""
+        rep = dmm_execute_report()
+        rc = lib().dmm_plan_last_execute(self._h, C.byref(rep))
+        if rc != DMM_OK:
+            raise DmmError(rc, "dmm_plan_last_execute")
+        return rep
+
     def ran_merged(self) -> bool:
-        return bool(lib().dmm_plan_ran_merged(self._h))
+        return bool(self.last_execute().ran_merged)
 
     def table_reused(self) -> bool:
         """The last execute launched from the work tables the call before it had left on the device."""
-        return bool(lib().dmm_plan_table_reused(self._h))
+        return bool(self.last_execute().table_reused)
 
     def ran_fused(self) -> int:
         """0: the last execute did not sum C's replicas in the GEMM; 1: it did, in one launch; 2: in two."""
-        return int(lib().dmm_plan_ran_fused(self._h))
+        return int(self.last_execute().ran_fused)
 
     def ran_k_split(self) -> bool:
-        return bool(lib().dmm_plan_ran_k_split(self._h))
+        return bool(self.last_execute().ran_k_split)
 
     def macro_tile(self) -> int:
         return int(lib().dmm_plan_macro_tile(self._h))

@@ -972,8 +972,6 @@ int dmm_execute(dmm_plan_t *P, int dtype, const void *const *a_tiles, const int6
   }
 }
 
-int dmm_plan_table_reused(const dmm_plan_t *P) { return P && P->dev && P->dev->table_reused ? 1 : 0; }
-
 int dmm_plan_gemm_launch_ms(dmm_plan_t *P, float ms[2], double flops[2]) {
   using namespace dmm;
   if (!P || !ms || !flops) return DMM_EINVAL;
@@ -988,11 +986,16 @@ int dmm_plan_gemm_launch_ms(dmm_plan_t *P, float ms[2], double flops[2]) {
   return DMM_OK;
 }
 
-int dmm_plan_ran_fused(const dmm_plan_t *P) { return P && P->dev ? P->dev->ran_fused : 0; }
-
-int dmm_plan_ran_k_split(const dmm_plan_t *P) { return P && P->dev && P->dev->ran_k_split ? 1 : 0; }
-
-int dmm_plan_ran_merged(const dmm_plan_t *P) { return P && P->dev && P->dev->ran_merged ? 1 : 0; }
+int dmm_plan_last_execute(const dmm_plan_t *P, dmm_execute_report *out) {
+  if (!out) return DMM_EINVAL;
+  *out = dmm_execute_report{0, 0, 0, 0};
+  if (!P || !P->dev) return DMM_OK;
+  out->ran_merged = P->dev->ran_merged ? 1 : 0;
+  out->ran_k_split = P->dev->ran_k_split ? 1 : 0;
+  out->ran_fused = P->dev->ran_fused;
+  out->table_reused = P->dev->table_reused ? 1 : 0;
+  return DMM_OK;
+}
 
 int dmm_plan_elapsed_ms(dmm_plan_t *P, float *gemm_ms, float *reduce_ms) {
   using namespace dmm;

@@ -176,9 +176,10 @@ def test_null_arguments_rejected():
     assert L.dmm_execute(None, 1, None, None, None, None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_reduce_replicas(None, None, None, 0, None) == binding.DMM_EINVAL
     assert L.dmm_reduce_replicas_static(None, None, None, 0, None) == binding.DMM_EINVAL
-    assert L.dmm_plan_ran_k_split(None) == 0
-    assert L.dmm_plan_ran_fused(None) == 0
-    assert L.dmm_plan_table_reused(None) == 0
+    assert L.dmm_plan_last_execute(None, None) == binding.DMM_EINVAL
+    rep = binding.dmm_execute_report(7, 7, 7, 7)
+    assert L.dmm_plan_last_execute(None, rep) == binding.DMM_OK
+    assert (rep.ran_merged, rep.ran_k_split, rep.ran_fused, rep.table_reused) == (0, 0, 0, 0)
     assert L.dmm_plan_gemm_launch_ms(None, None, None) == binding.DMM_EINVAL
     ok = dict(rows=8, cols=8, row_cuts=(0, 8), col_cuts=(0, 8), proc_rows=1, proc_cols=1, replication=1)
     fresh = binding.Plan(ok, ok, ok, 1)
