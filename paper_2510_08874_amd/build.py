@@ -95,6 +95,27 @@ def check_wait_states(asm_path: str) -> None:
         raise RuntimeError("missing wait states in front of inline assembly (%d places), first:\n%s" % (len(bad), "\n".join(bad[:4])))
 
 
+def check_m0_private(asm_path: str) -> None:
+    """The kernels' assembly statements overwrite M0 (the LDS address of a direct-to-LDS load)
+    without the compiler knowing: it refuses M0 in a clobber list.  That is sound as long as the
+    compiler has no use for M0 of its own: fail the build where an instruction
+    outside the assembly statements names m0 or uses relative register addressing (which goes
+    through M0)."""
+    inside = False
+    with open(asm_path) as f:
+        for ln, line in enumerate(f, 1):
+            t = line.strip()
+            if t.startswith(";;#ASMSTART"):
+                inside = True
+                continue
+            if t.startswith(";;#ASMEND"):
+                inside = False
+                continue
+            t = t.split(";")[0].strip()
+            if not inside and t and not t.startswith(".") and re.search(r"\bm0\b|s_set_gpr_idx|movrel", t):
+                raise RuntimeError(f"{asm_path}:{ln}: `{t}`: the compiler uses M0, which the assembly statements overwrite")
+
+
 def _device_asm(name: str) -> str:
     for f in os.listdir(os.path.join(OUT, name)):
         if "-hip-amdgcn" in f and f.endswith(".s"):
@@ -130,6 +151,7 @@ def build(verbose: bool = False, extra=()) -> str:
         if src.endswith(".hip"):
             check_resources(err, want_kernel=src == "gemm_instance.hip" and name[-1] in "0123")
             check_wait_states(_device_asm(name))
+            check_m0_private(_device_asm(name))
 
     try:
         while todo or running:

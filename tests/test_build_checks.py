@@ -77,6 +77,17 @@ def test_missing_wait_states_fail_the_build(tmp_path, text, line):
     assert f"unit.s:{line}:" in str(e.value)
 
 
+def test_compiler_use_of_m0_fails_the_build(tmp_path):
+    ok = tmp_path / "ok.s"
+    ok.write_text("\t;;#ASMSTART\n\ts_mov_b32 m0, s5\n\tglobal_load_lds_dwordx4 v3, s[2:3]\n\t;;#ASMEND\n\tv_add_u32_e32 v5, s18, v5\n")
+    build.check_m0_private(str(ok))
+    for text in ("\ts_mov_b32 m0, s7\n", "\ts_set_gpr_idx_on s3, gpr_idx(SRC0)\n", "\tv_movrels_b32_e32 v1, v0\n"):
+        bad = tmp_path / "bad.s"
+        bad.write_text("\t;;#ASMSTART\n\ts_mov_b32 m0, s5\n\t;;#ASMEND\n" + text)
+        with pytest.raises(RuntimeError):
+            build.check_m0_private(str(bad))
+
+
 def test_resource_check_rejects_scratch_and_lost_accumulators():
     ok = ("remark: k.hpp:1:0: Function Name: _ZN3dmm19grouped_gemm_kernelILi2ELb0EEEv [-Rpass]\n"
           "remark: k.hpp:1:0:     VGPRs: 152 [-Rpass]\nremark: k.hpp:1:0:     AGPRs: 256 [-Rpass]\n"
