@@ -26,7 +26,8 @@ The line also carries
                 its FLOPs against the MFMA peak and the bytes of the sum it also moves;
   per_config    (default workload only) the other configurations, a short run each:
                 plan + execute rate, kernel rate and fraction of the MFMA peak of the
-                configuration's element type, parity of a sample of rows;
+                configuration's element type, parity of a sample of rows (cfg1, cfg2, cfg3,
+                cfg5 packed and with ld padded to 8, and cfg4 with fp32 operands);
   separate_replica_sum   (replicated C) the same plan + execute steps with
                 DMM_SEPARATE_REDUCE: one GEMM launch over all macro-tiles, then the
                 replica-sum kernel; reported beside `value`, never as it, with
@@ -92,10 +93,12 @@ def parity_sample(prob, cfg, A, B, np, omatmul):
             "tolerance": 2e-3 if cfg["dtype"] == "bf16" else 1e-5}
 
 
-def short_run(name, ld_multiple, np, torch, workloads, binding, DeviceProblem, omatmul, steps=12, kernel_steps=12):
+def short_run(name, ld_multiple, np, torch, workloads, binding, DeviceProblem, omatmul, steps=12, kernel_steps=12, dtype=None):
     """One of the other configurations: `steps` plan + execute steps between two synchronisations,
     then `kernel_steps` more with events around the kernels, then the parity sample."""
     cfg = workloads.config(name)
+    if dtype and dtype != cfg["dtype"]:
+        cfg = dict(cfg, dtype=dtype, name=f"{cfg['name']}/{dtype}")
     A, B = workloads.make_operands(cfg)
     prob = DeviceProblem(cfg, A, B, ld_multiple=ld_multiple)
     stream = torch.cuda.current_stream().cuda_stream
@@ -484,6 +487,7 @@ def main() -> int:
         per = {}
         for name, ldm in (("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg5", 1), ("cfg5", 8)):
             per[name if ldm == 1 else f"{name}/ld{ldm}"] = short_run(name, ldm, np, torch, workloads, binding, DeviceProblem, omatmul)
+        per["cfg4/f32"] = short_run("cfg4", 1, np, torch, workloads, binding, DeviceProblem, omatmul, dtype="f32")
         per["cfg4"] = {"see": "the top level of this line (value, roofline, parity)"}
         out["per_config"] = per
 
